@@ -1,0 +1,208 @@
+"""ctypes access to the plain CPU oracle (``irm_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the CPU-baseline leg
+of the benchmark are the only callers.  This module does argument marshalling
+and nothing else; every step of the method is in the C file.  It imports
+nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "irm_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+ROW_DIM = 576
+CKV_DIM = 512
+KR_DIM = 64
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C99, -O2, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c99", "-O2", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        L.oracle_cdc_chunk.restype = ctypes.c_int64
+        L.oracle_fnv1a64_bytes.restype = ctypes.c_uint64
+        L.oracle_fnv1a64_bytes.argtypes = [ctypes.c_char_p, ctypes.c_uint64]
+        L.oracle_lookup.restype = ctypes.c_int
+        L.oracle_reattach.restype = ctypes.c_int
+        L.oracle_bf16_to_f64.restype = ctypes.c_double
+        L.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
+        L.oracle_f64_to_bf16.restype = ctypes.c_uint16
+        L.oracle_f64_to_bf16.argtypes = [ctypes.c_double]
+        _lib = L
+    return _lib
+
+
+def _arr(x, dtype):
+    return np.ascontiguousarray(x, dtype=dtype)
+
+
+def cdc_chunk(tokens, req_offsets, gear, mask, min_chunk, max_chunk):
+    """-> (chunk_start u32[C], chunk_len u32[C], req_chunk_offsets u32[R+1])."""
+    tokens = _arr(tokens, np.int32)
+    req_offsets = _arr(req_offsets, np.uint32)
+    gear = _arr(gear, np.uint32)
+    assert gear.shape == (256,)
+    n_req = len(req_offsets) - 1
+    n_tok = int(req_offsets[-1]) if n_req >= 0 and len(req_offsets) else 0
+    assert n_tok <= len(tokens)
+    cap = n_tok + n_req + 1
+    start = np.zeros(cap, np.uint32)
+    length = np.zeros(cap, np.uint32)
+    rco = np.zeros(n_req + 1, np.uint32)
+    n = lib().oracle_cdc_chunk(
+        _p(tokens, ctypes.c_int32), _p(req_offsets, ctypes.c_uint32), ctypes.c_uint32(n_req),
+        _p(gear, ctypes.c_uint32), ctypes.c_uint32(mask), ctypes.c_uint32(min_chunk),
+        ctypes.c_uint32(max_chunk), _p(start, ctypes.c_uint32), _p(length, ctypes.c_uint32),
+        _p(rco, ctypes.c_uint32), ctypes.c_uint64(cap))
+    if n < 0:
+        raise ValueError("oracle_cdc_chunk rejected its arguments")
+    return start[:n].copy(), length[:n].copy(), rco
+
+
+def fnv1a64_bytes(data: bytes) -> int:
+    return int(lib().oracle_fnv1a64_bytes(data, len(data)))
+
+
+def chunk_hash(tokens, chunk_start, chunk_len):
+    tokens = _arr(tokens, np.int32)
+    chunk_start = _arr(chunk_start, np.uint32)
+    chunk_len = _arr(chunk_len, np.uint32)
+    out = np.zeros(len(chunk_start), np.uint64)
+    lib().oracle_chunk_hash(_p(tokens, ctypes.c_int32), _p(chunk_start, ctypes.c_uint32),
+                            _p(chunk_len, ctypes.c_uint32), ctypes.c_uint64(len(chunk_start)),
+                            _p(out, ctypes.c_uint64))
+    return out
+
+
+@dataclass
+class Hits:
+    """Struct-of-arrays hit list, ascending chunk order."""
+    src_row: np.ndarray   # u32, first row of the cached chunk in the source pool
+    dst_tok: np.ndarray   # u32, first token of the request chunk (index into dst_slots)
+    len: np.ndarray       # u32
+    delta: np.ndarray     # i32, new position - stored position
+
+    def __len__(self):
+        return len(self.src_row)
+
+
+def lookup(reg_hash, reg_src_row, reg_p_src, reg_len, reg_entry_id, chunk_hash_, chunk_start,
+           chunk_len, req_chunk_offsets, req_offsets, pos_base, carve_out):
+    """-> (chunk_entry i32[C], Hits, hit_tokens)."""
+    reg_hash = _arr(reg_hash, np.uint64)
+    reg_src_row = _arr(reg_src_row, np.uint32)
+    reg_p_src = _arr(reg_p_src, np.int32)
+    reg_len = _arr(reg_len, np.uint32)
+    reg_entry_id = _arr(reg_entry_id, np.uint32)
+    chunk_hash_ = _arr(chunk_hash_, np.uint64)
+    chunk_start = _arr(chunk_start, np.uint32)
+    chunk_len = _arr(chunk_len, np.uint32)
+    rco = _arr(req_chunk_offsets, np.uint32)
+    req_offsets = _arr(req_offsets, np.uint32)
+    pos_base = _arr(pos_base, np.int32)
+    n_req = len(req_offsets) - 1
+    C = len(chunk_hash_)
+    entry = np.full(C, -1, np.int32)
+    h_src = np.zeros(C, np.uint32)
+    h_dst = np.zeros(C, np.uint32)
+    h_len = np.zeros(C, np.uint32)
+    h_delta = np.zeros(C, np.int32)
+    n_hits = ctypes.c_uint32(0)
+    hit_tokens = ctypes.c_uint64(0)
+    rc = lib().oracle_lookup(
+        _p(reg_hash, ctypes.c_uint64), _p(reg_src_row, ctypes.c_uint32),
+        _p(reg_p_src, ctypes.c_int32), _p(reg_len, ctypes.c_uint32),
+        _p(reg_entry_id, ctypes.c_uint32), ctypes.c_uint64(len(reg_hash)),
+        _p(chunk_hash_, ctypes.c_uint64), _p(chunk_start, ctypes.c_uint32),
+        _p(chunk_len, ctypes.c_uint32), _p(rco, ctypes.c_uint32),
+        _p(req_offsets, ctypes.c_uint32), _p(pos_base, ctypes.c_int32), ctypes.c_uint32(n_req),
+        ctypes.c_uint32(carve_out), _p(entry, ctypes.c_int32), _p(h_src, ctypes.c_uint32),
+        _p(h_dst, ctypes.c_uint32), _p(h_len, ctypes.c_uint32), _p(h_delta, ctypes.c_int32),
+        ctypes.byref(n_hits), ctypes.byref(hit_tokens))
+    if rc != 0:
+        raise MemoryError("oracle_lookup")
+    n = n_hits.value
+    return entry, Hits(h_src[:n].copy(), h_dst[:n].copy(), h_len[:n].copy(), h_delta[:n].copy()), \
+        int(hit_tokens.value)
+
+
+def bf16_to_f64(bits) -> np.ndarray:
+    """Exact widening of bf16 bit patterns (uint16) to float64."""
+    b = _arr(bits, np.uint16)
+    with np.errstate(invalid="ignore"):          # signalling NaN patterns widen to quiet NaN
+        return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16(x) -> np.ndarray:
+    """Element-wise call of the oracle's single-rounding fp64 -> bf16."""
+    x = _arr(x, np.float64)
+    f = lib().oracle_f64_to_bf16
+    return np.array([f(float(v)) for v in x.ravel()], np.uint16).reshape(x.shape)
+
+
+def rotate_kr_f64(k, delta, inv_freq) -> np.ndarray:
+    k = _arr(k, np.float64)
+    inv_freq = _arr(inv_freq, np.float32)
+    assert k.shape == (KR_DIM,) and inv_freq.shape == (KR_DIM // 2,)
+    out = np.zeros(KR_DIM, np.float64)
+    lib().oracle_rotate_kr_f64(_p(k, ctypes.c_double), ctypes.c_int64(int(delta)),
+                               _p(inv_freq, ctypes.c_float), _p(out, ctypes.c_double))
+    return out
+
+
+def reattach_row(row_bits, delta, inv_freq) -> np.ndarray:
+    row_bits = _arr(row_bits, np.uint16)
+    inv_freq = _arr(inv_freq, np.float32)
+    assert row_bits.shape == (ROW_DIM,) and inv_freq.shape == (KR_DIM // 2,)
+    out = np.zeros(ROW_DIM, np.uint16)
+    lib().oracle_reattach_row(_p(row_bits, ctypes.c_uint16), ctypes.c_int32(int(delta)),
+                              _p(inv_freq, ctypes.c_float), _p(out, ctypes.c_uint16))
+    return out
+
+
+def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq) -> None:
+    """In place on ``dst_bits``.  src_bits [L][src_rows][576] u16, dst_bits [L][dst_rows][576] u16."""
+    assert src_bits.dtype == np.uint16 and dst_bits.dtype == np.uint16
+    assert src_bits.flags.c_contiguous and dst_bits.flags.c_contiguous
+    assert src_bits.ndim == 3 and dst_bits.ndim == 3
+    assert src_bits.shape[2] == ROW_DIM and dst_bits.shape[2] == ROW_DIM
+    assert src_bits.shape[0] == dst_bits.shape[0]
+    dst_slots = _arr(dst_slots, np.int32)
+    inv_freq = _arr(inv_freq, np.float32)
+    assert inv_freq.shape == (KR_DIM // 2,)
+    hs, hd = _arr(hits.src_row, np.uint32), _arr(hits.dst_tok, np.uint32)
+    hl, hx = _arr(hits.len, np.uint32), _arr(hits.delta, np.int32)
+    if len(hs):
+        assert int((hd.astype(np.int64) + hl).max()) <= len(dst_slots)
+    rc = lib().oracle_reattach(
+        _p(src_bits, ctypes.c_uint16), ctypes.c_uint64(src_bits.shape[1]),
+        _p(dst_bits, ctypes.c_uint16), ctypes.c_uint64(dst_bits.shape[1]),
+        ctypes.c_uint32(src_bits.shape[0]), _p(dst_slots, ctypes.c_int32),
+        _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32),
+        _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
+    if rc != 0:
+        raise IndexError("oracle_reattach: a hit or slot points outside its pool")
