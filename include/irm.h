@@ -1,0 +1,210 @@
+/*
+ * irm.h -- C ABI of the cache-hit re-attachment path of an MLA-native
+ * position-independent KV cache, for AMD MI355X (gfx950).
+ *
+ * The path serves one batch of prompts (paper Alg. 1, "serve path"):
+ *
+ *   irm_cdc_chunk    cut each prompt's token ids into content-defined chunks
+ *   irm_chunk_hash   one 64-bit fingerprint per chunk
+ *   irm_lookup       probe the registry of cached chunks; list the hits with
+ *                    delta = new position - stored position
+ *   irm_reattach     for every hit and every layer, copy the position-free
+ *                    c_KV part of each cached row verbatim and write the
+ *                    RoPE part k_r rotated by delta into the request's slots
+ *
+ * Conventions
+ *   - Plain C, no C++ or framework types.  Every call returns an irm_status.
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; all others
+ *     are host pointers.  The library never frees or reallocates caller
+ *     memory.  The hot-path calls (cdc_chunk, chunk_hash, lookup, reattach)
+ *     allocate nothing, do not synchronise, and only enqueue kernels on the
+ *     caller's stream (`stream` is a hipStream_t passed as void*; NULL is the
+ *     default stream).  They record no memset nodes, so a caller may capture
+ *     them into a HIP graph.
+ *   - Host-checkable preconditions are verified before anything is launched
+ *     and reported as IRM_ERR_INVALID_ARG / IRM_ERR_CAPACITY /
+ *     IRM_ERR_UNSUPPORTED.  Conditions only the device can see (an index
+ *     outside its pool, a full table, more chunks than `chunk_capacity`) make
+ *     the kernel skip the offending item and raise a bit in the context's
+ *     device error word, read with irm_ctx_error_flags().
+ *   - Counts produced on the device (number of chunks, number of hits) stay
+ *     on the device and are consumed there by the next call: nothing between
+ *     the four calls needs the host.
+ *   - A context serialises its scratch memory: calls on the same context must
+ *     be ordered on one stream (or otherwise not overlap).
+ *
+ * KV row layout: 576 bf16 = [ c_KV: 512 | k_r: 64 ] = 1152 bytes
+ * (paper Sec. 2 "MLA", App. C).  k_r pairs are half-split: element i pairs
+ * with element i+32, i < 32.
+ */
+#ifndef IRM_H
+#define IRM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum irm_status {
+    IRM_OK = 0,
+    IRM_ERR_INVALID_ARG = 1, /* null pointer, zero size, misaligned row, min > max ...      */
+    IRM_ERR_CAPACITY = 2,    /* an argument exceeds what the context / a buffer was sized for */
+    IRM_ERR_UNSUPPORTED = 3, /* dims other than 512+64, pair mode other than half-split ...  */
+    IRM_ERR_DEVICE = 4,      /* a HIP runtime call failed (no GPU, out of memory, ...)       */
+    IRM_ERR_TABLE_FULL = 5   /* irm_table_insert found no free slot                          */
+} irm_status;
+
+/* bits of the device error word */
+#define IRM_FLAG_CHUNK_OVERFLOW 0x1u /* more chunks than chunk_capacity; extra chunks dropped   */
+#define IRM_FLAG_TABLE_FULL 0x2u     /* an insert found no free slot                             */
+#define IRM_FLAG_ROW_RANGE 0x4u      /* a hit or slot pointed outside its pool; row skipped      */
+#define IRM_FLAG_BAD_CHUNK 0x8u      /* a chunk record pointed outside the token array; skipped  */
+
+#define IRM_PAIR_HALF_SPLIT 0u
+#define IRM_KR_PAIRS 32
+
+typedef struct irm_config {
+    /* CDC (paper Sec. 4, Sec. 7.2 "CDC boundary rule", App. B) */
+    uint32_t gear[256];   /* gear table; one step per token, indexed by the id's low byte */
+    uint32_t mask;        /* 2^k - 1, k <= 32; a cut needs (state & mask) == 0             */
+    uint32_t min_chunk;   /* >= max(k, 1)                                                   */
+    uint32_t max_chunk;   /* >= min_chunk, <= 65536                                         */
+    /* lookup (Sec. 7.1): chunks at absolute position < carve_out are never served; 0 = off */
+    uint32_t carve_out;
+    /* KV geometry: only 512 + 64, half-split pairs */
+    uint32_t n_layers;
+    uint32_t ckv_dim;
+    uint32_t kr_dim;
+    uint32_t pair_mode;
+    /* the model's fp32 rotary inverse frequencies (App. D: cos/sin are derived from
+     * this buffer, never from a position table); pure rotation, no magnitude factor */
+    float inv_freq[IRM_KR_PAIRS];
+    /* sizing of the context's scratch: largest token count / request count per call */
+    uint64_t max_tokens;
+    uint32_t max_requests;
+} irm_config;
+
+/* registry value: where a cached chunk's rows live and where it was computed */
+typedef struct irm_entry {
+    uint32_t src_row;  /* first row in the source pool; the chunk's rows are contiguous */
+    int32_t p_src;     /* absolute position of the chunk's first token when cached      */
+    uint32_t len;      /* tokens in the chunk                                           */
+    uint32_t entry_id; /* caller's tag, < 2^31; reported in chunk_entry on a hit        */
+} irm_entry;
+
+/* one re-attachable chunk of the current batch */
+typedef struct irm_hit {
+    uint32_t src_row; /* first source-pool row                                           */
+    uint32_t dst_tok; /* index of the chunk's first token in the batch (into dst_slots) */
+    uint32_t len;     /* rows                                                            */
+    int32_t delta;    /* new position - stored position                                  */
+} irm_hit;
+
+typedef struct irm_ctx irm_ctx;
+typedef struct irm_table irm_table;
+
+/* Chunks a batch can produce at most, given per-request lengths n_r:
+ * sum over r of (n_r / min_chunk + 1).  A safe bound from totals only. */
+static inline uint64_t irm_chunk_capacity_bound(uint64_t n_tokens, uint32_t n_req, uint32_t min_chunk)
+{
+    return n_tokens / (min_chunk ? min_chunk : 1) + n_req;
+}
+
+/* ---- lifetime (not on the hot path; these allocate and may synchronise) ---- */
+
+/* Validates cfg, allocates the context's constant tables and scratch on the
+ * current HIP device.  *out is set only on IRM_OK. */
+irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out);
+irm_status irm_ctx_destroy(irm_ctx *ctx);
+
+/* Blocks until `stream` is idle, then returns the device error word in *flags
+ * and clears it. */
+irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
+
+/* Tuning knobs for measurements (launch shapes only; results never change).
+ * knob 0: workgroups of the re-attach row kernel (0 = default). */
+irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
+
+/* Registry R: hash -> entry (Alg. 1 "Require", steps 7 and 13), an
+ * open-addressing table of n_slots slots in device memory owned by the table. */
+irm_status irm_table_create(irm_ctx *ctx, uint64_t n_slots, irm_table **out);
+irm_status irm_table_destroy(irm_table *table);
+
+/* Insert-if-absent of n (hash, entry) pairs (Alg. 1 step 13 inserts only on a
+ * miss, so the first entry offered for a hash stays: within a batch the lowest
+ * index wins, and earlier batches win over later ones).  Deterministic.
+ * d_hash, d_val: device arrays of n.  A full table raises IRM_FLAG_TABLE_FULL. */
+irm_status irm_table_insert(irm_table *table, const uint64_t *d_hash, const irm_entry *d_val,
+                            uint32_t n, void *stream);
+
+/* ---- hot path ------------------------------------------------------------ */
+
+/* Gear-hash CDC (Sec. 4; Sec. 7.2; App. B).  Per request the rolling state
+ * starts at 0 and takes one step per token, h = (h << 1) + gear[id & 0xFF]
+ * (32-bit); the chunk that starts at s ends at the first token i with
+ * i - s + 1 >= min_chunk and (h_i & mask) == 0, or at s + max_chunk - 1, or at
+ * the request's last token, whichever comes first.
+ *   d_tokens           int32[n_tokens], all requests concatenated
+ *   d_req_offsets      uint32[n_req + 1], ascending, [0] = 0, [n_req] = n_tokens
+ *   d_chunk_start/len  uint32[chunk_capacity] out, offsets into d_tokens, ascending
+ *   d_req_chunk_offsets uint32[n_req + 1] out, request r owns chunks [r], [r+1])
+ *   d_n_chunks         uint32[1] out
+ * Needs n_tokens <= cfg.max_tokens, n_req <= cfg.max_requests and
+ * chunk_capacity >= irm_chunk_capacity_bound(n_tokens, n_req, min_chunk)
+ * (else IRM_ERR_CAPACITY). */
+irm_status irm_cdc_chunk(irm_ctx *ctx, const int32_t *d_tokens, uint64_t n_tokens,
+                         const uint32_t *d_req_offsets, uint32_t n_req, uint32_t *d_chunk_start,
+                         uint32_t *d_chunk_len, uint32_t *d_req_chunk_offsets,
+                         uint32_t *d_n_chunks, uint32_t chunk_capacity, void *stream);
+
+/* Chunk fingerprint (Sec. 4; Alg. 1 steps 2, 7): FNV-1a-64 over the chunk's
+ * token ids taken as little-endian bytes.
+ *   d_chunk_hash uint64[chunk_capacity] out; entries >= *d_n_chunks untouched. */
+irm_status irm_chunk_hash(irm_ctx *ctx, const int32_t *d_tokens, uint64_t n_tokens,
+                          const uint32_t *d_chunk_start, const uint32_t *d_chunk_len,
+                          const uint32_t *d_n_chunks, uint32_t chunk_capacity,
+                          uint64_t *d_chunk_hash, void *stream);
+
+/* Registry probe (Alg. 1 steps 4-8; Sec. 7.1).  Chunk c of request r sits at
+ * p = d_pos_base[r] + (chunk_start[c] - req_offsets[r]).  It is a miss if
+ * p < carve_out, a hit if the table holds its hash with the same length, a
+ * miss otherwise.
+ *   d_chunk_entry int32[chunk_capacity] out: entry_id or -1
+ *   d_hits        irm_hit[chunk_capacity] out: the hits in ascending chunk order
+ *   d_n_hits      uint32[1] out;  d_hit_tokens uint64[1] out (sum of hit lengths) */
+irm_status irm_lookup(irm_ctx *ctx, const irm_table *table, const uint64_t *d_chunk_hash,
+                      const uint32_t *d_chunk_start, const uint32_t *d_chunk_len,
+                      const uint32_t *d_req_chunk_offsets, const uint32_t *d_req_offsets,
+                      const int32_t *d_pos_base, uint32_t n_req, const uint32_t *d_n_chunks,
+                      uint32_t chunk_capacity, int32_t *d_chunk_entry, irm_hit *d_hits,
+                      uint32_t *d_n_hits, uint64_t *d_hit_tokens, void *stream);
+
+/* Fused gather + delta-rotation + scatter (Alg. 1 steps 8-10; Sec. 7.2 "k_r
+ * rotation"; App. C "k_r rotation materialisation").  For every hit h, layer l
+ * and j < len:
+ *   dst[l][ d_dst_slots[dst_tok + j] ][0:512]  = src[l][src_row + j][0:512]   (bit copy)
+ *   dst[l][ ... ][512 + i], [512 + 32 + i]     = the pair (k_i, k_{i+32}) turned by
+ *                                                delta * inv_freq[i], i < 32
+ * with the angle reduced in fp64, the rotation in fp32 and one
+ * round-to-nearest-even to bf16.
+ *   d_src_layer_ptrs / d_dst_layer_ptrs  device arrays of n_layers device pointers
+ *                                        to row 0 of each layer (16-byte aligned)
+ *   *_row_stride_bytes                   >= 1152, multiple of 16
+ *   src_rows / dst_rows                  rows per layer (bounds; rows outside are skipped
+ *                                        and raise IRM_FLAG_ROW_RANGE)
+ *   d_dst_slots                          int32[n_slots_tokens]: destination row per batch token
+ *   d_hits, d_n_hits                     as written by irm_lookup; *d_n_hits <= hit_capacity
+ * Destination rows of different hits must not overlap; src and dst pools must
+ * not alias.  Rows no hit covers are not touched. */
+irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
+                        uint64_t src_row_stride_bytes, uint64_t src_rows,
+                        void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,
+                        uint64_t dst_rows, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
+                        const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
+                        void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IRM_H */

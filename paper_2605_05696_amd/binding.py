@@ -1,0 +1,222 @@
+"""ctypes binding of ``libirm.so`` with the same names as ``include/irm.h``.
+
+Argument marshalling only: torch supplies device memory (``tensor.data_ptr()``)
+and the stream handle; every step of the path runs in the library's HIP
+kernels.  There is no CPU fallback: if the library has not been built, loading
+it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libirm.so")
+
+IRM_OK, IRM_ERR_INVALID_ARG, IRM_ERR_CAPACITY, IRM_ERR_UNSUPPORTED, IRM_ERR_DEVICE, IRM_ERR_TABLE_FULL = range(6)
+STATUS_NAMES = {0: "IRM_OK", 1: "IRM_ERR_INVALID_ARG", 2: "IRM_ERR_CAPACITY", 3: "IRM_ERR_UNSUPPORTED",
+                4: "IRM_ERR_DEVICE", 5: "IRM_ERR_TABLE_FULL"}
+IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_CHUNK = 1, 2, 4, 8
+
+SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
+           "irm_table_create", "irm_table_destroy", "irm_table_insert",
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach")
+
+
+class IrmError(RuntimeError):
+    def __init__(self, call, status):
+        super().__init__(f"{call} -> {STATUS_NAMES.get(status, status)}")
+        self.status = status
+
+
+class irm_config(ctypes.Structure):
+    _fields_ = [("gear", ctypes.c_uint32 * 256), ("mask", ctypes.c_uint32),
+                ("min_chunk", ctypes.c_uint32), ("max_chunk", ctypes.c_uint32),
+                ("carve_out", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
+                ("ckv_dim", ctypes.c_uint32), ("kr_dim", ctypes.c_uint32),
+                ("pair_mode", ctypes.c_uint32), ("inv_freq", ctypes.c_float * 32),
+                ("max_tokens", ctypes.c_uint64), ("max_requests", ctypes.c_uint32)]
+
+
+# numpy / torch views of the two record types (16 bytes each)
+ENTRY_DTYPE = np.dtype([("src_row", "<u4"), ("p_src", "<i4"), ("len", "<u4"), ("entry_id", "<u4")])
+HIT_DTYPE = np.dtype([("src_row", "<u4"), ("dst_tok", "<u4"), ("len", "<u4"), ("delta", "<i4")])
+
+_lib = None
+
+
+def lib():
+    """Load the built library; raises if it is missing (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2605_05696_amd.build` "
+                              "(or __graft_entry__.build()); there is no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
+        L.irm_ctx_create.argtypes = [ctypes.POINTER(irm_config), ctypes.POINTER(vp)]
+        L.irm_ctx_destroy.argtypes = [vp]
+        L.irm_ctx_error_flags.argtypes = [vp, vp, ctypes.POINTER(u32)]
+        L.irm_ctx_tune.argtypes = [vp, u32, u32]
+        L.irm_table_create.argtypes = [vp, u64, ctypes.POINTER(vp)]
+        L.irm_table_destroy.argtypes = [vp]
+        L.irm_table_insert.argtypes = [vp, vp, vp, u32, vp]
+        L.irm_cdc_chunk.argtypes = [vp, vp, u64, vp, u32, vp, vp, vp, vp, u32, vp]
+        L.irm_chunk_hash.argtypes = [vp, vp, u64, vp, vp, vp, u32, vp, vp]
+        L.irm_lookup.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
+        L.irm_reattach.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, u64, vp, vp, u32, vp]
+        for name in SYMBOLS:
+            getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(call, status):
+    if status != IRM_OK:
+        raise IrmError(call, status)
+
+
+def _dev(t, dtype, what):
+    """Device pointer of a contiguous CUDA/HIP tensor of the given torch dtype."""
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError(f"{what}: need a contiguous device tensor of dtype {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def make_config(gear, mask, min_chunk, max_chunk, carve_out, n_layers, inv_freq, max_tokens,
+                max_requests, ckv_dim=512, kr_dim=64, pair_mode=0) -> irm_config:
+    cfg = irm_config()
+    gear = np.ascontiguousarray(gear, np.uint32)
+    inv_freq = np.ascontiguousarray(inv_freq, np.float32)
+    assert gear.shape == (256,) and inv_freq.shape == (32,)
+    cfg.gear[:] = gear.tolist()
+    cfg.inv_freq[:] = inv_freq.tolist()
+    cfg.mask, cfg.min_chunk, cfg.max_chunk, cfg.carve_out = mask, min_chunk, max_chunk, carve_out
+    cfg.n_layers, cfg.ckv_dim, cfg.kr_dim, cfg.pair_mode = n_layers, ckv_dim, kr_dim, pair_mode
+    cfg.max_tokens, cfg.max_requests = max_tokens, max_requests
+    return cfg
+
+
+def irm_ctx_create(cfg: irm_config) -> ctypes.c_void_p:
+    out = ctypes.c_void_p()
+    _check("irm_ctx_create", lib().irm_ctx_create(ctypes.byref(cfg), ctypes.byref(out)))
+    return out
+
+
+def irm_ctx_destroy(ctx) -> None:
+    _check("irm_ctx_destroy", lib().irm_ctx_destroy(ctx))
+
+
+def irm_ctx_error_flags(ctx, stream=None) -> int:
+    flags = ctypes.c_uint32(0)
+    _check("irm_ctx_error_flags", lib().irm_ctx_error_flags(ctx, _stream(stream), ctypes.byref(flags)))
+    return flags.value
+
+
+def irm_ctx_tune(ctx, knob: int, value: int) -> None:
+    _check("irm_ctx_tune", lib().irm_ctx_tune(ctx, knob, value))
+
+
+def irm_table_create(ctx, n_slots: int) -> ctypes.c_void_p:
+    out = ctypes.c_void_p()
+    _check("irm_table_create", lib().irm_table_create(ctx, n_slots, ctypes.byref(out)))
+    return out
+
+
+def irm_table_destroy(table) -> None:
+    _check("irm_table_destroy", lib().irm_table_destroy(table))
+
+
+def irm_table_insert(table, d_hash, d_val, stream=None) -> None:
+    """d_hash: int64 device tensor [n] (bit pattern of the uint64 hashes);
+    d_val: int32 device tensor [n, 4] laid out as irm_entry."""
+    import torch
+    n = d_hash.numel()
+    if d_val.shape != (n, 4):
+        raise TypeError("d_val: need shape [n, 4]")
+    _check("irm_table_insert", lib().irm_table_insert(
+        table, _dev(d_hash, torch.int64, "d_hash"), _dev(d_val, torch.int32, "d_val"), n, _stream(stream)))
+
+
+def irm_cdc_chunk(ctx, d_tokens, d_req_offsets, d_chunk_start, d_chunk_len, d_req_chunk_offsets,
+                  d_n_chunks, stream=None) -> None:
+    """uint32 arrays travel as int32 tensors (same bits)."""
+    import torch
+    i32 = torch.int32
+    n_req = d_req_offsets.numel() - 1
+    cap = d_chunk_start.numel()
+    if d_chunk_len.numel() != cap or d_req_chunk_offsets.numel() != n_req + 1 or d_n_chunks.numel() != 1:
+        raise TypeError("irm_cdc_chunk: output sizes do not match")
+    _check("irm_cdc_chunk", lib().irm_cdc_chunk(
+        ctx, _dev(d_tokens, i32, "d_tokens"), d_tokens.numel(), _dev(d_req_offsets, i32, "d_req_offsets"),
+        n_req, _dev(d_chunk_start, i32, "d_chunk_start"), _dev(d_chunk_len, i32, "d_chunk_len"),
+        _dev(d_req_chunk_offsets, i32, "d_req_chunk_offsets"), _dev(d_n_chunks, i32, "d_n_chunks"),
+        cap, _stream(stream)))
+
+
+def irm_chunk_hash(ctx, d_tokens, d_chunk_start, d_chunk_len, d_n_chunks, d_chunk_hash, stream=None) -> None:
+    import torch
+    i32 = torch.int32
+    cap = d_chunk_hash.numel()
+    if d_chunk_start.numel() < cap or d_chunk_len.numel() < cap:
+        raise TypeError("irm_chunk_hash: chunk arrays shorter than the hash array")
+    _check("irm_chunk_hash", lib().irm_chunk_hash(
+        ctx, _dev(d_tokens, i32, "d_tokens"), d_tokens.numel(), _dev(d_chunk_start, i32, "d_chunk_start"),
+        _dev(d_chunk_len, i32, "d_chunk_len"), _dev(d_n_chunks, i32, "d_n_chunks"), cap,
+        _dev(d_chunk_hash, torch.int64, "d_chunk_hash"), _stream(stream)))
+
+
+def irm_lookup(ctx, table, d_chunk_hash, d_chunk_start, d_chunk_len, d_req_chunk_offsets, d_req_offsets,
+               d_pos_base, d_n_chunks, d_chunk_entry, d_hits, d_n_hits, d_hit_tokens, stream=None) -> None:
+    """d_hits: int32 device tensor [capacity, 4] laid out as irm_hit."""
+    import torch
+    i32, i64 = torch.int32, torch.int64
+    n_req = d_req_offsets.numel() - 1
+    cap = d_chunk_entry.numel()
+    if (d_hits.shape != (cap, 4) or d_chunk_hash.numel() < cap or d_chunk_start.numel() < cap
+            or d_chunk_len.numel() < cap or d_pos_base.numel() != n_req
+            or d_req_chunk_offsets.numel() != n_req + 1):
+        raise TypeError("irm_lookup: array sizes do not match")
+    _check("irm_lookup", lib().irm_lookup(
+        ctx, table, _dev(d_chunk_hash, i64, "d_chunk_hash"), _dev(d_chunk_start, i32, "d_chunk_start"),
+        _dev(d_chunk_len, i32, "d_chunk_len"), _dev(d_req_chunk_offsets, i32, "d_req_chunk_offsets"),
+        _dev(d_req_offsets, i32, "d_req_offsets"), _dev(d_pos_base, i32, "d_pos_base"), n_req,
+        _dev(d_n_chunks, i32, "d_n_chunks"), cap, _dev(d_chunk_entry, i32, "d_chunk_entry"),
+        _dev(d_hits, i32, "d_hits"), _dev(d_n_hits, i32, "d_n_hits"),
+        _dev(d_hit_tokens, i64, "d_hit_tokens"), _stream(stream)))
+
+
+def layer_pointers(pool):
+    """Device array of per-layer base pointers of a [L, rows, 576] bf16 pool tensor."""
+    import torch
+    if pool.dim() != 3 or pool.shape[2] != 576 or pool.dtype != torch.bfloat16 or not pool.is_cuda:
+        raise TypeError("pool: need a [L, rows, 576] bf16 device tensor")
+    if pool.stride(2) != 1 or pool.stride(1) < 576:
+        raise TypeError("pool: rows must be dense")
+    ptrs = [pool.data_ptr() + l * pool.stride(0) * 2 for l in range(pool.shape[0])]
+    return torch.tensor(ptrs, dtype=torch.int64, device=pool.device)
+
+
+def irm_reattach(ctx, d_src_layer_ptrs, src_row_stride_bytes, src_rows, d_dst_layer_ptrs,
+                 dst_row_stride_bytes, dst_rows, d_dst_slots, d_hits, d_n_hits, stream=None) -> None:
+    import torch
+    i32, i64 = torch.int32, torch.int64
+    if d_hits.dim() != 2 or d_hits.shape[1] != 4:
+        raise TypeError("d_hits: need shape [capacity, 4]")
+    if d_src_layer_ptrs.numel() != d_dst_layer_ptrs.numel():
+        raise TypeError("layer pointer arrays differ in length")
+    _check("irm_reattach", lib().irm_reattach(
+        ctx, _dev(d_src_layer_ptrs, i64, "d_src_layer_ptrs"), src_row_stride_bytes, src_rows,
+        _dev(d_dst_layer_ptrs, i64, "d_dst_layer_ptrs"), dst_row_stride_bytes, dst_rows,
+        _dev(d_dst_slots, i32, "d_dst_slots"), d_dst_slots.numel(), _dev(d_hits, i32, "d_hits"),
+        _dev(d_n_hits, i32, "d_n_hits"), d_hits.shape[0], _stream(stream)))

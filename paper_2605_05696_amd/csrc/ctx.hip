@@ -1,0 +1,226 @@
+// Context and registry-table lifetime, argument validation, insert-if-absent.
+#include <new>
+#include <string.h>
+
+#include "irm_internal.hpp"
+
+static inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
+{
+    if (!cfg || !out) return IRM_ERR_INVALID_ARG;
+    if (cfg->ckv_dim != 512 || cfg->kr_dim != 64 || cfg->pair_mode != IRM_PAIR_HALF_SPLIT)
+        return IRM_ERR_UNSUPPORTED;
+    const uint64_t m = cfg->mask;
+    if ((m & (m + 1)) != 0) return IRM_ERR_UNSUPPORTED;        // mask must be 2^k - 1
+    const uint32_t k_bits = (uint32_t)__builtin_popcountll(m);
+    if (cfg->min_chunk < 1 || cfg->min_chunk < k_bits) return IRM_ERR_INVALID_ARG;
+    if (cfg->max_chunk < cfg->min_chunk || cfg->max_chunk > 65536) return IRM_ERR_INVALID_ARG;
+    if (cfg->n_layers < 1 || cfg->n_layers > 4096) return IRM_ERR_INVALID_ARG;
+    if (cfg->max_tokens < 1 || cfg->max_tokens > 0xFFFFFFF0ull - 65536) return IRM_ERR_INVALID_ARG;
+    if (cfg->max_requests < 1 || cfg->max_requests > (1u << 20)) return IRM_ERR_INVALID_ARG;
+    for (int i = 0; i < IRM_KR_PAIRS; ++i)
+        if (!(cfg->inv_freq[i] == cfg->inv_freq[i]) || cfg->inv_freq[i] - cfg->inv_freq[i] != 0.0f)
+            return IRM_ERR_INVALID_ARG;                         // NaN or infinite frequency
+    const uint64_t chunk_cap64 = cfg->max_tokens / cfg->min_chunk + cfg->max_requests;
+    if (chunk_cap64 > 0x7FFFFFFFull) return IRM_ERR_CAPACITY;
+
+    irm_ctx *c = new (std::nothrow) irm_ctx;
+    if (!c) return IRM_ERR_DEVICE;
+    memset(c, 0, sizeof *c);
+    c->cfg = *cfg;
+    c->k_bits = k_bits;
+    c->chunk_cap = (uint32_t)chunk_cap64;
+    c->tile_cap = (uint32_t)(cfg->max_tokens / IRM_TILE_ROWS + chunk_cap64);
+
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&c->device) != hipSuccess || hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return IRM_ERR_DEVICE;
+    }
+    c->n_cu = (uint32_t)prop.multiProcessorCount;
+
+    // carve one slab
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
+    const uint64_t o_gear = take(256 * 4), o_inv = take(IRM_KR_PAIRS * 4), o_err = take(4);
+    const uint64_t o_bitmap = take((cfg->max_tokens / 64 + 2) * 8);
+    const uint64_t o_ss = take((uint64_t)c->chunk_cap * 4), o_sl = take((uint64_t)c->chunk_cap * 4);
+    const uint64_t o_rc = take((uint64_t)cfg->max_requests * 4);
+    const uint64_t o_ht = take((uint64_t)c->chunk_cap * sizeof(irm_hit));
+    const uint64_t o_tiles = take((uint64_t)c->tile_cap * sizeof(irm_tile));
+    const uint64_t o_trig = take((uint64_t)c->chunk_cap * IRM_KR_PAIRS * sizeof(float2));
+    const uint64_t o_plan = take(16);
+    if (hipMalloc(&c->slab, off) != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return IRM_ERR_DEVICE;
+    }
+    char *base = (char *)c->slab;
+    c->d_gear = (uint32_t *)(base + o_gear);
+    c->d_inv_freq = (float *)(base + o_inv);
+    c->d_err = (uint32_t *)(base + o_err);
+    c->d_bitmap = (uint64_t *)(base + o_bitmap);
+    c->d_stage_start = (uint32_t *)(base + o_ss);
+    c->d_stage_len = (uint32_t *)(base + o_sl);
+    c->d_req_count = (uint32_t *)(base + o_rc);
+    c->d_hit_tmp = (irm_hit *)(base + o_ht);
+    c->d_tiles = (irm_tile *)(base + o_tiles);
+    c->d_trig = (float2 *)(base + o_trig);
+    c->d_plan = (uint32_t *)(base + o_plan);
+    if (hipMemset(c->slab, 0, off) != hipSuccess ||
+        hipMemcpy(c->d_gear, cfg->gear, 256 * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(c->d_inv_freq, cfg->inv_freq, IRM_KR_PAIRS * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(c->slab);
+        delete c;
+        return IRM_ERR_DEVICE;
+    }
+    *out = c;
+    return IRM_OK;
+}
+
+extern "C" irm_status irm_ctx_destroy(irm_ctx *ctx)
+{
+    if (!ctx) return IRM_ERR_INVALID_ARG;
+    irm_status st = IRM_OK;
+    if (ctx->slab && hipFree(ctx->slab) != hipSuccess) {
+        (void)hipGetLastError();
+        st = IRM_ERR_DEVICE;
+    }
+    delete ctx;
+    return st;
+}
+
+extern "C" irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags)
+{
+    if (!ctx || !flags) return IRM_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t zero = 0;
+    IRM_HIP_TRY(hipStreamSynchronize(s));
+    IRM_HIP_TRY(hipMemcpy(flags, ctx->d_err, 4, hipMemcpyDeviceToHost));
+    IRM_HIP_TRY(hipMemcpy(ctx->d_err, &zero, 4, hipMemcpyHostToDevice));
+    return IRM_OK;
+}
+
+extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
+{
+    if (!ctx) return IRM_ERR_INVALID_ARG;
+    if (knob == 0) {
+        if (value > (1u << 20)) return IRM_ERR_INVALID_ARG;
+        ctx->reattach_grid = value;
+        return IRM_OK;
+    }
+    return IRM_ERR_INVALID_ARG;
+}
+
+// ---------------------------------------------------------------- registry --
+
+extern "C" irm_status irm_table_create(irm_ctx *ctx, uint64_t n_slots, irm_table **out)
+{
+    if (!ctx || !out || n_slots < 1) return IRM_ERR_INVALID_ARG;
+    if (n_slots > (1ull << 32)) return IRM_ERR_CAPACITY;
+    irm_table *t = new (std::nothrow) irm_table;
+    if (!t) return IRM_ERR_DEVICE;
+    memset(t, 0, sizeof *t);
+    t->ctx = ctx;
+    t->n_slots = n_slots;
+    const uint64_t n = n_slots + 1;
+    if (hipMalloc((void **)&t->d_keys, n * 8) != hipSuccess ||
+        hipMalloc((void **)&t->d_owner, n * 4) != hipSuccess ||
+        hipMalloc((void **)&t->d_vals, n * sizeof(irm_entry)) != hipSuccess ||
+        hipMemset(t->d_keys, 0, n * 8) != hipSuccess ||
+        hipMemset(t->d_owner, 0xFF, n * 4) != hipSuccess ||
+        hipMemset(t->d_vals, 0, n * sizeof(irm_entry)) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        (void)hipGetLastError();
+        if (t->d_keys) (void)hipFree(t->d_keys);
+        if (t->d_owner) (void)hipFree(t->d_owner);
+        if (t->d_vals) (void)hipFree(t->d_vals);
+        delete t;
+        return IRM_ERR_DEVICE;
+    }
+    *out = t;
+    return IRM_OK;
+}
+
+extern "C" irm_status irm_table_destroy(irm_table *table)
+{
+    if (!table) return IRM_ERR_INVALID_ARG;
+    irm_status st = IRM_OK;
+    if (hipFree(table->d_keys) != hipSuccess) st = IRM_ERR_DEVICE;
+    if (hipFree(table->d_owner) != hipSuccess) st = IRM_ERR_DEVICE;
+    if (hipFree(table->d_vals) != hipSuccess) st = IRM_ERR_DEVICE;
+    if (st != IRM_OK) (void)hipGetLastError();
+    delete table;
+    return st;
+}
+
+// Walk the probe sequence of `key` until its slot is found or claimed.
+// Returns the slot, or n_slots + 1 when the table has no room.
+__device__ __forceinline__ uint64_t claim_slot(uint64_t *keys, uint64_t n_slots, uint64_t key)
+{
+    if (key == 0) return n_slots;                       // reserved slot: 0 marks "empty" elsewhere
+    uint64_t s = irm_slot_of(key, n_slots);
+    for (uint64_t tries = 0; tries < n_slots; ++tries) {
+        unsigned long long seen = atomicCAS((unsigned long long *)&keys[s], 0ull, (unsigned long long)key);
+        if (seen == 0ull || seen == key) return s;
+        s = (s + 1 == n_slots) ? 0 : s + 1;
+    }
+    return n_slots + 1;
+}
+
+// pass 1: claim a slot per key and record the lowest offer rank that wants it
+__global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *owner, uint64_t n_slots,
+                                                   const uint64_t *hash, uint32_t n, uint32_t rank0,
+                                                   uint32_t *err)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint64_t s = claim_slot(keys, n_slots, hash[i]);
+    if (s > n_slots) {
+        atomicOr(err, IRM_FLAG_TABLE_FULL);
+        return;
+    }
+    atomicMin(&owner[s], rank0 + i);
+}
+
+// pass 2: the winning offer of a slot that was empty before this batch writes the value
+__global__ __launch_bounds__(256) void table_fill(const uint64_t *keys, const uint32_t *owner,
+                                                  irm_entry *vals, uint64_t n_slots,
+                                                  const uint64_t *hash, const irm_entry *val,
+                                                  uint32_t n, uint32_t rank0)
+{
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t key = hash[i];
+    uint64_t s = n_slots;
+    if (key != 0) {
+        s = irm_slot_of(key, n_slots);
+        uint64_t tries = 0;
+        while (keys[s] != key) {                        // present unless the table was full
+            if (keys[s] == 0 || ++tries >= n_slots) return;
+            s = (s + 1 == n_slots) ? 0 : s + 1;
+        }
+    }
+    if (owner[s] == rank0 + i) vals[s] = val[i];
+}
+
+extern "C" irm_status irm_table_insert(irm_table *table, const uint64_t *d_hash,
+                                       const irm_entry *d_val, uint32_t n, void *stream)
+{
+    if (!table || (!d_hash && n) || (!d_val && n)) return IRM_ERR_INVALID_ARG;
+    if (n == 0) return IRM_OK;
+    if (table->offered + n >= 0xFFFFFFFFull) return IRM_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t rank0 = (uint32_t)table->offered;
+    const uint32_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(table_claim, dim3(blocks), dim3(256), 0, s, table->d_keys, table->d_owner,
+                       table->n_slots, d_hash, n, rank0, table->ctx->d_err);
+    hipLaunchKernelGGL(table_fill, dim3(blocks), dim3(256), 0, s, table->d_keys, table->d_owner,
+                       table->d_vals, table->n_slots, d_hash, d_val, n, rank0);
+    table->offered += n;
+    return irm_launch_status();
+}

@@ -1,0 +1,109 @@
+// Internal declarations shared by the HIP sources of libirm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "irm.h"
+
+#define IRM_ROW_BYTES 1152u     // 576 bf16
+#define IRM_CKV_BYTES 1024u     // 512 bf16
+#define IRM_KR_BYTES 128u       // 64 bf16
+#define IRM_TILE_ROWS 64u       // rows of one re-attach tile
+#define IRM_WAVE 64
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// One tile of the re-attach row kernel: up to IRM_TILE_ROWS consecutive rows of one hit.
+struct irm_tile {
+    uint32_t src_row0;
+    uint32_t dst_tok0;
+    uint32_t n_rows;
+    uint32_t hit;
+};
+
+struct irm_ctx {
+    irm_config cfg;
+    int device;
+    uint32_t k_bits;        // popcount(mask)
+    uint32_t chunk_cap;     // max_tokens / min_chunk + max_requests
+    uint32_t tile_cap;      // max_tokens / IRM_TILE_ROWS + chunk_cap
+    uint32_t reattach_grid; // tuning knob 0
+    uint32_t n_cu;
+    // one device slab, carved up below
+    void *slab;
+    uint32_t *d_gear;       // [256]
+    float *d_inv_freq;      // [32]
+    uint32_t *d_err;        // [1] device error word
+    uint64_t *d_bitmap;     // candidate bit per token
+    uint32_t *d_stage_start, *d_stage_len; // [chunk_cap] per-request staged chunks
+    uint32_t *d_req_count;  // [max_requests]
+    irm_hit *d_hit_tmp;     // [chunk_cap] per-chunk probe result, len == 0 for a miss
+    irm_tile *d_tiles;      // [tile_cap]
+    float2 *d_trig;         // [chunk_cap][32] (cos, sin) per hit and pair
+    uint32_t *d_plan;       // [4]: n_tiles
+};
+
+struct irm_table {
+    irm_ctx *ctx;
+    uint64_t n_slots;       // slot n_slots is reserved for the key 0
+    uint64_t offered;       // entries offered so far (ranks first-wins across batches)
+    uint64_t *d_keys;       // [n_slots + 1], 0 = empty
+    uint32_t *d_owner;      // [n_slots + 1], rank of the winning offer, 0xFFFFFFFF = none
+    irm_entry *d_vals;      // [n_slots + 1]
+};
+
+#define IRM_HIP_TRY(expr)                      \
+    do {                                       \
+        if ((expr) != hipSuccess) {            \
+            (void)hipGetLastError();           \
+            return IRM_ERR_DEVICE;             \
+        }                                      \
+    } while (0)
+
+static inline irm_status irm_launch_status()
+{
+    return hipGetLastError() == hipSuccess ? IRM_OK : IRM_ERR_DEVICE;
+}
+
+// slot of a key: Fibonacci mixing, then multiply-shift range reduction
+__device__ __forceinline__ uint64_t irm_slot_of(uint64_t key, uint64_t n_slots)
+{
+    uint64_t m = key * 0x9E3779B97F4A7C15ull;
+    m ^= m >> 29;
+    return __umul64hi(m, n_slots);
+}
+
+__device__ __forceinline__ uint32_t irm_wave_id()
+{
+    return __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+}
+
+// inclusive scan of one uint32 per thread over a block of up to 1024 threads;
+// *total receives the block sum.  `lds` must hold 17 uint32.  All threads call.
+__device__ __forceinline__ uint32_t irm_block_scan_incl(uint32_t v, uint32_t *lds, uint32_t *total)
+{
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = (blockDim.x + 63) >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t y = __shfl_up(x, d);
+        if (lane >= (uint32_t)d) x += y;
+    }
+    __syncthreads();          // protects lds reuse across consecutive calls
+    if (lane == 63) lds[wave] = x;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (uint32_t w = 0; w < n_waves; ++w) {
+            uint32_t t = lds[w];
+            lds[w] = run;
+            run += t;
+        }
+        lds[16] = run;
+    }
+    __syncthreads();
+    *total = lds[16];
+    return x + lds[wave];
+}

@@ -1,0 +1,238 @@
+// Fused gather + delta-rotation + scatter (paper Alg. 1 steps 8-10; Sec. 7.2
+// "k_r rotation"; App. C "k_r rotation materialisation").
+//
+// Two launches.
+//   reattach_plan  per hit: the 32 (cos, sin) of delta * inv_freq[i], angle as an
+//                  fp64 product with fp64 range reduction (|delta| reaches 1e5, an
+//                  fp32 angle would already cost half a bf16 ulp); workgroup 0 also
+//                  cuts the hits into tiles of up to 64 rows.
+//   reattach_rows  persistent workgroups stream the tiles, layer-outer: a tile's
+//                  source rows are one contiguous span; each wave moves 16 rows of
+//                  c_KV with one 16-byte load and store per lane and row (a row's
+//                  1024 c_KV bytes are exactly one wave-wide access), and every
+//                  lane rotates 8 pairs of one row's k_r: the two 16-byte vectors
+//                  that hold elements 8j.. and 32+8j.. sit in the same lane, so the
+//                  half-split partners never cross lanes.  The row's 128 k_r bytes
+//                  are one cache line.  Loads and stores are non-temporal: every
+//                  byte is touched once.
+#include "irm_internal.hpp"
+
+// ---- plan --------------------------------------------------------------------
+__global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__ hits,
+                                                     const uint32_t *__restrict__ n_hits_p,
+                                                     uint32_t hit_capacity, const float *__restrict__ inv_freq,
+                                                     uint64_t src_rows, uint64_t n_slot_tokens,
+                                                     float2 *__restrict__ trig, irm_tile *__restrict__ tiles,
+                                                     uint32_t tile_cap, uint32_t *__restrict__ plan,
+                                                     uint32_t *err)
+{
+    uint32_t n_hits = *n_hits_p;
+    if (n_hits > hit_capacity) {
+        n_hits = hit_capacity;
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(err, IRM_FLAG_CHUNK_OVERFLOW);
+    }
+    // (cos, sin) table: one lane per (hit, pair)
+    {
+        const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+        const uint64_t h = gid / IRM_KR_PAIRS;
+        const uint32_t i = (uint32_t)(gid % IRM_KR_PAIRS);
+        if (h < n_hits) {
+            const int32_t delta = hits[h].delta;
+            float2 cs = make_float2(1.0f, 0.0f);          // delta == 0: exact identity
+            if (delta != 0) {
+                const double phi = (double)delta * (double)inv_freq[i];
+                double s, c;
+                sincos(phi, &s, &c);
+                cs = make_float2((float)c, (float)s);
+            }
+            trig[h * IRM_KR_PAIRS + i] = cs;
+        }
+    }
+    if (blockIdx.x != 0) return;
+    // tiles: exclusive scan of ceil(len / 64) over the hits, in order
+    __shared__ uint32_t lds[17];
+    uint32_t carry = 0;
+    for (uint32_t h0 = 0; h0 < n_hits; h0 += blockDim.x) {
+        const uint32_t h = h0 + threadIdx.x;
+        irm_hit hit = {0u, 0u, 0u, 0};
+        uint32_t nt = 0;
+        if (h < n_hits) {
+            hit = hits[h];
+            const bool ok = (uint64_t)hit.src_row + hit.len <= src_rows &&
+                            (uint64_t)hit.dst_tok + hit.len <= n_slot_tokens;
+            if (ok) nt = (hit.len + IRM_TILE_ROWS - 1) / IRM_TILE_ROWS;
+            else atomicOr(err, IRM_FLAG_ROW_RANGE);
+        }
+        uint32_t total;
+        const uint32_t incl = irm_block_scan_incl(nt, lds, &total);
+        uint32_t t = carry + incl - nt;
+        for (uint32_t k = 0; k < nt; ++k, ++t) {
+            if (t >= tile_cap) {
+                atomicOr(err, IRM_FLAG_CHUNK_OVERFLOW);
+                break;
+            }
+            const uint32_t done = k * IRM_TILE_ROWS;
+            irm_tile tile;
+            tile.src_row0 = hit.src_row + done;
+            tile.dst_tok0 = hit.dst_tok + done;
+            tile.n_rows = hit.len - done < IRM_TILE_ROWS ? hit.len - done : IRM_TILE_ROWS;
+            tile.hit = h;
+            tiles[t] = tile;
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) plan[0] = carry < tile_cap ? carry : tile_cap;
+}
+
+// ---- rows ----------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// fp32 -> bf16 bits, round to nearest even; NaN stays NaN
+__device__ __forceinline__ uint32_t f32_to_bf16(float x)
+{
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// rotate the two bf16 pairs packed in (wa, wb): wa holds elements (e, e+1) of the
+// first halves, wb their partners; cs0/cs1 are (cos, sin) for e and e+1
+__device__ __forceinline__ void rotate_word(uint32_t wa, uint32_t wb, float2 cs0, float2 cs1,
+                                            uint32_t &oa, uint32_t &ob)
+{
+    const float a0 = bf16_lo(wa), a1 = bf16_hi(wa), b0 = bf16_lo(wb), b1 = bf16_hi(wb);
+    const float ra0 = a0 * cs0.x - b0 * cs0.y, rb0 = b0 * cs0.x + a0 * cs0.y;
+    const float ra1 = a1 * cs1.x - b1 * cs1.y, rb1 = b1 * cs1.x + a1 * cs1.y;
+    oa = f32_to_bf16(ra0) | (f32_to_bf16(ra1) << 16);
+    ob = f32_to_bf16(rb0) | (f32_to_bf16(rb1) << 16);
+}
+
+template <bool FULL>
+__device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, uint64_t src_stride,
+                                              char *__restrict__ dbase, uint64_t dst_stride,
+                                              uint64_t dst_rows, int32_t slot, uint32_t n_rows,
+                                              const float2 *__restrict__ trig_hit, uint32_t wave,
+                                              uint32_t lane, uint32_t *err)
+{
+    constexpr int RPW = IRM_TILE_ROWS / 4;            // rows per wave
+    const uint32_t row0 = wave * RPW;
+    // c_KV: issue every load of this wave's rows before the first store
+    u32x4 v[RPW];
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const uint32_t r = row0 + i;
+        if (FULL || r < n_rows)
+            v[i] = __builtin_nontemporal_load((const u32x4 *)(sbase + (uint64_t)r * src_stride) + lane);
+    }
+    // k_r: lane (rr, j) owns pairs 8j .. 8j+7 of row rr
+    const uint32_t rr = row0 + (lane >> 2), j = lane & 3;
+    const bool kr_on = FULL || rr < n_rows;
+    u32x4 ka = {0, 0, 0, 0}, kb = {0, 0, 0, 0};
+    f32x4 t0 = {1, 0, 1, 0}, t1 = t0, t2 = t0, t3 = t0;
+    if (kr_on) {
+        const u32x4 *kr = (const u32x4 *)(sbase + (uint64_t)rr * src_stride + IRM_CKV_BYTES);
+        ka = __builtin_nontemporal_load(kr + j);
+        kb = __builtin_nontemporal_load(kr + 4 + j);
+        const f32x4 *tp = (const f32x4 *)(trig_hit + 8 * j);
+        t0 = tp[0];
+        t1 = tp[1];
+        t2 = tp[2];
+        t3 = tp[3];
+    }
+    const int32_t kr_slot = __shfl(slot, (int)rr);
+#pragma unroll
+    for (int i = 0; i < RPW; ++i) {
+        const uint32_t r = row0 + i;
+        if (FULL || r < n_rows) {
+            const int32_t s = __builtin_amdgcn_readlane(slot, (int)r);
+            if ((uint64_t)(uint32_t)s < dst_rows && s >= 0)
+                __builtin_nontemporal_store(v[i], (u32x4 *)(dbase + (uint64_t)(uint32_t)s * dst_stride) + lane);
+        }
+    }
+    if (kr_on && kr_slot >= 0 && (uint64_t)(uint32_t)kr_slot < dst_rows) {
+        uint32_t a0, a1, a2, a3, b0, b1, b2, b3;
+        rotate_word(ka.x, kb.x, make_float2(t0.x, t0.y), make_float2(t0.z, t0.w), a0, b0);
+        rotate_word(ka.y, kb.y, make_float2(t1.x, t1.y), make_float2(t1.z, t1.w), a1, b1);
+        rotate_word(ka.z, kb.z, make_float2(t2.x, t2.y), make_float2(t2.z, t2.w), a2, b2);
+        rotate_word(ka.w, kb.w, make_float2(t3.x, t3.y), make_float2(t3.z, t3.w), a3, b3);
+        const u32x4 oa = {a0, a1, a2, a3}, ob = {b0, b1, b2, b3};
+        u32x4 *out = (u32x4 *)(dbase + (uint64_t)(uint32_t)kr_slot * dst_stride + IRM_CKV_BYTES);
+        __builtin_nontemporal_store(oa, out + j);
+        __builtin_nontemporal_store(ob, out + 4 + j);
+    }
+    (void)err;
+}
+
+__global__ __launch_bounds__(256) void reattach_rows(const void *const *__restrict__ src_ptrs,
+                                                     uint64_t src_stride, void *const *__restrict__ dst_ptrs,
+                                                     uint64_t dst_stride, uint64_t dst_rows,
+                                                     const int32_t *__restrict__ dst_slots,
+                                                     const irm_tile *__restrict__ tiles,
+                                                     const uint32_t *__restrict__ plan,
+                                                     const float2 *__restrict__ trig, uint32_t n_layers,
+                                                     uint32_t *err)
+{
+    const uint32_t n_tiles = plan[0];
+    const uint64_t total = (uint64_t)n_tiles * n_layers;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = irm_wave_id();
+    for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
+        const uint32_t layer = (uint32_t)(t / n_tiles);
+        const uint32_t ti = (uint32_t)(t - (uint64_t)layer * n_tiles);
+        const irm_tile *tp = tiles + ti;
+        const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
+        const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
+        const uint32_t n_rows = __builtin_amdgcn_readfirstlane(tp->n_rows);
+        const uint32_t hit = __builtin_amdgcn_readfirstlane(tp->hit);
+        const char *sbase = (const char *)src_ptrs[layer] + (uint64_t)src_row0 * src_stride;
+        char *dbase = (char *)dst_ptrs[layer];
+        int32_t slot = -1;
+        if (lane < n_rows) {
+            slot = dst_slots[(uint64_t)dst_tok0 + lane];
+            if (slot < 0 || (uint64_t)(uint32_t)slot >= dst_rows) {
+                atomicOr(err, IRM_FLAG_ROW_RANGE);
+                slot = -1;
+            }
+        }
+        const float2 *trig_hit = trig + (uint64_t)hit * IRM_KR_PAIRS;
+        if (n_rows == IRM_TILE_ROWS)
+            reattach_tile<true>(sbase, src_stride, dbase, dst_stride, dst_rows, slot, n_rows, trig_hit, wave,
+                                lane, err);
+        else
+            reattach_tile<false>(sbase, src_stride, dbase, dst_stride, dst_rows, slot, n_rows, trig_hit, wave,
+                                 lane, err);
+    }
+}
+
+extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
+                                   uint64_t src_row_stride_bytes, uint64_t src_rows,
+                                   void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,
+                                   uint64_t dst_rows, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
+                                   const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
+                                   void *stream)
+{
+    if (!ctx || !d_src_layer_ptrs || !d_dst_layer_ptrs || !d_dst_slots || !d_hits || !d_n_hits)
+        return IRM_ERR_INVALID_ARG;
+    if (src_row_stride_bytes < IRM_ROW_BYTES || dst_row_stride_bytes < IRM_ROW_BYTES ||
+        (src_row_stride_bytes & 15) || (dst_row_stride_bytes & 15))
+        return IRM_ERR_INVALID_ARG;
+    if (src_rows < 1 || dst_rows < 1 || src_rows > 0xFFFFFFFFull || dst_rows > 0x7FFFFFFFull ||
+        n_slot_tokens < 1)
+        return IRM_ERR_INVALID_ARG;
+    if (hit_capacity < 1) return IRM_ERR_INVALID_ARG;
+    if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t plan_blocks = (uint32_t)(((uint64_t)hit_capacity * IRM_KR_PAIRS + 255) / 256);
+    hipLaunchKernelGGL(reattach_plan, dim3(plan_blocks), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
+                       ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles, ctx->tile_cap,
+                       ctx->d_plan, ctx->d_err);
+    uint64_t max_work = ((uint64_t)(n_slot_tokens / IRM_TILE_ROWS) + hit_capacity) * ctx->cfg.n_layers;
+    uint32_t grid = ctx->reattach_grid ? ctx->reattach_grid : ctx->n_cu * 8;
+    if (grid > max_work) grid = (uint32_t)(max_work ? max_work : 1);
+    hipLaunchKernelGGL(reattach_rows, dim3(grid), dim3(256), 0, s, d_src_layer_ptrs, src_row_stride_bytes,
+                       d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows, d_dst_slots, ctx->d_tiles,
+                       ctx->d_plan, ctx->d_trig, ctx->cfg.n_layers, ctx->d_err);
+    return irm_launch_status();
+}

@@ -1,0 +1,88 @@
+"""The C-ABI library: it loads, exports every function the header declares, and
+rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_05696_amd import binding as B
+from paper_2605_05696_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "irm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\birm_status\s+(irm_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert len(names) >= 11
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.SYMBOLS) == names
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(B.irm_config) == 256 * 4 + 8 * 4 + 32 * 4 + 8 + 8   # max_requests padded to 8
+    assert B.ENTRY_DTYPE.itemsize == 16 and B.HIT_DTYPE.itemsize == 16
+
+
+def good_config(**over):
+    kw = dict(gear=wl.gear_table(), mask=0xFF, min_chunk=64, max_chunk=1024, carve_out=32, n_layers=2,
+              inv_freq=wl.inv_freq_plain(), max_tokens=4096, max_requests=4)
+    kw.update(over)
+    return B.make_config(**kw)
+
+
+@pytest.mark.parametrize("over,status", [
+    (dict(mask=0xFE), B.IRM_ERR_UNSUPPORTED),               # not 2^k - 1
+    (dict(ckv_dim=256), B.IRM_ERR_UNSUPPORTED),
+    (dict(kr_dim=128), B.IRM_ERR_UNSUPPORTED),
+    (dict(pair_mode=1), B.IRM_ERR_UNSUPPORTED),
+    (dict(min_chunk=4), B.IRM_ERR_INVALID_ARG),             # window of 8 tokens needs min >= 8
+    (dict(min_chunk=0), B.IRM_ERR_INVALID_ARG),
+    (dict(min_chunk=2000), B.IRM_ERR_INVALID_ARG),          # min > max
+    (dict(max_chunk=1 << 20), B.IRM_ERR_INVALID_ARG),
+    (dict(n_layers=0), B.IRM_ERR_INVALID_ARG),
+    (dict(max_tokens=0), B.IRM_ERR_INVALID_ARG),
+    (dict(max_requests=0), B.IRM_ERR_INVALID_ARG),
+    (dict(inv_freq=np.full(32, np.nan, np.float32)), B.IRM_ERR_INVALID_ARG),
+])
+def test_ctx_create_rejects_bad_configs(over, status):
+    cfg = good_config(**over)
+    out = ctypes.c_void_p()
+    assert B.lib().irm_ctx_create(ctypes.byref(cfg), ctypes.byref(out)) == status
+    assert not out.value
+
+
+def test_null_arguments_are_rejected():
+    L = B.lib()
+    out = ctypes.c_void_p()
+    assert L.irm_ctx_create(None, ctypes.byref(out)) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_ctx_create(ctypes.byref(good_config()), None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_ctx_destroy(None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_table_destroy(None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_table_create(None, 16, ctypes.byref(out)) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_table_insert(None, None, None, 0, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_cdc_chunk(None, None, 0, None, 0, None, None, None, None, 0, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_chunk_hash(None, None, 0, None, None, None, 0, None, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_lookup(*([None] * 8), 0, None, 0, *([None] * 5)) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_reattach(None, None, 0, 0, None, 0, 0, None, 0, None, None, 0, None) == B.IRM_ERR_INVALID_ARG
+    flags = ctypes.c_uint32()
+    assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG
+
+
+def test_without_a_gpu_creation_fails_loudly_instead_of_falling_back():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.IrmError) as e:
+        B.irm_ctx_create(good_config())
+    assert e.value.status == B.IRM_ERR_DEVICE

@@ -1,0 +1,291 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle, through the C ABI.
+
+Integer stages (chunk boundaries, fingerprints, lookup results, c_KV bytes) are
+compared bit for bit; rotated k_r within 2 bf16 steps of the oracle's
+fp64-rounded value or 1e-2 absolute.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import irm_oracle as orc
+from paper_2605_05696_amd import binding as B
+from paper_2605_05696_amd import workloads as wl
+from paper_2605_05696_amd.pipeline import Session
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from tests.gpu_util import (DEV, ROW, Rig, bits, compare_rows, covered_rows, hits_from_dev,
+                                hits_to_dev, oracle_front, verify_reattach)
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need an MI355X; deselect with -m 'not gpu'"
+
+
+def small(name, **kw):
+    return wl.make_workload(name, orc.cdc_chunk, size="small", **kw)
+
+
+# ------------------------------------------------------------ chunk + hash --
+
+def gpu_chunks(tokens, req_offsets, gear, mask, lo, hi):
+    n_req = len(req_offsets) - 1
+    s = Session(gear, mask, lo, hi, 32, 1, wl.inv_freq_plain(), max(len(tokens), 1), max(n_req, 1), DEV)
+    try:
+        out = s.chunk_host(tokens, req_offsets)
+        assert s.error_flags() == 0
+    finally:
+        s.close()
+    return out
+
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+def test_cdc_and_hash_bit_exact_small_configs(name):
+    w = small(name)
+    for tokens, off in ((w.tokens, w.req_offsets), (w.pool_tokens, np.array([0, len(w.pool_tokens)], np.uint32))):
+        st, ln, rco, ch = gpu_chunks(tokens, off, w.gear, w.mask, w.min_chunk, w.max_chunk)
+        o_st, o_ln, o_rco = orc.cdc_chunk(tokens, off, w.gear, w.mask, w.min_chunk, w.max_chunk)
+        assert np.array_equal(st, o_st) and np.array_equal(ln, o_ln) and np.array_equal(rco, o_rco)
+        assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
+
+
+def test_cdc_ragged_requests_and_edge_lengths():
+    rng = np.random.default_rng(17)
+    gear = wl.gear_table()
+    lens = [1, 0, 63, 64, 65, 127, 128, 1023, 1024, 1025, 2048, 0, 5000, 7, 300000, 1]
+    tokens = rng.integers(0, 102400, size=sum(lens)).astype(np.int32)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
+    st, ln, rco, ch = gpu_chunks(tokens, off, gear, 0xFF, 64, 1024)
+    o_st, o_ln, o_rco = orc.cdc_chunk(tokens, off, gear, 0xFF, 64, 1024)
+    assert np.array_equal(rco, o_rco) and np.array_equal(st, o_st) and np.array_equal(ln, o_ln)
+    assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
+
+
+@pytest.mark.parametrize("mask,lo,hi", [(0x7F, 32, 512), (0x1, 1, 3), (0xFFFF, 16, 100), (0x0, 4, 9),
+                                        (0xF, 4, 4), (0xFFFFF, 64, 65536), (0xFF, 64, 1024),
+                                        (0xFFFFFFFF, 32, 40)])
+def test_cdc_other_masks_and_clamps(mask, lo, hi):
+    rng = np.random.default_rng(mask % 1000 + lo)
+    gear = wl.gear_table(seed=99)
+    n = 200000 if hi > 1024 else 30000
+    tokens = rng.integers(-2**31, 2**31, size=n, dtype=np.int64).astype(np.int32)
+    off = np.array([0, 11, n // 3, n], np.uint32)
+    st, ln, rco, ch = gpu_chunks(tokens, off, gear, mask, lo, hi)
+    o_st, o_ln, o_rco = orc.cdc_chunk(tokens, off, gear, mask, lo, hi)
+    assert np.array_equal(rco, o_rco) and np.array_equal(st, o_st) and np.array_equal(ln, o_ln)
+    assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
+
+
+def test_cdc_degenerate_streams():
+    gear = wl.gear_table()
+    same = np.full(5000, 7, np.int32)                    # constant stream: all or no candidates
+    for tokens in (same, np.arange(5000, dtype=np.int32) % 3):
+        off = np.array([0, len(tokens)], np.uint32)
+        st, ln, _, ch = gpu_chunks(tokens, off, gear, 0xFF, 64, 1024)
+        o_st, o_ln, _ = orc.cdc_chunk(tokens, off, gear, 0xFF, 64, 1024)
+        assert np.array_equal(st, o_st) and np.array_equal(ln, o_ln)
+        assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
+
+
+# ------------------------------------------------------------------ lookup --
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+def test_lookup_bit_exact_small_configs(name):
+    w = small(name)
+    rig = Rig(w, with_pools=False)
+    try:
+        o, buf = rig.o, rig.buf
+        rig.s.chunk_and_hash(rig.d_tokens, rig.d_req_offsets, buf)
+        B.irm_lookup(rig.s.ctx, rig.s.table, buf["chunk_hash"], buf["chunk_start"], buf["chunk_len"],
+                     buf["req_chunk_offsets"], rig.d_req_offsets, rig.d_pos_base, buf["n_chunks"],
+                     buf["chunk_entry"], buf["hits"], buf["n_hits"], buf["hit_tokens"])
+        assert rig.s.error_flags() == 0
+        n = int(buf["n_chunks"].item())
+        assert n == len(o["start"])
+        assert np.array_equal(buf["chunk_entry"].cpu().numpy()[:n], o["entry"])
+        n_hits = int(buf["n_hits"].item())
+        assert n_hits == len(o["hits"]) and int(buf["hit_tokens"].item()) == o["hit_tokens"]
+        g = hits_from_dev(buf["hits"], n_hits)
+        for f in ("src_row", "dst_tok", "len", "delta"):
+            assert np.array_equal(getattr(g, f), getattr(o["hits"], f)), f
+    finally:
+        rig.close()
+
+
+def test_table_first_wins_batches_zero_key_and_length_guard():
+    rng = np.random.default_rng(3)
+    n_reg, n_chunks = 5000, 3000
+    keys = rng.integers(0, 1500, size=n_reg, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)  # key 0 included
+    reg = dict(hash=keys, src_row=rng.integers(0, 10**6, n_reg).astype(np.uint32),
+               p_src=rng.integers(0, 5000, n_reg).astype(np.int32),
+               len=rng.integers(64, 67, n_reg).astype(np.uint32),
+               entry_id=np.arange(n_reg, dtype=np.uint32))
+    length = rng.integers(64, 67, n_chunks).astype(np.uint32)
+    start = np.concatenate([[0], np.cumsum(length)[:-1]]).astype(np.uint32)
+    rco = np.array([0, 1000, 1000, n_chunks], np.uint32)            # an empty request in the middle
+    off = np.array([0, start[1000], start[1000], int(length.sum())], np.uint32)
+    ch = rng.integers(0, 1600, size=n_chunks, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+    pos_base = np.array([0, 5, 40], np.int32)
+    o_entry, o_hits, o_tok = orc.lookup(reg["hash"], reg["src_row"], reg["p_src"], reg["len"],
+                                        reg["entry_id"], ch, start, length, rco, off, pos_base, 32)
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, 1, wl.inv_freq_plain(), int(length.sum()), 3, DEV)
+    try:
+        s.build_table(int(n_reg / 0.7), reg, batch=1234)             # several insert batches
+        cap = n_chunks
+        i32, i64 = torch.int32, torch.int64
+        d = lambda a: s.to_dev_u32(a)
+        entry = torch.full((cap,), -7, dtype=i32, device=DEV)
+        hits = torch.zeros((cap, 4), dtype=i32, device=DEV)
+        n_hits = torch.zeros(1, dtype=i32, device=DEV)
+        tok = torch.zeros(1, dtype=i64, device=DEV)
+        B.irm_lookup(s.ctx, s.table, s.to_dev_u64(ch), d(start), d(length), d(rco), d(off),
+                     torch.from_numpy(pos_base).to(DEV), torch.tensor([n_chunks], dtype=i32, device=DEV),
+                     entry, hits, n_hits, tok)
+        assert s.error_flags() == 0
+        assert np.array_equal(entry.cpu().numpy(), o_entry)
+        g = hits_from_dev(hits, int(n_hits.item()))
+        assert int(n_hits.item()) == len(o_hits) and int(tok.item()) == o_tok
+        for f in ("src_row", "dst_tok", "len", "delta"):
+            assert np.array_equal(getattr(g, f), getattr(o_hits, f)), f
+        assert (o_entry >= 0).sum() > 100 and (o_entry < 0).sum() > 100
+    finally:
+        s.close()
+
+
+def test_table_full_is_reported_not_fatal():
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, 1, wl.inv_freq_plain(), 1024, 1, DEV)
+    try:
+        n = 64
+        reg = dict(hash=np.arange(1, n + 1, dtype=np.uint64), src_row=np.zeros(n, np.uint32),
+                   p_src=np.zeros(n, np.int32), len=np.full(n, 64, np.uint32),
+                   entry_id=np.arange(n, dtype=np.uint32))
+        s.build_table(16, reg)
+        assert s.error_flags() & B.IRM_FLAG_TABLE_FULL
+        assert s.error_flags() == 0                                  # reading clears
+    finally:
+        s.close()
+
+
+# ---------------------------------------------------------------- reattach --
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+@pytest.mark.parametrize("slots", ["contiguous", "permuted"])
+def test_reattach_small_configs_all_rows(name, slots):
+    """Driven by the ORACLE's hit list, so this stage is tested on its own."""
+    w = small(name, slots=slots)
+    rig = Rig(w, with_table=False)
+    try:
+        hits = rig.o["hits"]
+        d_hits, d_n = hits_to_dev(hits, rig.buf["cap"])
+        rig.reattach(d_hits, d_n)
+        assert rig.s.error_flags() == 0
+        stats = verify_reattach(w, hits, rig.src, rig.dst, what=w.name)
+        assert stats["rows"] == rig.o["hit_tokens"] * w.n_layers
+        assert stats["exact"] > 0.95                                 # nearly all k_r values match exactly
+        # rows no hit covers still hold the sentinel
+        untouched = ~covered_rows(w, hits)
+        rest = bits(rig.dst[:, torch.from_numpy(np.nonzero(untouched)[0]).to(DEV), :])
+        assert np.all(rest == wl.SENTINEL_BF16)
+        # bit-for-bit repeatable
+        first = rig.dst.clone()
+        rig.reattach(d_hits, d_n)
+        torch.cuda.synchronize()
+        assert torch.equal(first.view(torch.int16), rig.dst.view(torch.int16))
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+def test_end_to_end_small_configs(name):
+    """The four calls chained on one stream with device-side counts."""
+    w = small(name)
+    rig = Rig(w)
+    try:
+        rig.serve()
+        assert rig.s.error_flags() == 0
+        o = rig.o
+        n_hits = int(rig.buf["n_hits"].item())
+        g = hits_from_dev(rig.buf["hits"], n_hits)
+        assert n_hits == len(o["hits"]) and np.array_equal(g.delta, o["hits"].delta)
+        assert np.array_equal(g.src_row, o["hits"].src_row) and np.array_equal(g.dst_tok, o["hits"].dst_tok)
+        verify_reattach(w, o["hits"], rig.src, rig.dst, what=w.name)
+    finally:
+        rig.close()
+
+
+def test_reattach_special_deltas_and_tile_tails():
+    """delta = 0 must reproduce the row bit for bit; hit lengths around the 64-row
+    tile size; extreme |delta|; strided pools."""
+    rng = np.random.default_rng(5)
+    L, src_rows, dst_rows = 2, 3000, 2600
+    lens = np.array([1, 63, 64, 65, 128, 129, 1024, 7], np.uint32)
+    src_row = np.array([0, 10, 100, 200, 300, 500, 700, 2900], np.uint32)
+    dst_tok = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.uint32)
+    delta = np.array([0, 1, -1, 131071, -131072, 2**31 - 1, -2**31, 0], np.int32)
+    hits = orc.Hits(src_row, dst_tok, lens, delta)
+    n_tok = int(lens.sum())
+    inv = wl.inv_freq_yarn()
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, L, inv, 4096, 1, DEV)
+    try:
+        stride_elems = ROW + 64                                       # padded rows: stride 1280 B
+        src_full = torch.randn((L, src_rows, stride_elems), device=DEV).to(torch.bfloat16)
+        dst_full = torch.empty((L, dst_rows, stride_elems), dtype=torch.bfloat16, device=DEV)
+        dst_full.view(torch.int16).fill_(wl.SENTINEL_BF16)
+        src, dst = src_full[:, :, :ROW], dst_full[:, :, :ROW]
+        slots = rng.permutation(dst_rows)[:n_tok].astype(np.int32)
+        d_hits, d_n = hits_to_dev(hits, 16)
+        B.irm_reattach(s.ctx, B.layer_pointers(src), stride_elems * 2, src_rows, B.layer_pointers(dst),
+                       stride_elems * 2, dst_rows, torch.from_numpy(slots).to(DEV), d_hits, d_n)
+        assert s.error_flags() == 0
+
+        class W:                                                      # what verify_reattach reads
+            dst_slots, inv_freq = slots, inv
+        stats = verify_reattach(W, hits, src, dst, what="special")
+        assert stats["rows"] == n_tok * L
+        # delta == 0 hits are exact copies of whole rows
+        for h in (0, 7):
+            for j in range(int(lens[h])):
+                a = bits(src[:, int(src_row[h]) + j]), bits(dst[:, int(slots[int(dst_tok[h]) + j])])
+                assert np.array_equal(a[0], a[1])
+        # padding columns and unlisted rows untouched
+        assert torch.all(dst_full[:, :, ROW:].view(torch.int16) == wl.SENTINEL_BF16)
+        mask = torch.ones(dst_rows, dtype=torch.bool, device=DEV)
+        mask[torch.from_numpy(slots.astype(np.int64)).to(DEV)] = False
+        assert torch.all(dst[:, mask].contiguous().view(torch.int16) == wl.SENTINEL_BF16)
+    finally:
+        s.close()
+
+
+def test_reattach_no_hits_and_bad_indices_are_skipped_and_flagged():
+    L, rows = 1, 256
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, L, wl.inv_freq_plain(), 1024, 1, DEV)
+    try:
+        src = wl.kv_pool_torch(L, rows, 1, DEV)
+        dst = wl.sentinel_pool_torch(L, rows, DEV)
+        slots = np.arange(rows, dtype=np.int32)
+        slots[5] = rows + 3                                           # outside the pool
+        slots[6] = -1
+        d_slots = torch.from_numpy(slots).to(DEV)
+        sp, dp = B.layer_pointers(src), B.layer_pointers(dst)
+        # no hits: nothing written
+        d_hits, d_n = hits_to_dev(orc.Hits(*(np.zeros(0, t) for t in (np.uint32, np.uint32, np.uint32, np.int32))), 8)
+        B.irm_reattach(s.ctx, sp, ROW * 2, rows, dp, ROW * 2, rows, d_slots, d_hits, d_n)
+        assert s.error_flags() == 0
+        assert torch.all(dst.view(torch.int16) == wl.SENTINEL_BF16)
+        # hit 0 touches the two bad slots, hit 1 reads past the source pool, hit 2 is fine
+        hits = orc.Hits(np.array([0, 250, 100], np.uint32), np.array([0, 64, 128], np.uint32),
+                        np.array([10, 10, 10], np.uint32), np.array([3, 3, 3], np.int32))
+        d_hits, d_n = hits_to_dev(hits, 8)
+        B.irm_reattach(s.ctx, sp, ROW * 2, rows, dp, ROW * 2, rows, d_slots, d_hits, d_n)
+        assert s.error_flags() & B.IRM_FLAG_ROW_RANGE
+        got = bits(dst)
+        written = np.any(got != wl.SENTINEL_BF16, axis=2)[0]
+        want = np.zeros(rows, bool)
+        want[[0, 1, 2, 3, 4, 7, 8, 9]] = True                         # hit 0 minus slots 5, 6
+        want[128:138] = True                                          # hit 2
+        assert np.array_equal(written, want)
+    finally:
+        s.close()
