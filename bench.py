@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the cache-hit re-attachment path on one MI355X.
+
+A *step* is one pass of the whole hot path -- irm_cdc_chunk, irm_chunk_hash,
+irm_lookup, irm_reattach, back to back on one stream with device-side counts --
+over one synthetic request batch whose inputs are already resident in HBM.
+Several batch variants against the same pool are cycled so that consecutive
+steps do not re-read the same rows from the last-level cache.
+
+Prints ONE JSON line: whole-path re-attached tokens/s (``value``), the achieved
+HBM bandwidth of the re-attach row kernel against the 8 TB/s peak
+(``roofline``), and the CPU oracle timed on this machine's host cores
+(``cpu_baseline``).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+ROW_BYTES = 1152
+HBM_PEAK_GBS = 8000.0
+PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "reattach_rows_c1_traffic.json")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c1", help="c0..c4 (the headline is c1)")
+    ap.add_argument("--size", default="full", choices=["full", "small"])
+    ap.add_argument("--variants", type=int, default=8, help="request batches cycled through")
+    ap.add_argument("--slots", default="contiguous", choices=["contiguous", "permuted"])
+    ap.add_argument("--grid", type=int, default=0, help="workgroups of the row kernel (0 = library default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle baseline")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path is built and measured on ONE GPU; --gpus above 1 is not supported "
+              "(it shards by layer or by request with no exchange step, see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_05696_amd import binding as B
+    from paper_2605_05696_amd import workloads as wl
+    from paper_2605_05696_amd.pipeline import Session
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    name = args.workload
+    dims = wl.CONFIGS[name][args.size]
+
+    # ---- inputs: chunked and fingerprinted by the library itself -------------
+    max_stream = max(dims["pool"], dims.get("n_req", 1) * dims.get("req_len", dims["pool"]) * 2 + 16384)
+    gear = wl.gear_table()
+    front = Session(gear, 0xFF, 64, 1024, 32, 1, wl.inv_freq_plain(), max_stream, 1, dev)
+
+    def gpu_chunker(tokens, req_offsets, gear_, mask, lo, hi):
+        st, ln, rco, _ = front.chunk_host(tokens, req_offsets)
+        return st, ln, rco
+
+    n_var = 1 if name == "c0" else max(1, args.variants)
+    works = [wl.make_workload(name, gpu_chunker, size=args.size, variant=v, slots=args.slots)
+             for v in range(n_var)]
+    w0 = works[0]
+    _, _, _, pool_hash = front.chunk_host(w0.pool_tokens, np.array([0, len(w0.pool_tokens)], np.uint32))
+    front.close()
+
+    L = w0.n_layers
+    src = wl.kv_pool_torch(L, w0.src_rows, wl.kv_seed(name), dev)
+    dst = wl.sentinel_pool_torch(L, w0.dst_rows, dev)
+    src_ptrs, dst_ptrs = B.layer_pointers(src), B.layer_pointers(dst)
+
+    sessions, dev_in = [], []
+    for w in works:
+        s = Session.for_workload(w, dev)
+        s.build_table(w.table_slots, w.registry(pool_hash))
+        sessions.append(s)
+        dev_in.append(dict(tokens=torch.from_numpy(w.tokens).to(dev), req_offsets=s.to_dev_u32(w.req_offsets),
+                           pos_base=torch.from_numpy(w.pos_base).to(dev),
+                           dst_slots=torch.from_numpy(w.dst_slots).to(dev),
+                           buf=s.alloc_front(len(w.tokens), w.n_req)))
+        if args.grid:
+            B.irm_ctx_tune(s.ctx, 0, args.grid)
+
+    stream = torch.cuda.Stream(device=dev)
+    torch.cuda.synchronize()
+
+    def step(v):
+        s, d = sessions[v], dev_in[v]
+        s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
+                w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], stream)
+
+    with torch.cuda.stream(stream):
+        # one pass per variant: learn the hit counts, check the error words
+        hit_tokens = []
+        for v in range(n_var):
+            step(v)
+            stream.synchronize()
+            hit_tokens.append(int(dev_in[v]["buf"]["hit_tokens"].item()))
+            flags = sessions[v].error_flags()
+            assert flags == 0, f"device error flags {flags:#x}"
+        for k in range(args.warmup):
+            step(k % n_var)
+        for s in sessions:
+            B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(k % n_var)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        kernel_ms, kernel_n, kernel_tokens = 0.0, 0, 0
+        for v, s in enumerate(sessions):
+            ms, n = B.irm_ctx_profile_end(s.ctx, stream)
+            kernel_ms += ms
+            kernel_n += n
+            kernel_tokens += n * hit_tokens[v]
+
+    total_tokens = sum(hit_tokens[k % n_var] for k in range(args.steps))
+    value = total_tokens / elapsed
+    alg_bytes = kernel_tokens * L * 2 * ROW_BYTES               # read + write per row
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    traffic = None
+    if name == "c1" and args.size == "full" and os.path.exists(PROFILE_TRAFFIC):
+        traffic = json.load(open(PROFILE_TRAFFIC)).get("hbm_bytes_per_launch")
+
+    out = {
+        "metric": "re-attached KV tokens/s (all layers), whole hot path, 1 MI355X",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
+                               f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
+                   "variants": n_var, "hit_tokens_per_step": float(np.mean(hit_tokens)),
+                   "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach on one stream"},
+        "roofline": {"bound": "hbm", "kernel": "reattach_rows", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_token_layer": 2 * ROW_BYTES, "launches": kernel_n,
+                     "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3,
+                     "kernel_tokens_per_s": kernel_tokens / (kernel_ms * 1e-3) if kernel_ms > 0 else 0.0},
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(works, src, args.cpu_seconds)
+
+    for s in sessions:
+        s.close()
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def cpu_baseline(works, src, budget_s):
+    """The CPU oracle, as it stands, on the same request batches: chunk, fingerprint,
+    lookup and re-attach, single thread, until about ``budget_s`` of CPU time is spent."""
+    import torch
+    from oracle import irm_oracle as orc
+    from paper_2605_05696_amd import workloads as wl
+
+    w0 = works[0]
+    pool_hash = orc.chunk_hash(w0.pool_tokens, w0.pool_chunk_start, w0.pool_chunk_len)
+    spent, tokens, batches = 0.0, 0, 0
+    L = src.shape[0]
+    for w in works:
+        reg = w.registry(pool_hash)
+        t0 = time.perf_counter()
+        st, ln, rco = orc.cdc_chunk(w.tokens, w.req_offsets, w.gear, w.mask, w.min_chunk, w.max_chunk)
+        ch = orc.chunk_hash(w.tokens, st, ln)
+        _, hits, hit_tokens = orc.lookup(reg["hash"], reg["src_row"], reg["p_src"], reg["len"],
+                                         reg["entry_id"], ch, st, ln, rco, w.req_offsets, w.pos_base,
+                                         w.carve_out)
+        front_s = time.perf_counter() - t0
+        # bound the sample: hits are taken in order until the remaining budget is used up
+        rows_per_s = 4.0e5
+        room = max(budget_s - spent - front_s, 0.5) * rows_per_s / L
+        keep = int(np.searchsorted(np.cumsum(hits.len.astype(np.int64)), room, side="right"))
+        keep = max(1, min(keep, len(hits)))
+        lens = hits.len[:keep].astype(np.int64)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        within = np.arange(off[-1]) - np.repeat(off[:-1], lens)
+        src_idx = torch.from_numpy(np.repeat(hits.src_row[:keep].astype(np.int64), lens) + within).to(src.device)
+        src_c = np.stack([src[l].index_select(0, src_idx).view(torch.int16).cpu().numpy().view(np.uint16)
+                          for l in range(L)])
+        dst_c = np.zeros_like(src_c)
+        compact = orc.Hits(off[:-1].astype(np.uint32), off[:-1].astype(np.uint32), lens.astype(np.uint32),
+                           hits.delta[:keep].copy())
+        t1 = time.perf_counter()
+        orc.reattach(src_c, dst_c, np.arange(off[-1], dtype=np.int32), compact, w.inv_freq)
+        re_s = time.perf_counter() - t1
+        # the integer stages ran on the whole batch: charge them in proportion to the sample
+        share = off[-1] / max(hit_tokens, 1)
+        spent += front_s * share + re_s
+        tokens += int(off[-1])
+        batches += 1
+        if spent >= budget_s:
+            break
+    return {"value": tokens / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"{tokens} re-attached tokens x {L} layers from {batches} batch(es) of the same workload "
+                      f"(chunk+hash+lookup+re-attach, single thread), {spent:.1f} s of CPU time"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -126,6 +126,15 @@ irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
  * knob 0: workgroups of the re-attach row kernel (0 = default). */
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
+/* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples
+ * pairs of HIP events; while enabled, every irm_reattach records one pair
+ * around its row kernel on the caller's stream (calls past max_samples are not
+ * sampled).  irm_ctx_profile_end waits for the stream, returns the summed
+ * elapsed milliseconds and the number of samples, destroys the events and
+ * disables sampling.  Not for use under graph capture. */
+irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples);
+irm_status irm_ctx_profile_end(irm_ctx *ctx, void *stream, float *total_ms, uint32_t *n_samples);
+
 /* Registry R: hash -> entry (Alg. 1 "Require", steps 7 and 13), an
  * open-addressing table of n_slots slots in device memory owned by the table. */
 irm_status irm_table_create(irm_ctx *ctx, uint64_t n_slots, irm_table **out);

@@ -21,6 +21,7 @@ STATUS_NAMES = {0: "IRM_OK", 1: "IRM_ERR_INVALID_ARG", 2: "IRM_ERR_CAPACITY", 3:
 IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_CHUNK = 1, 2, 4, 8
 
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
+           "irm_ctx_profile_begin", "irm_ctx_profile_end",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
            "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach")
 
@@ -54,12 +55,15 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2605_05696_amd.build` "
                               "(or __graft_entry__.build()); there is no CPU fallback")
+        import torch  # noqa: F401  -- first, so that the library binds to the HIP runtime torch uses
         L = ctypes.CDLL(LIB_PATH)
         vp, u32, u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
         L.irm_ctx_create.argtypes = [ctypes.POINTER(irm_config), ctypes.POINTER(vp)]
         L.irm_ctx_destroy.argtypes = [vp]
         L.irm_ctx_error_flags.argtypes = [vp, vp, ctypes.POINTER(u32)]
         L.irm_ctx_tune.argtypes = [vp, u32, u32]
+        L.irm_ctx_profile_begin.argtypes = [vp, u32]
+        L.irm_ctx_profile_end.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(u32)]
         L.irm_table_create.argtypes = [vp, u64, ctypes.POINTER(vp)]
         L.irm_table_destroy.argtypes = [vp]
         L.irm_table_insert.argtypes = [vp, vp, vp, u32, vp]
@@ -125,6 +129,17 @@ def irm_ctx_error_flags(ctx, stream=None) -> int:
 
 def irm_ctx_tune(ctx, knob: int, value: int) -> None:
     _check("irm_ctx_tune", lib().irm_ctx_tune(ctx, knob, value))
+
+
+def irm_ctx_profile_begin(ctx, max_samples: int) -> None:
+    _check("irm_ctx_profile_begin", lib().irm_ctx_profile_begin(ctx, max_samples))
+
+
+def irm_ctx_profile_end(ctx, stream=None):
+    """-> (summed milliseconds of the sampled row-kernel launches, number of samples)"""
+    ms, n = ctypes.c_float(0), ctypes.c_uint32(0)
+    _check("irm_ctx_profile_end", lib().irm_ctx_profile_end(ctx, _stream(stream), ctypes.byref(ms), ctypes.byref(n)))
+    return ms.value, n.value
 
 
 def irm_table_create(ctx, n_slots: int) -> ctypes.c_void_p:

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void cdc_candidates(const int32_t *__restrict_
     for (uint32_t j = 0; j < k_bits; ++j) acc += g[32 + tid - j] << j;
     const bool cand = (i < n_tokens) && ((acc & mask) == 0);
     const uint64_t word = __ballot(cand);
-    if ((tid & 63) == 0) bitmap[i >> 6] = word;   // i is a multiple of 64 here; covers ceil(n/256)*4 words
+    if ((tid & 63) == 0 && i < n_tokens) bitmap[i >> 6] = word;   // i is a multiple of 64 here
 }
 
 // ---- kernel 2: greedy cut selection, one workgroup per request -------------

@@ -4,6 +4,8 @@
 
 #include "irm_internal.hpp"
 
+static void profile_drop(irm_ctx *ctx);
+
 static inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
 extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
@@ -45,7 +47,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes, 256); return o; };
     const uint64_t o_gear = take(256 * 4), o_inv = take(IRM_KR_PAIRS * 4), o_err = take(4);
-    const uint64_t o_bitmap = take((cfg->max_tokens / 64 + 2) * 8);
+    const uint64_t o_bitmap = take((cfg->max_tokens / 64 + 8) * 8);
     const uint64_t o_ss = take((uint64_t)c->chunk_cap * 4), o_sl = take((uint64_t)c->chunk_cap * 4);
     const uint64_t o_rc = take((uint64_t)cfg->max_requests * 4);
     const uint64_t o_ht = take((uint64_t)c->chunk_cap * sizeof(irm_hit));
@@ -86,6 +88,7 @@ extern "C" irm_status irm_ctx_destroy(irm_ctx *ctx)
 {
     if (!ctx) return IRM_ERR_INVALID_ARG;
     irm_status st = IRM_OK;
+    profile_drop(ctx);
     if (ctx->slab && hipFree(ctx->slab) != hipSuccess) {
         (void)hipGetLastError();
         st = IRM_ERR_DEVICE;
@@ -114,6 +117,59 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
         return IRM_OK;
     }
     return IRM_ERR_INVALID_ARG;
+}
+
+static void profile_drop(irm_ctx *ctx)
+{
+    if (ctx->prof_events) {
+        for (uint32_t k = 0; k < 2 * ctx->prof_cap; ++k)
+            if (ctx->prof_events[k]) (void)hipEventDestroy(ctx->prof_events[k]);
+        delete[] ctx->prof_events;
+    }
+    ctx->prof_events = nullptr;
+    ctx->prof_cap = ctx->prof_n = 0;
+}
+
+extern "C" irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples)
+{
+    if (!ctx || max_samples < 1 || max_samples > 65536) return IRM_ERR_INVALID_ARG;
+    profile_drop(ctx);
+    ctx->prof_events = new (std::nothrow) hipEvent_t[2 * (size_t)max_samples]();
+    if (!ctx->prof_events) return IRM_ERR_DEVICE;
+    ctx->prof_cap = max_samples;
+    for (uint32_t k = 0; k < 2 * max_samples; ++k) {
+        if (hipEventCreate(&ctx->prof_events[k]) != hipSuccess) {
+            (void)hipGetLastError();
+            profile_drop(ctx);
+            return IRM_ERR_DEVICE;
+        }
+    }
+    return IRM_OK;
+}
+
+extern "C" irm_status irm_ctx_profile_end(irm_ctx *ctx, void *stream, float *total_ms, uint32_t *n_samples)
+{
+    if (!ctx || !total_ms || !n_samples) return IRM_ERR_INVALID_ARG;
+    *total_ms = 0.0f;
+    *n_samples = 0;
+    if (!ctx->prof_events) return IRM_OK;
+    irm_status st = IRM_OK;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) st = IRM_ERR_DEVICE;
+    double sum = 0.0;
+    for (uint32_t k = 0; k < ctx->prof_n && st == IRM_OK; ++k) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ctx->prof_events[2 * k], ctx->prof_events[2 * k + 1]) != hipSuccess)
+            st = IRM_ERR_DEVICE;
+        sum += ms;
+    }
+    if (st == IRM_OK) {
+        *total_ms = (float)sum;
+        *n_samples = ctx->prof_n;
+    } else {
+        (void)hipGetLastError();
+    }
+    profile_drop(ctx);
+    return st;
 }
 
 // ---------------------------------------------------------------- registry --

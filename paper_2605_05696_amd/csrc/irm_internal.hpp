@@ -43,6 +43,9 @@ struct irm_ctx {
     irm_tile *d_tiles;      // [tile_cap]
     float2 *d_trig;         // [chunk_cap][32] (cos, sin) per hit and pair
     uint32_t *d_plan;       // [4]: n_tiles
+    // optional timing of the row kernel
+    hipEvent_t *prof_events; // [2 * prof_cap]
+    uint32_t prof_cap, prof_n;
 };
 
 struct irm_table {

@@ -231,8 +231,14 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     uint64_t max_work = ((uint64_t)(n_slot_tokens / IRM_TILE_ROWS) + hit_capacity) * ctx->cfg.n_layers;
     uint32_t grid = ctx->reattach_grid ? ctx->reattach_grid : ctx->n_cu * 8;
     if (grid > max_work) grid = (uint32_t)(max_work ? max_work : 1);
+    const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap;
+    if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
     hipLaunchKernelGGL(reattach_rows, dim3(grid), dim3(256), 0, s, d_src_layer_ptrs, src_row_stride_bytes,
                        d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows, d_dst_slots, ctx->d_tiles,
                        ctx->d_plan, ctx->d_trig, ctx->cfg.n_layers, ctx->d_err);
+    if (sample) {
+        IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
+        ++ctx->prof_n;
+    }
     return irm_launch_status();
 }
