@@ -123,7 +123,12 @@ irm_status irm_ctx_destroy(irm_ctx *ctx);
 irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
 
 /* Tuning knobs for measurements (launch shapes only; results never change).
- * knob 0: workgroups of the re-attach row kernel (0 = default). */
+ * knob 0: workgroups of the re-attach row kernel (0 = default)
+ * knob 1: c_KV rows per wave and tile (1, 2, 4 or 16)
+ * knob 2: bit 0 = non-temporal loads, bit 1 = non-temporal stores
+ * knob 3: work order, 0 = layer-outer, 1 = layer-inner
+ * knob 4: waves per workgroup (1, 2, 4, 8 or 16); a tile is waves x rows-per-wave rows,
+ *         at least 4 */
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
 /* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples
@@ -134,6 +139,12 @@ irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
  * disables sampling.  Not for use under graph capture. */
 irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples);
 irm_status irm_ctx_profile_end(irm_ctx *ctx, void *stream, float *total_ms, uint32_t *n_samples);
+
+/* Measurement aid: a plain copy of `bytes` (multiple of 16) from d_src to d_dst
+ * with 16-byte accesses, `grid` workgroups of 256 lanes (0 = default).  Its HBM
+ * traffic is known exactly (bytes read + bytes written), which calibrates
+ * hardware counters and gives the copy bandwidth the machine can reach. */
+irm_status irm_calibrate_copy(void *d_dst, const void *d_src, uint64_t bytes, uint32_t grid, void *stream);
 
 /* Registry R: hash -> entry (Alg. 1 "Require", steps 7 and 13), an
  * open-addressing table of n_slots slots in device memory owned by the table. */

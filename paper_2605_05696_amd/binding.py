@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "IRM_OK", 1: "IRM_ERR_INVALID_ARG", 2: "IRM_ERR_CAPACITY", 3:
 IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_CHUNK = 1, 2, 4, 8
 
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
-           "irm_ctx_profile_begin", "irm_ctx_profile_end",
+           "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
            "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach")
 
@@ -64,6 +64,7 @@ def lib():
         L.irm_ctx_tune.argtypes = [vp, u32, u32]
         L.irm_ctx_profile_begin.argtypes = [vp, u32]
         L.irm_ctx_profile_end.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(u32)]
+        L.irm_calibrate_copy.argtypes = [vp, vp, u64, u32, vp]
         L.irm_table_create.argtypes = [vp, u64, ctypes.POINTER(vp)]
         L.irm_table_destroy.argtypes = [vp]
         L.irm_table_insert.argtypes = [vp, vp, vp, u32, vp]
@@ -140,6 +141,16 @@ def irm_ctx_profile_end(ctx, stream=None):
     ms, n = ctypes.c_float(0), ctypes.c_uint32(0)
     _check("irm_ctx_profile_end", lib().irm_ctx_profile_end(ctx, _stream(stream), ctypes.byref(ms), ctypes.byref(n)))
     return ms.value, n.value
+
+
+def irm_calibrate_copy(d_dst, d_src, grid: int = 0, stream=None) -> None:
+    """Plain copy of one byte tensor into another of the same size (known HBM traffic)."""
+    import torch
+    n = d_src.numel() * d_src.element_size()
+    if d_dst.numel() * d_dst.element_size() != n or not d_src.is_contiguous() or not d_dst.is_contiguous():
+        raise TypeError("irm_calibrate_copy: need two contiguous device tensors of equal byte size")
+    _check("irm_calibrate_copy", lib().irm_calibrate_copy(
+        ctypes.c_void_p(d_dst.data_ptr()), ctypes.c_void_p(d_src.data_ptr()), n, grid, _stream(stream)))
 
 
 def irm_table_create(ctx, n_slots: int) -> ctypes.c_void_p:

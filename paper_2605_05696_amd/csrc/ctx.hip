@@ -33,7 +33,11 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     c->cfg = *cfg;
     c->k_bits = k_bits;
     c->chunk_cap = (uint32_t)chunk_cap64;
-    c->tile_cap = (uint32_t)(cfg->max_tokens / IRM_TILE_ROWS + chunk_cap64);
+    c->tile_cap = (uint32_t)(cfg->max_tokens / IRM_TILE_ROWS_MIN + chunk_cap64);
+    c->rows_per_wave = 4;
+    c->block_waves = 4;
+    c->mem_mode = 3;
+    c->layer_inner = 0;
 
     hipDeviceProp_t prop;
     if (hipGetDevice(&c->device) != hipSuccess || hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
@@ -74,6 +78,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     if (hipMemset(c->slab, 0, off) != hipSuccess ||
         hipMemcpy(c->d_gear, cfg->gear, 256 * 4, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(c->d_inv_freq, cfg->inv_freq, IRM_KR_PAIRS * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        irm_chunk_hash_init(c->device) != IRM_OK ||
         hipDeviceSynchronize() != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(c->slab);
@@ -114,6 +119,28 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
     if (knob == 0) {
         if (value > (1u << 20)) return IRM_ERR_INVALID_ARG;
         ctx->reattach_grid = value;
+        return IRM_OK;
+    }
+    if (knob == 1) {
+        if (value != 1 && value != 2 && value != 4 && value != 16) return IRM_ERR_INVALID_ARG;
+        if (value * ctx->block_waves < IRM_TILE_ROWS_MIN) return IRM_ERR_INVALID_ARG;
+        ctx->rows_per_wave = value;
+        return IRM_OK;
+    }
+    if (knob == 2) {
+        if (value > 3) return IRM_ERR_INVALID_ARG;
+        ctx->mem_mode = value;
+        return IRM_OK;
+    }
+    if (knob == 4) {
+        if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return IRM_ERR_INVALID_ARG;
+        if (value * ctx->rows_per_wave < IRM_TILE_ROWS_MIN) return IRM_ERR_INVALID_ARG;
+        ctx->block_waves = value;
+        return IRM_OK;
+    }
+    if (knob == 3) {
+        if (value > 1) return IRM_ERR_INVALID_ARG;
+        ctx->layer_inner = value;
         return IRM_OK;
     }
     return IRM_ERR_INVALID_ARG;

@@ -9,13 +9,13 @@
 #define IRM_ROW_BYTES 1152u     // 576 bf16
 #define IRM_CKV_BYTES 1024u     // 512 bf16
 #define IRM_KR_BYTES 128u       // 64 bf16
-#define IRM_TILE_ROWS 64u       // rows of one re-attach tile
+#define IRM_TILE_ROWS_MIN 4u    // smallest tile of the re-attach row kernel (sizes the tile list)
 #define IRM_WAVE 64
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// One tile of the re-attach row kernel: up to IRM_TILE_ROWS consecutive rows of one hit.
+// One tile of the re-attach row kernel: up to tile_rows consecutive rows of one hit.
 struct irm_tile {
     uint32_t src_row0;
     uint32_t dst_tok0;
@@ -29,7 +29,11 @@ struct irm_ctx {
     uint32_t k_bits;        // popcount(mask)
     uint32_t chunk_cap;     // max_tokens / min_chunk + max_requests
     uint32_t tile_cap;      // max_tokens / IRM_TILE_ROWS + chunk_cap
-    uint32_t reattach_grid; // tuning knob 0
+    uint32_t reattach_grid; // tuning knob 0: workgroups of the row kernel, 0 = default
+    uint32_t rows_per_wave; // knob 1: 4, 8 or 16 c_KV rows per wave and tile
+    uint32_t block_waves;   // knob 4: 4, 8 or 16 waves per workgroup (tile = waves * rows_per_wave rows)
+    uint32_t mem_mode;      // knob 2: bit 0 non-temporal loads, bit 1 non-temporal stores
+    uint32_t layer_inner;   // knob 3: 0 = layer-outer work order, 1 = layer-inner
     uint32_t n_cu;
     // one device slab, carved up below
     void *slab;
@@ -56,6 +60,9 @@ struct irm_table {
     uint32_t *d_owner;      // [n_slots + 1], rank of the winning offer, 0xFFFFFFFF = none
     irm_entry *d_vals;      // [n_slots + 1]
 };
+
+// uploads the fingerprint kernel's constant table to the current device (idempotent)
+irm_status irm_chunk_hash_init(int device);
 
 #define IRM_HIP_TRY(expr)                      \
     do {                                       \

@@ -23,8 +23,8 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
                                                      uint32_t hit_capacity, const float *__restrict__ inv_freq,
                                                      uint64_t src_rows, uint64_t n_slot_tokens,
                                                      float2 *__restrict__ trig, irm_tile *__restrict__ tiles,
-                                                     uint32_t tile_cap, uint32_t *__restrict__ plan,
-                                                     uint32_t *err)
+                                                     uint32_t tile_cap, uint32_t tile_rows,
+                                                     uint32_t *__restrict__ plan, uint32_t *err)
 {
     uint32_t n_hits = *n_hits_p;
     if (n_hits > hit_capacity) {
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
         }
     }
     if (blockIdx.x != 0) return;
-    // tiles: exclusive scan of ceil(len / 64) over the hits, in order
+    // tiles: exclusive scan of ceil(len / tile_rows) over the hits, in order
     __shared__ uint32_t lds[17];
     uint32_t carry = 0;
     for (uint32_t h0 = 0; h0 < n_hits; h0 += blockDim.x) {
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
             hit = hits[h];
             const bool ok = (uint64_t)hit.src_row + hit.len <= src_rows &&
                             (uint64_t)hit.dst_tok + hit.len <= n_slot_tokens;
-            if (ok) nt = (hit.len + IRM_TILE_ROWS - 1) / IRM_TILE_ROWS;
+            if (ok) nt = (hit.len + tile_rows - 1) / tile_rows;
             else atomicOr(err, IRM_FLAG_ROW_RANGE);
         }
         uint32_t total;
@@ -71,11 +71,11 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
                 atomicOr(err, IRM_FLAG_CHUNK_OVERFLOW);
                 break;
             }
-            const uint32_t done = k * IRM_TILE_ROWS;
+            const uint32_t done = k * tile_rows;
             irm_tile tile;
             tile.src_row0 = hit.src_row + done;
             tile.dst_tok0 = hit.dst_tok + done;
-            tile.n_rows = hit.len - done < IRM_TILE_ROWS ? hit.len - done : IRM_TILE_ROWS;
+            tile.n_rows = hit.len - done < tile_rows ? hit.len - done : tile_rows;
             tile.hit = h;
             tiles[t] = tile;
         }
@@ -109,49 +109,72 @@ __device__ __forceinline__ void rotate_word(uint32_t wa, uint32_t wb, float2 cs0
     ob = f32_to_bf16(rb0) | (f32_to_bf16(rb1) << 16);
 }
 
-template <bool FULL>
+template <bool NT>
+__device__ __forceinline__ u32x4 ld16(const u32x4 *p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st16(u32x4 v, u32x4 *p)
+{
+    if (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// One tile: up to WAVES * RPW rows.  Wave w moves the c_KV of rows [w*RPW, (w+1)*RPW)
+// and rotates the k_r of rows [16w, 16w+16) (four lanes per row).  slot[q] holds the
+// destination row of tile row 64q + lane (-1: absent or unusable).
+template <int WAVES, int RPW, bool FULL, bool NT_LD, bool NT_ST>
 __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, uint64_t src_stride,
                                               char *__restrict__ dbase, uint64_t dst_stride,
-                                              uint64_t dst_rows, int32_t slot, uint32_t n_rows,
-                                              const float2 *__restrict__ trig_hit, uint32_t wave,
-                                              uint32_t lane, uint32_t *err)
+                                              const int32_t (&slot)[(WAVES * RPW + 63) / 64],
+                                              uint32_t n_rows, const float2 *__restrict__ trig_hit,
+                                              uint32_t wave, uint32_t lane)
 {
-    constexpr int RPW = IRM_TILE_ROWS / 4;            // rows per wave
+    constexpr int TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
     const uint32_t row0 = wave * RPW;
     // c_KV: issue every load of this wave's rows before the first store
     u32x4 v[RPW];
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const uint32_t r = row0 + i;
-        if (FULL || r < n_rows)
-            v[i] = __builtin_nontemporal_load((const u32x4 *)(sbase + (uint64_t)r * src_stride) + lane);
+        if (FULL || r < n_rows) v[i] = ld16<NT_LD>((const u32x4 *)(sbase + (uint64_t)r * src_stride) + lane);
     }
     // k_r: lane (rr, j) owns pairs 8j .. 8j+7 of row rr
-    const uint32_t rr = row0 + (lane >> 2), j = lane & 3;
-    const bool kr_on = FULL || rr < n_rows;
+    const uint32_t rr = wave * 16 + (lane >> 2), j = lane & 3;
+    const bool kr_on = rr < n_rows;                   // n_rows <= TILE
     u32x4 ka = {0, 0, 0, 0}, kb = {0, 0, 0, 0};
     f32x4 t0 = {1, 0, 1, 0}, t1 = t0, t2 = t0, t3 = t0;
     if (kr_on) {
         const u32x4 *kr = (const u32x4 *)(sbase + (uint64_t)rr * src_stride + IRM_CKV_BYTES);
-        ka = __builtin_nontemporal_load(kr + j);
-        kb = __builtin_nontemporal_load(kr + 4 + j);
+        ka = ld16<NT_LD>(kr + j);
+        kb = ld16<NT_LD>(kr + 4 + j);
         const f32x4 *tp = (const f32x4 *)(trig_hit + 8 * j);
         t0 = tp[0];
         t1 = tp[1];
         t2 = tp[2];
         t3 = tp[3];
     }
-    const int32_t kr_slot = __shfl(slot, (int)rr);
+    // rows 16w .. 16w+15 all lie in slot word (16w)/64 = w/4
+    int32_t kr_slot = -1;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int32_t cand = __shfl(slot[q], (int)(rr & 63));
+        if ((wave >> 2) == (uint32_t)q) kr_slot = cand;
+    }
 #pragma unroll
     for (int i = 0; i < RPW; ++i) {
         const uint32_t r = row0 + i;
         if (FULL || r < n_rows) {
-            const int32_t s = __builtin_amdgcn_readlane(slot, (int)r);
-            if ((uint64_t)(uint32_t)s < dst_rows && s >= 0)
-                __builtin_nontemporal_store(v[i], (u32x4 *)(dbase + (uint64_t)(uint32_t)s * dst_stride) + lane);
+            int32_t s = -1;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                if ((r >> 6) == (uint32_t)q) s = __builtin_amdgcn_readlane(slot[q], (int)(r & 63));
+            if (s >= 0) st16<NT_ST>(v[i], (u32x4 *)(dbase + (uint64_t)(uint32_t)s * dst_stride) + lane);
         }
     }
-    if (kr_on && kr_slot >= 0 && (uint64_t)(uint32_t)kr_slot < dst_rows) {
+    if (kr_on && kr_slot >= 0) {
         uint32_t a0, a1, a2, a3, b0, b1, b2, b3;
         rotate_word(ka.x, kb.x, make_float2(t0.x, t0.y), make_float2(t0.z, t0.w), a0, b0);
         rotate_word(ka.y, kb.y, make_float2(t1.x, t1.y), make_float2(t1.z, t1.w), a1, b1);
@@ -159,28 +182,34 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
         rotate_word(ka.w, kb.w, make_float2(t3.x, t3.y), make_float2(t3.z, t3.w), a3, b3);
         const u32x4 oa = {a0, a1, a2, a3}, ob = {b0, b1, b2, b3};
         u32x4 *out = (u32x4 *)(dbase + (uint64_t)(uint32_t)kr_slot * dst_stride + IRM_CKV_BYTES);
-        __builtin_nontemporal_store(oa, out + j);
-        __builtin_nontemporal_store(ob, out + 4 + j);
+        st16<NT_ST>(oa, out + j);
+        st16<NT_ST>(ob, out + 4 + j);
     }
-    (void)err;
 }
 
-__global__ __launch_bounds__(256) void reattach_rows(const void *const *__restrict__ src_ptrs,
-                                                     uint64_t src_stride, void *const *__restrict__ dst_ptrs,
-                                                     uint64_t dst_stride, uint64_t dst_rows,
-                                                     const int32_t *__restrict__ dst_slots,
-                                                     const irm_tile *__restrict__ tiles,
-                                                     const uint32_t *__restrict__ plan,
-                                                     const float2 *__restrict__ trig, uint32_t n_layers,
-                                                     uint32_t *err)
+// Work item t of n_tiles * n_layers: layer-outer (all tiles of layer 0, then layer 1, ...)
+// or layer-inner (all layers of tile 0, then tile 1, ...).
+template <int WAVES, int RPW, bool NT_LD, bool NT_ST>
+__global__ __launch_bounds__(WAVES * 64) void reattach_rows(
+    const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ dst_ptrs,
+    uint64_t dst_stride, uint64_t dst_rows, const int32_t *__restrict__ dst_slots,
+    const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
+    uint32_t n_layers, uint32_t layer_inner, uint32_t *err)
 {
+    constexpr uint32_t TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
     const uint32_t n_tiles = plan[0];
     const uint64_t total = (uint64_t)n_tiles * n_layers;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = irm_wave_id();
     for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
-        const uint32_t layer = (uint32_t)(t / n_tiles);
-        const uint32_t ti = (uint32_t)(t - (uint64_t)layer * n_tiles);
+        uint32_t layer, ti;
+        if (layer_inner) {
+            ti = (uint32_t)(t / n_layers);
+            layer = (uint32_t)(t - (uint64_t)ti * n_layers);
+        } else {
+            layer = (uint32_t)(t / n_tiles);
+            ti = (uint32_t)(t - (uint64_t)layer * n_tiles);
+        }
         const irm_tile *tp = tiles + ti;
         const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
         const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
@@ -188,21 +217,61 @@ __global__ __launch_bounds__(256) void reattach_rows(const void *const *__restri
         const uint32_t hit = __builtin_amdgcn_readfirstlane(tp->hit);
         const char *sbase = (const char *)src_ptrs[layer] + (uint64_t)src_row0 * src_stride;
         char *dbase = (char *)dst_ptrs[layer];
-        int32_t slot = -1;
-        if (lane < n_rows) {
-            slot = dst_slots[(uint64_t)dst_tok0 + lane];
-            if (slot < 0 || (uint64_t)(uint32_t)slot >= dst_rows) {
-                atomicOr(err, IRM_FLAG_ROW_RANGE);
-                slot = -1;
+        int32_t slot[NQ];                               // -1: row absent or its slot unusable
+#pragma unroll
+        for (uint32_t q = 0; q < NQ; ++q) {
+            const uint32_t r = 64 * q + lane;
+            slot[q] = -1;
+            if (r < n_rows) {
+                const int32_t sl = dst_slots[(uint64_t)dst_tok0 + r];
+                if (sl < 0 || (uint64_t)(uint32_t)sl >= dst_rows) atomicOr(err, IRM_FLAG_ROW_RANGE);
+                else slot[q] = sl;
             }
         }
         const float2 *trig_hit = trig + (uint64_t)hit * IRM_KR_PAIRS;
-        if (n_rows == IRM_TILE_ROWS)
-            reattach_tile<true>(sbase, src_stride, dbase, dst_stride, dst_rows, slot, n_rows, trig_hit, wave,
-                                lane, err);
+        if (n_rows == TILE)
+            reattach_tile<WAVES, RPW, true, NT_LD, NT_ST>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
+                                                          trig_hit, wave, lane);
         else
-            reattach_tile<false>(sbase, src_stride, dbase, dst_stride, dst_rows, slot, n_rows, trig_hit, wave,
-                                 lane, err);
+            reattach_tile<WAVES, RPW, false, NT_LD, NT_ST>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
+                                                           trig_hit, wave, lane);
+    }
+}
+
+typedef void (*rows_kernel_t)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t,
+                              const int32_t *, const irm_tile *, const uint32_t *, const float2 *, uint32_t,
+                              uint32_t, uint32_t *);
+
+template <int WAVES, int RPW>
+static rows_kernel_t pick_mode(uint32_t mode)
+{
+    switch (mode & 3u) {
+    case 0: return reattach_rows<WAVES, RPW, false, false>;
+    case 1: return reattach_rows<WAVES, RPW, true, false>;
+    case 2: return reattach_rows<WAVES, RPW, false, true>;
+    default: return reattach_rows<WAVES, RPW, true, true>;
+    }
+}
+
+template <int WAVES>
+static rows_kernel_t pick_rpw(uint32_t rpw, uint32_t mode)
+{
+    switch (rpw) {
+    case 1: return pick_mode<WAVES, 1>(mode);
+    case 2: return pick_mode<WAVES, 2>(mode);
+    case 4: return pick_mode<WAVES, 4>(mode);
+    default: return pick_mode<WAVES, 16>(mode);
+    }
+}
+
+static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode)
+{
+    switch (waves) {
+    case 1: return pick_rpw<1>(rpw, mode);
+    case 2: return pick_rpw<2>(rpw, mode);
+    case 4: return pick_rpw<4>(rpw, mode);
+    case 8: return pick_rpw<8>(rpw, mode);
+    default: return pick_rpw<16>(rpw, mode);
     }
 }
 
@@ -224,18 +293,23 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     if (hit_capacity < 1) return IRM_ERR_INVALID_ARG;
     if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
+    const uint32_t tile_rows = ctx->block_waves * ctx->rows_per_wave;
     const uint32_t plan_blocks = (uint32_t)(((uint64_t)hit_capacity * IRM_KR_PAIRS + 255) / 256);
     hipLaunchKernelGGL(reattach_plan, dim3(plan_blocks), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
                        ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles, ctx->tile_cap,
-                       ctx->d_plan, ctx->d_err);
-    uint64_t max_work = ((uint64_t)(n_slot_tokens / IRM_TILE_ROWS) + hit_capacity) * ctx->cfg.n_layers;
-    uint32_t grid = ctx->reattach_grid ? ctx->reattach_grid : ctx->n_cu * 8;
+                       tile_rows, ctx->d_plan, ctx->d_err);
+    uint64_t max_work = ((uint64_t)(n_slot_tokens / tile_rows) + hit_capacity) * ctx->cfg.n_layers;
+    // default: one workgroup per tile while that fits a launch; the hardware dispatcher
+    // then balances the load (measured faster than a persistent grid of resident size)
+    uint32_t grid = ctx->reattach_grid ? ctx->reattach_grid : (1u << 20);
     if (grid > max_work) grid = (uint32_t)(max_work ? max_work : 1);
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(reattach_rows, dim3(grid), dim3(256), 0, s, d_src_layer_ptrs, src_row_stride_bytes,
-                       d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows, d_dst_slots, ctx->d_tiles,
-                       ctx->d_plan, ctx->d_trig, ctx->cfg.n_layers, ctx->d_err);
+    hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode), dim3(grid),
+                       dim3(ctx->block_waves * 64), 0, s,
+                       d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
+                       d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->cfg.n_layers,
+                       ctx->layer_inner, ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;

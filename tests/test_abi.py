@@ -21,7 +21,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = declared_functions()
-    assert len(names) >= 13
+    assert len(names) >= 14
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -77,6 +77,7 @@ def test_null_arguments_are_rejected():
     flags = ctypes.c_uint32()
     assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_calibrate_copy(None, None, 0, 0, None) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_profile_begin(None, 4) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_profile_end(None, None, None, None) == B.IRM_ERR_INVALID_ARG
 
