@@ -1,0 +1,123 @@
+"""GPU parity at the full sizes of the five measured configurations, in the launch
+configuration bench.py times (library defaults, contiguous slots, the four calls
+chained on one stream).
+
+Integer stages are compared bit for bit on every token and chunk.  Re-attached
+rows are recomputed by the oracle: all of them for c0, c1 and c3; for c2 and c4
+(tens to hundreds of GB) a seeded sample -- every layer of 256 random hits and
+three layers of every hit's first and last row -- plus checks that hold at any
+size: c_KV of every re-attached row equals its source row bit for bit, pair
+norms of k_r survive the rotation to bf16 rounding, and rows no hit covers keep
+the sentinel.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import irm_oracle as orc
+from paper_2605_05696_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from tests.gpu_util import DEV, Rig, bits, covered_rows, hits_from_dev, verify_reattach
+
+
+@pytest.fixture(autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need an MI355X; deselect with -m 'not gpu'"
+    yield
+    torch.cuda.empty_cache()
+
+
+def check_front(rig):
+    """chunks, fingerprints, lookup: every element against the oracle"""
+    o, buf = rig.o, rig.buf
+    n = int(buf["n_chunks"].item())
+    assert n == len(o["start"])
+    u32 = lambda t: t.cpu().numpy().view(np.uint32)
+    assert np.array_equal(u32(buf["chunk_start"])[:n], o["start"])
+    assert np.array_equal(u32(buf["chunk_len"])[:n], o["len"])
+    assert np.array_equal(u32(buf["req_chunk_offsets"]), o["rco"])
+    assert np.array_equal(buf["chunk_hash"].cpu().numpy().view(np.uint64)[:n], o["hash"])
+    assert np.array_equal(buf["chunk_entry"].cpu().numpy()[:n], o["entry"])
+    n_hits = int(buf["n_hits"].item())
+    assert n_hits == len(o["hits"]) and int(buf["hit_tokens"].item()) == o["hit_tokens"]
+    g = hits_from_dev(buf["hits"], n_hits)
+    for f in ("src_row", "dst_tok", "len", "delta"):
+        assert np.array_equal(getattr(g, f), getattr(o["hits"], f)), f
+
+
+def check_properties(rig, layers):
+    """size-independent checks on whole layers, computed on the device"""
+    w, hits = rig.w, rig.o["hits"]
+    lens = hits.len.astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    within = np.arange(off[-1]) - np.repeat(off[:-1], lens)
+    src_idx = torch.from_numpy(np.repeat(hits.src_row.astype(np.int64), lens) + within).to(DEV)
+    dst_idx = torch.from_numpy(w.dst_slots[np.repeat(hits.dst_tok.astype(np.int64), lens) + within]
+                               .astype(np.int64)).to(DEV)
+    untouched = torch.from_numpy(np.nonzero(~covered_rows(w, hits))[0]).to(DEV)
+    step = 1 << 18
+    for l in layers:
+        for a in range(0, len(src_idx), step):
+            s = rig.src[l].index_select(0, src_idx[a:a + step])
+            d = rig.dst[l].index_select(0, dst_idx[a:a + step])
+            assert torch.equal(s[:, :512].view(torch.int16), d[:, :512].view(torch.int16)), f"c_KV layer {l}"
+            ns = torch.hypot(s[:, 512:544].float(), s[:, 544:].float())
+            nd = torch.hypot(d[:, 512:544].float(), d[:, 544:].float())
+            assert torch.all((nd - ns).abs() <= ns * 2.0 ** -7 + 1e-30), f"pair norms layer {l}"
+        rest = rig.dst[l].index_select(0, untouched)
+        assert torch.all(rest.view(torch.int16) == wl.SENTINEL_BF16), f"untouched rows layer {l}"
+
+
+@pytest.mark.parametrize("name", ["c0", "c1", "c3"])
+def test_full_size_all_rows(name):
+    w = wl.make_workload(name, orc.cdc_chunk, size="full")
+    rig = Rig(w)
+    try:
+        rig.serve()
+        assert rig.s.error_flags() == 0
+        check_front(rig)
+        hits = rig.o["hits"]
+        L = w.n_layers
+        total = 0
+        for l0 in range(0, L, 9):                              # a few layers at a time bounds host memory
+            stats = verify_reattach(w, hits, rig.src, rig.dst, layers=range(l0, min(L, l0 + 9)), what=w.name)
+            total += stats["rows"]
+        assert total == rig.o["hit_tokens"] * L
+        check_properties(rig, range(L))
+        if name == "c3":
+            assert np.abs(hits.delta).max() > 90000 and np.abs(hits.delta).max() <= 100000
+        if name == "c1":
+            assert 0.75 < rig.o["hit_tokens"] / len(w.tokens) <= 0.80
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("name", ["c2", "c4"])
+def test_full_size_sampled(name):
+    w = wl.make_workload(name, orc.cdc_chunk, size="full")
+    rig = Rig(w)
+    try:
+        rig.serve()
+        assert rig.s.error_flags() == 0
+        check_front(rig)
+        hits = rig.o["hits"]
+        L = w.n_layers
+        rng = np.random.default_rng(4000 + wl.CONFIG_NAMES.index(name))
+        sample = np.sort(rng.choice(len(hits), size=256, replace=False))
+        stats = verify_reattach(w, hits, rig.src, rig.dst, hit_sel=sample, what=f"{w.name} sample")
+        assert stats["rows"] == int(hits.len[sample].sum()) * L
+        # first and last row of every hit, three layers
+        ends = orc.Hits(np.concatenate([hits.src_row, hits.src_row + hits.len - 1]),
+                        np.concatenate([hits.dst_tok, hits.dst_tok + hits.len - 1]),
+                        np.ones(2 * len(hits), np.uint32), np.concatenate([hits.delta, hits.delta]))
+        verify_reattach(w, ends, rig.src, rig.dst, layers=[0, L // 2, L - 1], what=f"{w.name} ends")
+        check_properties(rig, [0, L // 2, L - 1] if name == "c4" else range(0, L, 4))
+        if name == "c4":
+            assert len(rig.o["reg"]["hash"]) == 4194304 and w.table_slots == int(np.ceil(4194304 / 0.7))
+        if name == "c2":
+            assert np.abs(hits.delta).max() < 16384 and w.n_req == 64
+    finally:
+        rig.close()
