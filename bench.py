@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--slots", default="contiguous", choices=["contiguous", "permuted"])
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the row kernel (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", type=int, default=0, metavar="N",
+                    help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
+                         "known-traffic yardstick for hardware counters")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle baseline")
     args = ap.parse_args()
 
@@ -113,6 +116,13 @@ def main() -> int:
             assert flags == 0, f"device error flags {flags:#x}"
         for k in range(args.warmup):
             step(k % n_var)
+        if args.calibrate:
+            a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+            b = torch.empty_like(a)
+            for _ in range(args.calibrate):
+                B.irm_calibrate_copy(b, a, 0, stream)
+            stream.synchronize()
+            del a, b
         for s in sessions:
             B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1)
         torch.cuda.synchronize()

@@ -1,0 +1,44 @@
+"""Reduce rocprofv3 --pmc CSV output to per-kernel averages.
+
+usage: python -m paper_2605_05696_amd.pmc_summary <counter_collection.csv> [<more.csv> ...]
+
+Prints, per counter and kernel, the number of dispatches and the mean counter
+value per dispatch.  FETCH_SIZE and WRITE_SIZE are reported by the hardware in
+KiB; the plain copy kernel ``calibrate_copy`` moves a known number of bytes, so
+the ratio (known bytes) / (counted KiB * 1024) calibrates the counters.
+"""
+from __future__ import annotations
+
+import csv
+import sys
+from collections import defaultdict
+
+
+def summarise(paths):
+    acc = defaultdict(lambda: [0, 0.0])
+    for path in paths:
+        with open(path, newline="") as f:
+            for row in csv.DictReader(f):
+                name = row.get("Kernel_Name") or row.get("kernel_name") or ""
+                counter = row.get("Counter_Name") or row.get("counter_name") or ""
+                value = float(row.get("Counter_Value") or row.get("counter_value") or 0.0)
+                short = name.split("(")[0].replace("void ", "")
+                a = acc[(counter, short)]
+                a[0] += 1
+                a[1] += value
+    return {k: (n, total / n) for k, (n, total) in acc.items() if n}
+
+
+def main(argv):
+    if len(argv) < 2:
+        print(__doc__)
+        return 2
+    table = summarise(argv[1:])
+    print(f"{'counter':14s} {'kernel':44s} {'dispatches':>10s} {'mean per dispatch':>20s}")
+    for (counter, kernel), (n, mean) in sorted(table.items()):
+        print(f"{counter:14s} {kernel[:44]:44s} {n:10d} {mean:20.1f}")
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv))
