@@ -201,6 +201,7 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
     const uint64_t total = (uint64_t)n_tiles * n_layers;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = irm_wave_id();
+#pragma nounroll
     for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
         uint32_t layer, ti;
         if (layer_inner) {
@@ -260,6 +261,7 @@ static rows_kernel_t pick_rpw(uint32_t rpw, uint32_t mode)
     case 1: return pick_mode<WAVES, 1>(mode);
     case 2: return pick_mode<WAVES, 2>(mode);
     case 4: return pick_mode<WAVES, 4>(mode);
+    case 8: return pick_mode<WAVES, 8>(mode);
     default: return pick_mode<WAVES, 16>(mode);
     }
 }
