@@ -138,6 +138,11 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
         ctx->block_waves = value;
         return IRM_OK;
     }
+    if (knob == 5) {
+        if (value > 1) return IRM_ERR_INVALID_ARG;
+        ctx->cdc_serial = value;
+        return IRM_OK;
+    }
     if (knob == 3) {
         if (value > 1) return IRM_ERR_INVALID_ARG;
         ctx->layer_inner = value;

@@ -31,10 +31,11 @@ def small(name, **kw):
 
 # ------------------------------------------------------------ chunk + hash --
 
-def gpu_chunks(tokens, req_offsets, gear, mask, lo, hi):
+def gpu_chunks(tokens, req_offsets, gear, mask, lo, hi, serial=False):
     n_req = len(req_offsets) - 1
     s = Session(gear, mask, lo, hi, 32, 1, wl.inv_freq_plain(), max(len(tokens), 1), max(n_req, 1), DEV)
     try:
+        B.irm_ctx_tune(s.ctx, 5, 1 if serial else 0)
         out = s.chunk_host(tokens, req_offsets)
         assert s.error_flags() == 0
     finally:
@@ -52,13 +53,15 @@ def test_cdc_and_hash_bit_exact_small_configs(name):
         assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
 
 
-def test_cdc_ragged_requests_and_edge_lengths():
+@pytest.mark.parametrize("serial", [False, True])
+def test_cdc_ragged_requests_and_edge_lengths(serial):
+    """Both cut-selection paths (pointer doubling over candidates, serial bitmap walk)."""
     rng = np.random.default_rng(17)
     gear = wl.gear_table()
-    lens = [1, 0, 63, 64, 65, 127, 128, 1023, 1024, 1025, 2048, 0, 5000, 7, 300000, 1]
+    lens = [1, 0, 63, 64, 65, 127, 128, 1023, 1024, 1025, 2048, 0, 5000, 7, 300000, 1, 1300000, 3]
     tokens = rng.integers(0, 102400, size=sum(lens)).astype(np.int32)
     off = np.concatenate([[0], np.cumsum(lens)]).astype(np.uint32)
-    st, ln, rco, ch = gpu_chunks(tokens, off, gear, 0xFF, 64, 1024)
+    st, ln, rco, ch = gpu_chunks(tokens, off, gear, 0xFF, 64, 1024, serial=serial)
     o_st, o_ln, o_rco = orc.cdc_chunk(tokens, off, gear, 0xFF, 64, 1024)
     assert np.array_equal(rco, o_rco) and np.array_equal(st, o_st) and np.array_equal(ln, o_ln)
     assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
@@ -67,13 +70,14 @@ def test_cdc_ragged_requests_and_edge_lengths():
 @pytest.mark.parametrize("mask,lo,hi", [(0x7F, 32, 512), (0x1, 1, 3), (0xFFFF, 16, 100), (0x0, 4, 9),
                                         (0xF, 4, 4), (0xFFFFF, 64, 65536), (0xFF, 64, 1024),
                                         (0xFFFFFFFF, 32, 40)])
-def test_cdc_other_masks_and_clamps(mask, lo, hi):
+@pytest.mark.parametrize("serial", [False, True])
+def test_cdc_other_masks_and_clamps(mask, lo, hi, serial):
     rng = np.random.default_rng(mask % 1000 + lo)
     gear = wl.gear_table(seed=99)
     n = 200000 if hi > 1024 else 30000
     tokens = rng.integers(-2**31, 2**31, size=n, dtype=np.int64).astype(np.int32)
     off = np.array([0, 11, n // 3, n], np.uint32)
-    st, ln, rco, ch = gpu_chunks(tokens, off, gear, mask, lo, hi)
+    st, ln, rco, ch = gpu_chunks(tokens, off, gear, mask, lo, hi, serial=serial)
     o_st, o_ln, o_rco = orc.cdc_chunk(tokens, off, gear, mask, lo, hi)
     assert np.array_equal(rco, o_rco) and np.array_equal(st, o_st) and np.array_equal(ln, o_ln)
     assert np.array_equal(ch, orc.chunk_hash(tokens, o_st, o_ln))
