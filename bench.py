@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
                          "known-traffic yardstick for hardware counters")
+    ap.add_argument("--kernel-timing", type=int, default=4, metavar="E",
+                    help="HIP events around every E-th row-kernel launch of each batch variant inside the "
+                         "timed region (0 = none, no roofline)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle baseline")
     args = ap.parse_args()
 
@@ -124,7 +127,8 @@ def main() -> int:
             stream.synchronize()
             del a, b
         for s in sessions:
-            B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1)
+            if args.kernel_timing:
+                B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1, args.kernel_timing)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(args.steps):

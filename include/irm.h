@@ -134,12 +134,12 @@ irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
 /* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples
- * pairs of HIP events; while enabled, every irm_reattach records one pair
- * around its row kernel on the caller's stream (calls past max_samples are not
- * sampled).  irm_ctx_profile_end waits for the stream, returns the summed
+ * pairs of HIP events; while enabled, every `every`-th irm_reattach (the first
+ * one included) records one pair around its row kernel on the caller's stream
+ * (calls past max_samples are not sampled).  irm_ctx_profile_end waits for the stream, returns the summed
  * elapsed milliseconds and the number of samples, destroys the events and
  * disables sampling.  Not for use under graph capture. */
-irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples);
+irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples, uint32_t every);
 irm_status irm_ctx_profile_end(irm_ctx *ctx, void *stream, float *total_ms, uint32_t *n_samples);
 
 /* Measurement aid: a plain copy of `bytes` (multiple of 16) from d_src to d_dst

@@ -62,7 +62,7 @@ def lib():
         L.irm_ctx_destroy.argtypes = [vp]
         L.irm_ctx_error_flags.argtypes = [vp, vp, ctypes.POINTER(u32)]
         L.irm_ctx_tune.argtypes = [vp, u32, u32]
-        L.irm_ctx_profile_begin.argtypes = [vp, u32]
+        L.irm_ctx_profile_begin.argtypes = [vp, u32, u32]
         L.irm_ctx_profile_end.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(u32)]
         L.irm_calibrate_copy.argtypes = [vp, vp, u64, u32, vp]
         L.irm_table_create.argtypes = [vp, u64, ctypes.POINTER(vp)]
@@ -132,8 +132,8 @@ def irm_ctx_tune(ctx, knob: int, value: int) -> None:
     _check("irm_ctx_tune", lib().irm_ctx_tune(ctx, knob, value))
 
 
-def irm_ctx_profile_begin(ctx, max_samples: int) -> None:
-    _check("irm_ctx_profile_begin", lib().irm_ctx_profile_begin(ctx, max_samples))
+def irm_ctx_profile_begin(ctx, max_samples: int, every: int = 1) -> None:
+    _check("irm_ctx_profile_begin", lib().irm_ctx_profile_begin(ctx, max_samples, every))
 
 
 def irm_ctx_profile_end(ctx, stream=None):

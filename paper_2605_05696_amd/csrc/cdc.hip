@@ -9,8 +9,8 @@
 // computed independently (kernel 1).  What stays sequential by definition is the
 // greedy choice of cuts under the min/max clamps (kernel 2): it is resolved by
 // pointer doubling over the candidate positions, with a serial walk of the bitmap
-// as the fallback for requests with very many candidates.  Kernel 3 turns the
-// per-request lists into the CSR output.
+// as the fallback for requests with very many candidates.  The workgroup that
+// finishes last turns the per-request lists into the CSR output.
 #include "irm_internal.hpp"
 
 #define CDC_SEG_WORDS 4096u   // bitmap words staged in LDS per round: 262,144 tokens, 32 KB
@@ -320,52 +320,16 @@ __device__ __forceinline__ bool select_jump(const uint64_t *__restrict__ bitmap,
     return true;
 }
 
-// ---- kernel 2: greedy cut selection, one workgroup per request -------------
-__global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ bitmap,
-                                                  const uint32_t *__restrict__ req_offsets,
-                                                  uint64_t n_tokens, uint32_t min_chunk, uint32_t max_chunk,
-                                                  uint32_t *__restrict__ stage_start,
-                                                  uint32_t *__restrict__ stage_len,
-                                                  uint32_t *__restrict__ req_count, uint32_t stage_cap,
-                                                  uint32_t force_serial, uint32_t *err)
+// ---- per-request lists -> CSR (run by the workgroup that finishes last) ------
+__device__ __forceinline__ void cdc_compact(const uint32_t *__restrict__ req_offsets, uint32_t n_req,
+                                            uint32_t min_chunk, const uint32_t *stage_start,
+                                            const uint32_t *stage_len, const uint32_t *req_count,
+                                            uint32_t stage_cap, uint32_t *__restrict__ chunk_start,
+                                            uint32_t *__restrict__ chunk_len,
+                                            uint32_t *__restrict__ req_chunk_offsets,
+                                            uint32_t *__restrict__ n_chunks, uint32_t chunk_capacity,
+                                            uint32_t *lds, uint32_t *err)
 {
-    __shared__ union {
-        uint64_t seg[CDC_SEG_WORDS];
-        cdc_jump_mem g;
-    } sm;
-    __shared__ uint32_t scan_lds[17];
-
-    const uint32_t r = blockIdx.x;
-    const uint32_t begin = req_offsets[r], end = req_offsets[r + 1];
-    if (begin > end || (uint64_t)end > n_tokens) {     // malformed offsets: emit nothing
-        if (threadIdx.x == 0) {
-            req_count[r] = 0;
-            atomicOr(err, IRM_FLAG_BAD_CHUNK);
-        }
-        return;
-    }
-    const uint32_t base = begin / min_chunk + r;       // this request's staging area
-    if (!force_serial && select_jump(bitmap, &sm.g, scan_lds, r, begin, end, base, min_chunk, max_chunk,
-                                     stage_start, stage_len, req_count, stage_cap, err))
-        return;
-    __syncthreads();
-    select_serial(bitmap, sm.seg, r, begin, end, base, min_chunk, max_chunk, stage_start, stage_len,
-                  req_count, stage_cap, err);
-}
-
-// ---- kernel 3: per-request lists -> CSR -------------------------------------
-__global__ __launch_bounds__(1024) void cdc_compact(const uint32_t *__restrict__ req_offsets, uint32_t n_req,
-                                                    uint32_t min_chunk,
-                                                    const uint32_t *__restrict__ stage_start,
-                                                    const uint32_t *__restrict__ stage_len,
-                                                    const uint32_t *__restrict__ req_count, uint32_t stage_cap,
-                                                    uint32_t *__restrict__ chunk_start,
-                                                    uint32_t *__restrict__ chunk_len,
-                                                    uint32_t *__restrict__ req_chunk_offsets,
-                                                    uint32_t *__restrict__ n_chunks, uint32_t chunk_capacity,
-                                                    uint32_t *err)
-{
-    __shared__ uint32_t lds[17];
     __shared__ uint32_t carry_sh;
     if (threadIdx.x == 0) carry_sh = 0;
     __syncthreads();
@@ -404,6 +368,55 @@ __global__ __launch_bounds__(1024) void cdc_compact(const uint32_t *__restrict__
     }
 }
 
+// ---- kernel 2: greedy cut selection, one workgroup per request -------------
+// The workgroup that finishes last (ticket counter in the context, left at zero again)
+// gathers the per-request lists into the caller's CSR arrays.
+__global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ bitmap,
+                                                  const uint32_t *__restrict__ req_offsets, uint32_t n_req,
+                                                  uint64_t n_tokens, uint32_t min_chunk, uint32_t max_chunk,
+                                                  uint32_t *stage_start, uint32_t *stage_len,
+                                                  uint32_t *req_count, uint32_t stage_cap,
+                                                  uint32_t force_serial, uint32_t *__restrict__ chunk_start,
+                                                  uint32_t *__restrict__ chunk_len,
+                                                  uint32_t *__restrict__ req_chunk_offsets,
+                                                  uint32_t *__restrict__ n_chunks, uint32_t chunk_capacity,
+                                                  uint32_t *tickets, uint32_t *err)
+{
+    __shared__ union {
+        uint64_t seg[CDC_SEG_WORDS];
+        cdc_jump_mem g;
+    } sm;
+    __shared__ uint32_t scan_lds[17];
+    __shared__ uint32_t last_sh;
+
+    const uint32_t r = blockIdx.x;
+    const uint32_t begin = req_offsets[r], end = req_offsets[r + 1];
+    if (begin > end || (uint64_t)end > n_tokens) {     // malformed offsets: emit nothing
+        if (threadIdx.x == 0) {
+            req_count[r] = 0;
+            atomicOr(err, IRM_FLAG_BAD_CHUNK);
+        }
+    } else {
+        const uint32_t base = begin / min_chunk + r;   // this request's staging area
+        if (force_serial || !select_jump(bitmap, &sm.g, scan_lds, r, begin, end, base, min_chunk, max_chunk,
+                                         stage_start, stage_len, req_count, stage_cap, err)) {
+            __syncthreads();
+            select_serial(bitmap, sm.seg, r, begin, end, base, min_chunk, max_chunk, stage_start, stage_len,
+                          req_count, stage_cap, err);
+        }
+    }
+    // publish this request's list, then take a ticket
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) last_sh = atomicAdd(tickets, 1u) == n_req - 1 ? 1u : 0u;
+    __syncthreads();
+    if (!last_sh) return;
+    __threadfence();                                   // see every other workgroup's list
+    cdc_compact(req_offsets, n_req, min_chunk, stage_start, stage_len, req_count, stage_cap, chunk_start,
+                chunk_len, req_chunk_offsets, n_chunks, chunk_capacity, scan_lds, err);
+    if (threadIdx.x == 0) *tickets = 0;
+}
+
 extern "C" irm_status irm_cdc_chunk(irm_ctx *ctx, const int32_t *d_tokens, uint64_t n_tokens,
                                     const uint32_t *d_req_offsets, uint32_t n_req,
                                     uint32_t *d_chunk_start, uint32_t *d_chunk_len,
@@ -424,12 +437,9 @@ extern "C" irm_status irm_cdc_chunk(irm_ctx *ctx, const int32_t *d_tokens, uint6
         hipLaunchKernelGGL(cdc_candidates, dim3(blocks), dim3(256), 0, s, d_tokens, n_tokens, ctx->d_gear,
                            c.mask, ctx->k_bits, ctx->d_bitmap);
     }
-    hipLaunchKernelGGL(cdc_select, dim3(n_req), dim3(256), 0, s, ctx->d_bitmap, d_req_offsets, n_tokens,
+    hipLaunchKernelGGL(cdc_select, dim3(n_req), dim3(256), 0, s, ctx->d_bitmap, d_req_offsets, n_req, n_tokens,
                        c.min_chunk, c.max_chunk, ctx->d_stage_start, ctx->d_stage_len, ctx->d_req_count,
-                       ctx->chunk_cap, ctx->cdc_serial, ctx->d_err);
-    hipLaunchKernelGGL(cdc_compact, dim3(1), dim3(1024), 0, s, d_req_offsets, n_req, c.min_chunk,
-                       ctx->d_stage_start, ctx->d_stage_len, ctx->d_req_count, ctx->chunk_cap,
-                       d_chunk_start, d_chunk_len, d_req_chunk_offsets, d_n_chunks, chunk_capacity,
-                       ctx->d_err);
+                       ctx->chunk_cap, ctx->cdc_serial, d_chunk_start, d_chunk_len, d_req_chunk_offsets,
+                       d_n_chunks, chunk_capacity, ctx->d_plan + 1, ctx->d_err);
     return irm_launch_status();
 }

@@ -162,13 +162,15 @@ static void profile_drop(irm_ctx *ctx)
     ctx->prof_cap = ctx->prof_n = 0;
 }
 
-extern "C" irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples)
+extern "C" irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples, uint32_t every)
 {
-    if (!ctx || max_samples < 1 || max_samples > 65536) return IRM_ERR_INVALID_ARG;
+    if (!ctx || max_samples < 1 || max_samples > 65536 || every < 1) return IRM_ERR_INVALID_ARG;
     profile_drop(ctx);
     ctx->prof_events = new (std::nothrow) hipEvent_t[2 * (size_t)max_samples]();
     if (!ctx->prof_events) return IRM_ERR_DEVICE;
     ctx->prof_cap = max_samples;
+    ctx->prof_every = every;
+    ctx->prof_calls = 0;
     for (uint32_t k = 0; k < 2 * max_samples; ++k) {
         if (hipEventCreate(&ctx->prof_events[k]) != hipSuccess) {
             (void)hipGetLastError();

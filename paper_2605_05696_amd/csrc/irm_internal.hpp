@@ -50,7 +50,7 @@ struct irm_ctx {
     uint32_t *d_plan;       // [4]: n_tiles
     // optional timing of the row kernel
     hipEvent_t *prof_events; // [2 * prof_cap]
-    uint32_t prof_cap, prof_n;
+    uint32_t prof_cap, prof_n, prof_every, prof_calls;
 };
 
 struct irm_table {

@@ -18,6 +18,18 @@
 #include "irm_internal.hpp"
 
 // ---- plan --------------------------------------------------------------------
+// tiles a hit is cut into; 0 when it points outside the pools (the hit is skipped)
+__device__ __forceinline__ uint32_t hit_tiles(const irm_hit &hit, uint64_t src_rows, uint64_t n_slot_tokens,
+                                              uint32_t tile_rows)
+{
+    const bool ok = (uint64_t)hit.src_row + hit.len <= src_rows &&
+                    (uint64_t)hit.dst_tok + hit.len <= n_slot_tokens;
+    return ok ? (hit.len + tile_rows - 1) / tile_rows : 0u;
+}
+
+// One lane per (hit, pair): 8 hits per workgroup.  Each workgroup sums the tile counts
+// of all hits in front of its own (independent loads, a block reduction), so the tile
+// list is written by all workgroups at once, 32 lanes per hit.
 __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__ hits,
                                                      const uint32_t *__restrict__ n_hits_p,
                                                      uint32_t hit_capacity, const float *__restrict__ inv_freq,
@@ -26,47 +38,47 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
                                                      uint32_t tile_cap, uint32_t tile_rows,
                                                      uint32_t *__restrict__ plan, uint32_t *err)
 {
+    __shared__ uint32_t lds[17];
+    __shared__ uint32_t local_nt[8];
     uint32_t n_hits = *n_hits_p;
     if (n_hits > hit_capacity) {
         n_hits = hit_capacity;
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(err, IRM_FLAG_CHUNK_OVERFLOW);
     }
-    // (cos, sin) table: one lane per (hit, pair)
-    {
-        const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-        const uint64_t h = gid / IRM_KR_PAIRS;
-        const uint32_t i = (uint32_t)(gid % IRM_KR_PAIRS);
-        if (h < n_hits) {
-            const int32_t delta = hits[h].delta;
-            float2 cs = make_float2(1.0f, 0.0f);          // delta == 0: exact identity
-            if (delta != 0) {
-                const double phi = (double)delta * (double)inv_freq[i];
-                double s, c;
-                sincos(phi, &s, &c);
-                cs = make_float2((float)c, (float)s);
-            }
-            trig[h * IRM_KR_PAIRS + i] = cs;
-        }
+    const uint32_t h0 = blockIdx.x * 8u;                // first hit of this workgroup
+    if (h0 >= n_hits) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) plan[0] = 0;   // no hits at all
+        return;
     }
-    if (blockIdx.x != 0) return;
-    // tiles: exclusive scan of ceil(len / tile_rows) over the hits, in order
-    __shared__ uint32_t lds[17];
-    uint32_t carry = 0;
-    for (uint32_t h0 = 0; h0 < n_hits; h0 += blockDim.x) {
-        const uint32_t h = h0 + threadIdx.x;
-        irm_hit hit = {0u, 0u, 0u, 0};
-        uint32_t nt = 0;
-        if (h < n_hits) {
-            hit = hits[h];
-            const bool ok = (uint64_t)hit.src_row + hit.len <= src_rows &&
-                            (uint64_t)hit.dst_tok + hit.len <= n_slot_tokens;
-            if (ok) nt = (hit.len + tile_rows - 1) / tile_rows;
-            else atomicOr(err, IRM_FLAG_ROW_RANGE);
+    const uint32_t h = h0 + (threadIdx.x >> 5), i = threadIdx.x & 31;
+    irm_hit hit = {0u, 0u, 0u, 0};
+    uint32_t nt = 0;
+    if (h < n_hits) {
+        hit = hits[h];
+        nt = hit_tiles(hit, src_rows, n_slot_tokens, tile_rows);
+        // (cos, sin) of delta * inv_freq[i]
+        float2 cs = make_float2(1.0f, 0.0f);            // delta == 0: exact identity
+        if (hit.delta != 0) {
+            const double phi = (double)hit.delta * (double)inv_freq[i];
+            double sn, cn;
+            sincos(phi, &sn, &cn);
+            cs = make_float2((float)cn, (float)sn);
         }
-        uint32_t total;
-        const uint32_t incl = irm_block_scan_incl(nt, lds, &total);
-        uint32_t t = carry + incl - nt;
-        for (uint32_t k = 0; k < nt; ++k, ++t) {
+        trig[(uint64_t)h * IRM_KR_PAIRS + i] = cs;
+        if (i == 0 && nt == 0 && hit.len != 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+    }
+    if (i == 0) local_nt[threadIdx.x >> 5] = nt;
+    // tiles in front of this workgroup's first hit
+    uint32_t before = 0;
+    for (uint32_t k = threadIdx.x; k < h0; k += blockDim.x)
+        before += hit_tiles(hits[k], src_rows, n_slot_tokens, tile_rows);
+    uint32_t total;
+    (void)irm_block_scan_incl(before, lds, &total);     // also orders local_nt for the reads below
+    uint32_t t0 = total;
+    for (uint32_t k = 0; k < (threadIdx.x >> 5); ++k) t0 += local_nt[k];
+    if (h < n_hits) {
+        for (uint32_t k = i; k < nt; k += 32) {
+            const uint32_t t = t0 + k;
             if (t >= tile_cap) {
                 atomicOr(err, IRM_FLAG_CHUNK_OVERFLOW);
                 break;
@@ -79,9 +91,8 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
             tile.hit = h;
             tiles[t] = tile;
         }
-        carry += total;
+        if (h == n_hits - 1 && i == 0) plan[0] = t0 + nt < tile_cap ? t0 + nt : tile_cap;
     }
-    if (threadIdx.x == 0) plan[0] = carry < tile_cap ? carry : tile_cap;
 }
 
 // ---- rows ----------------------------------------------------------------------
@@ -296,7 +307,7 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
     const uint32_t tile_rows = ctx->block_waves * ctx->rows_per_wave;
-    const uint32_t plan_blocks = (uint32_t)(((uint64_t)hit_capacity * IRM_KR_PAIRS + 255) / 256);
+    const uint32_t plan_blocks = (hit_capacity + 7) / 8;
     hipLaunchKernelGGL(reattach_plan, dim3(plan_blocks), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
                        ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles, ctx->tile_cap,
                        tile_rows, ctx->d_plan, ctx->d_err);
@@ -305,7 +316,8 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     // then balances the load (measured faster than a persistent grid of resident size)
     uint32_t grid = ctx->reattach_grid ? ctx->reattach_grid : (1u << 20);
     if (grid > max_work) grid = (uint32_t)(max_work ? max_work : 1);
-    const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap;
+    const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
+                        (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
     hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode), dim3(grid),
                        dim3(ctx->block_waves * 64), 0, s,

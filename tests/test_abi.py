@@ -78,7 +78,7 @@ def test_null_arguments_are_rejected():
     assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG
     assert L.irm_calibrate_copy(None, None, 0, 0, None) == B.IRM_ERR_INVALID_ARG
-    assert L.irm_ctx_profile_begin(None, 4) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_ctx_profile_begin(None, 4, 1) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_profile_end(None, None, None, None) == B.IRM_ERR_INVALID_ARG
 
 
