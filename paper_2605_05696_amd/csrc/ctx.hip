@@ -34,10 +34,10 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     c->k_bits = k_bits;
     c->chunk_cap = (uint32_t)chunk_cap64;
     c->tile_cap = (uint32_t)(cfg->max_tokens / IRM_TILE_ROWS_MIN + chunk_cap64);
-    c->rows_per_wave = 4;
-    c->block_waves = 4;
+    c->rows_per_wave = 2;
+    c->block_waves = 8;
     c->mem_mode = 3;
-    c->layer_inner = 0;
+    c->xcd_ranges = 1;
 
     hipDeviceProp_t prop;
     if (hipGetDevice(&c->device) != hipSuccess || hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
@@ -117,7 +117,7 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
 {
     if (!ctx) return IRM_ERR_INVALID_ARG;
     if (knob == 0) {
-        if (value > (1u << 20)) return IRM_ERR_INVALID_ARG;
+        if (value > (1u << 24)) return IRM_ERR_INVALID_ARG;
         ctx->reattach_grid = value;
         return IRM_OK;
     }
@@ -145,7 +145,7 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
     }
     if (knob == 3) {
         if (value > 1) return IRM_ERR_INVALID_ARG;
-        ctx->layer_inner = value;
+        ctx->xcd_ranges = value;
         return IRM_OK;
     }
     return IRM_ERR_INVALID_ARG;

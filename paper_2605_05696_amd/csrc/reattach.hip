@@ -198,30 +198,28 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
     }
 }
 
-// Work item t of n_tiles * n_layers: layer-outer (all tiles of layer 0, then layer 1, ...)
-// or layer-inner (all layers of tile 0, then tile 1, ...).
+// Grid (x, y) = (tile slots, layers): all tiles of layer 0 are dispatched first, then
+// layer 1, ...; a tile's address needs no division.  grid.x is a multiple of 8 and the
+// dispatcher deals workgroups round-robin to the 8 XCDs, so with `xcd_ranges` workgroup
+// x serves tile (x % 8) * ceil(n_tiles / 8) + x / 8: each XCD streams one contiguous
+// eighth of the layer's tile list.  Workgroups past the last tile leave at once.
 template <int WAVES, int RPW, bool NT_LD, bool NT_ST>
 __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ dst_ptrs,
     uint64_t dst_stride, uint64_t dst_rows, const int32_t *__restrict__ dst_slots,
     const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
-    uint32_t n_layers, uint32_t layer_inner, uint32_t *err)
+    uint32_t xcd_ranges, uint32_t *err)
 {
     constexpr uint32_t TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
     const uint32_t n_tiles = plan[0];
-    const uint64_t total = (uint64_t)n_tiles * n_layers;
+    const uint32_t layer = blockIdx.y;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = irm_wave_id();
+    const uint32_t per_xcd = (n_tiles + 7) >> 3;
 #pragma nounroll
-    for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
-        uint32_t layer, ti;
-        if (layer_inner) {
-            ti = (uint32_t)(t / n_layers);
-            layer = (uint32_t)(t - (uint64_t)ti * n_layers);
-        } else {
-            layer = (uint32_t)(t / n_tiles);
-            ti = (uint32_t)(t - (uint64_t)layer * n_tiles);
-        }
+    for (uint32_t x = blockIdx.x; x < per_xcd * 8; x += gridDim.x) {
+        const uint32_t ti = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
+        if (ti >= n_tiles) continue;
         const irm_tile *tp = tiles + ti;
         const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
         const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
@@ -252,7 +250,7 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
 
 typedef void (*rows_kernel_t)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t,
                               const int32_t *, const irm_tile *, const uint32_t *, const float2 *, uint32_t,
-                              uint32_t, uint32_t *);
+                              uint32_t *);
 
 template <int WAVES, int RPW>
 static rows_kernel_t pick_mode(uint32_t mode)
@@ -311,19 +309,20 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     hipLaunchKernelGGL(reattach_plan, dim3(plan_blocks), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
                        ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles, ctx->tile_cap,
                        tile_rows, ctx->d_plan, ctx->d_err);
-    uint64_t max_work = ((uint64_t)(n_slot_tokens / tile_rows) + hit_capacity) * ctx->cfg.n_layers;
-    // default: one workgroup per tile while that fits a launch; the hardware dispatcher
-    // then balances the load (measured faster than a persistent grid of resident size)
-    uint32_t grid = ctx->reattach_grid ? ctx->reattach_grid : (1u << 20);
-    if (grid > max_work) grid = (uint32_t)(max_work ? max_work : 1);
+    // one workgroup per tile slot and layer: the hardware dispatcher balances the load
+    // (measured faster than a persistent grid of resident size); the slot count can only
+    // be bounded on the host, surplus workgroups exit on their first compare
+    uint64_t tile_slots = n_slot_tokens / tile_rows + hit_capacity;
+    if (ctx->reattach_grid) tile_slots = ctx->reattach_grid;
+    if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
+    const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8);
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode), dim3(grid),
-                       dim3(ctx->block_waves * 64), 0, s,
+    hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode),
+                       dim3(grid_x, ctx->cfg.n_layers), dim3(ctx->block_waves * 64), 0, s,
                        d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
-                       d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->cfg.n_layers,
-                       ctx->layer_inner, ctx->d_err);
+                       d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->xcd_ranges, ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;
