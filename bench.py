@@ -186,7 +186,10 @@ def cpu_baseline(works, src, budget_s):
     pool_hash = orc.chunk_hash(w0.pool_tokens, w0.pool_chunk_start, w0.pool_chunk_len)
     spent, tokens, batches = 0.0, 0, 0
     L = src.shape[0]
-    for w in works:
+    k = 0
+    while spent < min(budget_s, 10.0) and k < 64:            # cycle the batches until ~10 s of CPU work
+        w = works[k % len(works)]
+        k += 1
         reg = w.registry(pool_hash)
         t0 = time.perf_counter()
         st, ln, rco = orc.cdc_chunk(w.tokens, w.req_offsets, w.gear, w.mask, w.min_chunk, w.max_chunk)
@@ -217,10 +220,8 @@ def cpu_baseline(works, src, budget_s):
         spent += front_s * share + re_s
         tokens += int(off[-1])
         batches += 1
-        if spent >= budget_s:
-            break
     return {"value": tokens / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": f"{tokens} re-attached tokens x {L} layers from {batches} batch(es) of the same workload "
+            "sample": f"{tokens} re-attached tokens x {L} layers from {batches} batch pass(es) over the same workload "
                       f"(chunk+hash+lookup+re-attach, single thread), {spent:.1f} s of CPU time"}
 
 
