@@ -26,6 +26,9 @@
  *                        written into the request's slots (Alg. 1 steps 9-10;
  *                        Sec. 7.2 "k_r rotation"; App. C "k_r rotation
  *                        materialisation": gather-rotate-scatter)
+ *   oracle_reattach_kr   the split-pool variant of the same step: c_KV is only
+ *                        referenced, k_r alone is materialised (App. C "Split
+ *                        TokenToKVPool")
  *
  * Floating point: fp64 throughout, one round-to-nearest-even to bf16 at the
  * store.  Parity status: every function below is pinned by the CPU tests to
@@ -292,6 +295,40 @@ int oracle_reattach(const uint16_t *src, uint64_t src_rows, uint16_t *dst, uint6
                 const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * ORACLE_ROW_DIM;
                 uint16_t *out = dst + ((uint64_t)l * dst_rows + (uint64_t)drow) * ORACLE_ROW_DIM;
                 oracle_reattach_row(in, hit_delta[h], inv_freq, out);
+            }
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Split-pool variant (App. C "Split TokenToKVPool"): the 512-dim c_KV stays in */
+/* the shared, content-addressed pool and is only REFERENCED; the 64-dim k_r   */
+/* slice alone is materialised per request, rotated by delta.                  */
+/* For every hit h, j < len[h], slot = dst_slots[dst_tok[h] + j]:              */
+/*   ckv_index[slot]      <- src_row[h] + j              (same for all layers) */
+/*   kr_dst[l][slot][0:64] <- R(delta[h]) src[l][src_row[h] + j][512:576]       */
+/* src is [n_layers][src_rows][576] bf16, kr_dst is [n_layers][kr_rows][64].    */
+/* ------------------------------------------------------------------------- */
+int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst, uint64_t kr_rows,
+                       int32_t *ckv_index, uint32_t n_layers, const int32_t *dst_slots,
+                       const uint32_t *hit_src_row, const uint32_t *hit_dst_tok,
+                       const uint32_t *hit_len, const int32_t *hit_delta, uint32_t n_hits,
+                       const float *inv_freq)
+{
+    for (uint32_t h = 0; h < n_hits; ++h) {
+        for (uint32_t j = 0; j < hit_len[h]; ++j) {
+            uint64_t srow = (uint64_t)hit_src_row[h] + j;
+            int64_t slot = dst_slots[(uint64_t)hit_dst_tok[h] + j];
+            if (srow >= src_rows || slot < 0 || (uint64_t)slot >= kr_rows) return -1;
+            ckv_index[slot] = (int32_t)srow;
+            for (uint32_t l = 0; l < n_layers; ++l) {
+                const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * ORACLE_ROW_DIM + ORACLE_CKV_DIM;
+                uint16_t *out = kr_dst + ((uint64_t)l * kr_rows + (uint64_t)slot) * ORACLE_KR_DIM;
+                double k[ORACLE_KR_DIM], kr[ORACLE_KR_DIM];
+                for (int d = 0; d < ORACLE_KR_DIM; ++d) k[d] = oracle_bf16_to_f64(in[d]);
+                oracle_rotate_kr_f64(k, (int64_t)hit_delta[h], inv_freq, kr);
+                for (int d = 0; d < ORACLE_KR_DIM; ++d) out[d] = oracle_f64_to_bf16(kr[d]);
             }
         }
     }

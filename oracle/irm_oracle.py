@@ -48,6 +48,7 @@ def lib():
         L.oracle_fnv1a64_bytes.argtypes = [ctypes.c_char_p, ctypes.c_uint64]
         L.oracle_lookup.restype = ctypes.c_int
         L.oracle_reattach.restype = ctypes.c_int
+        L.oracle_reattach_kr.restype = ctypes.c_int
         L.oracle_bf16_to_f64.restype = ctypes.c_double
         L.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
         L.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -206,3 +207,25 @@ def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq) -> None:
         _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
     if rc != 0:
         raise IndexError("oracle_reattach: a hit or slot points outside its pool")
+
+
+def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq) -> None:
+    """Split-pool variant, in place on ``kr_bits`` [L][kr_rows][64] u16 and ``ckv_index`` i32[kr_rows]."""
+    assert src_bits.dtype == np.uint16 and kr_bits.dtype == np.uint16 and ckv_index.dtype == np.int32
+    assert src_bits.flags.c_contiguous and kr_bits.flags.c_contiguous and ckv_index.flags.c_contiguous
+    assert src_bits.ndim == 3 and kr_bits.ndim == 3 and src_bits.shape[2] == ROW_DIM and kr_bits.shape[2] == KR_DIM
+    assert src_bits.shape[0] == kr_bits.shape[0] and len(ckv_index) == kr_bits.shape[1]
+    dst_slots = _arr(dst_slots, np.int32)
+    inv_freq = _arr(inv_freq, np.float32)
+    hs, hd = _arr(hits.src_row, np.uint32), _arr(hits.dst_tok, np.uint32)
+    hl, hx = _arr(hits.len, np.uint32), _arr(hits.delta, np.int32)
+    if len(hs):
+        assert int((hd.astype(np.int64) + hl).max()) <= len(dst_slots)
+    rc = lib().oracle_reattach_kr(
+        _p(src_bits, ctypes.c_uint16), ctypes.c_uint64(src_bits.shape[1]),
+        _p(kr_bits, ctypes.c_uint16), ctypes.c_uint64(kr_bits.shape[1]), _p(ckv_index, ctypes.c_int32),
+        ctypes.c_uint32(src_bits.shape[0]), _p(dst_slots, ctypes.c_int32),
+        _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32),
+        _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
+    if rc != 0:
+        raise IndexError("oracle_reattach_kr: a hit or slot points outside its pool")

@@ -249,3 +249,28 @@ def test_out_of_range_indices_are_refused():
                    np.array([0], np.int32))
     with pytest.raises(IndexError):
         orc.reattach(src, dst, slots, bad, INV)
+
+
+# ------------------------------------------------------------- split pool --
+
+def test_split_pool_variant_references_ckv_and_materialises_only_kr():
+    """App. C "Split TokenToKVPool": c_KV is shared by reference, only the 64-dim k_r is
+    written per request.  The k_r written must be the k_r slice the full materialisation
+    writes, and the index must name the source row whose c_KV that materialisation copies."""
+    rng = np.random.default_rng(8)
+    L, src_rows, dst_rows = 2, 60, 45
+    src = bf16_bits(rng.standard_normal((L, src_rows, 576)))
+    slots = rng.permutation(dst_rows).astype(np.int32)
+    hits = orc.Hits(src_row=np.array([3, 40], np.uint32), dst_tok=np.array([1, 25], np.uint32),
+                    len=np.array([9, 13], np.uint32), delta=np.array([777, -12], np.int32))
+    full = np.full((L, dst_rows, 576), wl.SENTINEL_BF16, np.uint16)
+    orc.reattach(src, full, slots, hits, INV)
+    kr = np.full((L, dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
+    idx = np.full(dst_rows, -1, np.int32)
+    orc.reattach_kr(src, kr, idx, slots, hits, INV)
+    assert np.array_equal(kr, full[:, :, 512:])                       # same rotated keys, same untouched rows
+    touched = idx >= 0
+    assert touched.sum() == 22
+    for l in range(L):
+        assert np.array_equal(src[l, idx[touched], :512], full[l, touched, :512])   # the referenced c_KV
+    assert np.all(full[:, ~touched, :512] == wl.SENTINEL_BF16)
