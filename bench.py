@@ -41,6 +41,10 @@ def main() -> int:
     ap.add_argument("--variants", type=int, default=8, help="request batches cycled through")
     ap.add_argument("--slots", default="contiguous", choices=["contiguous", "permuted"])
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the row kernel (0 = library default)")
+    ap.add_argument("--reattach", default="full", choices=["full", "kr", "kr-dense"],
+                    help="full = c_KV copied + k_r rotated (the headline); kr = split-pool variant, "
+                         "only the k_r slice is materialised (256 B per token and layer), read from "
+                         "the packed 576-wide source rows; kr-dense = the same from a dense k_r_base pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
@@ -85,8 +89,23 @@ def main() -> int:
 
     L = w0.n_layers
     src = wl.kv_pool_torch(L, w0.src_rows, wl.kv_seed(name), dev)
-    dst = wl.sentinel_pool_torch(L, w0.dst_rows, dev)
-    src_ptrs, dst_ptrs = B.layer_pointers(src), B.layer_pointers(dst)
+    src_ptrs = B.layer_pointers(src)
+    if args.reattach == "full":
+        dst = wl.sentinel_pool_torch(L, w0.dst_rows, dev)
+        dst_ptrs = B.layer_pointers(dst)
+        bytes_per_token_layer = 2 * ROW_BYTES                        # one row read, one written
+    else:
+        dst = torch.zeros((L, w0.dst_rows, 64), dtype=torch.bfloat16, device=dev)
+        dst_ptrs = B.kr_layer_pointers(dst)
+        if args.reattach == "kr":
+            kr_src_ptrs, kr_src_stride = B.kr_slice_pointers(src), ROW_BYTES
+        else:
+            kr_base = torch.empty((L, w0.src_rows, 64), dtype=torch.bfloat16, device=dev)
+            for l in range(L):
+                kr_base[l].copy_(src[l, :, 512:])
+            kr_src_ptrs, kr_src_stride = B.kr_layer_pointers(kr_base), 128
+        ckv_index = torch.full((w0.dst_rows,), -1, dtype=torch.int32, device=dev)
+        bytes_per_token_layer = 2 * 128                              # k_r slice read and written
 
     sessions, dev_in = [], []
     for w in works:
@@ -105,8 +124,12 @@ def main() -> int:
 
     def step(v):
         s, d = sessions[v], dev_in[v]
-        s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
-                w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], stream)
+        if args.reattach == "full":
+            s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
+                    w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], stream)
+        else:
+            s.serve_kr(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], kr_src_ptrs,
+                       kr_src_stride, w0.src_rows, dst_ptrs, 128, w0.dst_rows, ckv_index, d["buf"], stream)
 
     with torch.cuda.stream(stream):
         # one pass per variant: learn the hit counts, check the error words
@@ -144,10 +167,10 @@ def main() -> int:
 
     total_tokens = sum(hit_tokens[k % n_var] for k in range(args.steps))
     value = total_tokens / elapsed
-    alg_bytes = kernel_tokens * L * 2 * ROW_BYTES               # read + write per row
+    alg_bytes = kernel_tokens * L * bytes_per_token_layer
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
     traffic = None
-    if name == "c1" and args.size == "full" and os.path.exists(PROFILE_TRAFFIC):
+    if name == "c1" and args.size == "full" and args.reattach == "full" and os.path.exists(PROFILE_TRAFFIC):
         traffic = json.load(open(PROFILE_TRAFFIC)).get("hbm_bytes_per_launch")
 
     out = {
@@ -158,10 +181,11 @@ def main() -> int:
         "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
                    "variants": n_var, "hit_tokens_per_step": float(np.mean(hit_tokens)),
-                   "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach on one stream"},
-        "roofline": {"bound": "hbm", "kernel": "reattach_rows", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                   "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s on one stream"
+                             % ("" if args.reattach == "full" else "_kr")},
+        "roofline": {"bound": "hbm", "kernel": "reattach_rows" if args.reattach == "full" else "reattach_kr_rows", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "bytes_per_token_layer": 2 * ROW_BYTES, "launches": kernel_n,
+                     "bytes_per_token_layer": bytes_per_token_layer, "launches": kernel_n,
                      "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3,
                      "kernel_tokens_per_s": kernel_tokens / (kernel_ms * 1e-3) if kernel_ms > 0 else 0.0},
     }

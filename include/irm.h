@@ -227,6 +227,28 @@ irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
                         const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
                         void *stream);
 
+/* Split-pool variant of irm_reattach (App. C "Split TokenToKVPool"): the shared,
+ * content-addressed pool keeps the position-free c_KV, which is only referenced; the
+ * 64-dim k_r slice alone is materialised per request.  For every hit h, j < len,
+ * slot = d_dst_slots[dst_tok + j]:
+ *   d_ckv_index[slot]          = src_row + j   (the pool row whose c_KV the token uses)
+ *   kr[l][slot][0:64]          = the k_r of source row src_row + j of layer l, rotated by delta
+ *   d_src_kr_layer_ptrs        device array of n_layers pointers to the k_r slice (64 bf16) of
+ *                              source row 0: base + 1024 for packed 576-wide rows, or the base
+ *                              of a dense k_r_base pool
+ *   src_kr_row_stride_bytes    >= 128, multiple of 16 (1152 for packed rows, 128 for a dense pool)
+ *   d_kr_layer_ptrs            device array of n_layers pointers to [kr_rows][64] bf16
+ *   kr_row_stride_bytes        >= 128, multiple of 16
+ *   d_ckv_index                int32[kr_rows]; entries of rows no hit covers are untouched
+ * Same arithmetic, error reporting and preconditions as irm_reattach.  Traffic is
+ * 256 bytes per token and layer instead of 2304. */
+irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
+                           uint64_t src_kr_row_stride_bytes, uint64_t src_rows,
+                           void *const *d_kr_layer_ptrs, uint64_t kr_row_stride_bytes, uint64_t kr_rows,
+                           int32_t *d_ckv_index, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
+                           const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
+                           void *stream);
+
 #ifdef __cplusplus
 }
 #endif

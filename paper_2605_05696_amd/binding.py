@@ -23,7 +23,7 @@ IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_C
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
-           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach")
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr")
 
 
 class IrmError(RuntimeError):
@@ -72,6 +72,7 @@ def lib():
         L.irm_chunk_hash.argtypes = [vp, vp, u64, vp, vp, vp, u32, vp, vp]
         L.irm_lookup.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
         L.irm_reattach.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, u64, vp, vp, u32, vp]
+        L.irm_reattach_kr.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, vp, u64, vp, vp, u32, vp]
         for name in SYMBOLS:
             getattr(L, name).restype = ctypes.c_int
         _lib = L
@@ -246,3 +247,35 @@ def irm_reattach(ctx, d_src_layer_ptrs, src_row_stride_bytes, src_rows, d_dst_la
         _dev(d_dst_layer_ptrs, i64, "d_dst_layer_ptrs"), dst_row_stride_bytes, dst_rows,
         _dev(d_dst_slots, i32, "d_dst_slots"), d_dst_slots.numel(), _dev(d_hits, i32, "d_hits"),
         _dev(d_n_hits, i32, "d_n_hits"), d_hits.shape[0], _stream(stream)))
+
+
+def kr_slice_pointers(pool):
+    """Per-layer pointers to the k_r slice of row 0 of a packed [L, rows, 576] bf16 pool."""
+    return layer_pointers(pool) + 1024
+
+
+def kr_layer_pointers(pool):
+    """Device array of per-layer base pointers of a [L, rows, 64] bf16 k_r pool tensor."""
+    import torch
+    if pool.dim() != 3 or pool.shape[2] != 64 or pool.dtype != torch.bfloat16 or not pool.is_cuda:
+        raise TypeError("pool: need a [L, rows, 64] bf16 device tensor")
+    if pool.stride(2) != 1 or pool.stride(1) < 64:
+        raise TypeError("pool: rows must be dense")
+    ptrs = [pool.data_ptr() + l * pool.stride(0) * 2 for l in range(pool.shape[0])]
+    return torch.tensor(ptrs, dtype=torch.int64, device=pool.device)
+
+
+def irm_reattach_kr(ctx, d_src_kr_layer_ptrs, src_kr_row_stride_bytes, src_rows, d_kr_layer_ptrs,
+                    kr_row_stride_bytes, kr_rows, d_ckv_index, d_dst_slots, d_hits, d_n_hits,
+                    stream=None) -> None:
+    import torch
+    i32, i64 = torch.int32, torch.int64
+    if d_hits.dim() != 2 or d_hits.shape[1] != 4:
+        raise TypeError("d_hits: need shape [capacity, 4]")
+    if d_src_kr_layer_ptrs.numel() != d_kr_layer_ptrs.numel() or d_ckv_index.numel() < kr_rows:
+        raise TypeError("irm_reattach_kr: array sizes do not match")
+    _check("irm_reattach_kr", lib().irm_reattach_kr(
+        ctx, _dev(d_src_kr_layer_ptrs, i64, "d_src_kr_layer_ptrs"), src_kr_row_stride_bytes, src_rows,
+        _dev(d_kr_layer_ptrs, i64, "d_kr_layer_ptrs"), kr_row_stride_bytes, kr_rows,
+        _dev(d_ckv_index, i32, "d_ckv_index"), _dev(d_dst_slots, i32, "d_dst_slots"), d_dst_slots.numel(),
+        _dev(d_hits, i32, "d_hits"), _dev(d_n_hits, i32, "d_n_hits"), d_hits.shape[0], _stream(stream)))

@@ -286,6 +286,120 @@ static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode)
     }
 }
 
+// ---- split-pool variant: only k_r is materialised (App. C "Split TokenToKVPool") ----
+// Tile = up to 64 rows of one hit, four lanes per row; lane (r, j) rotates pairs
+// 8j .. 8j+7 of row r.  The source is addressed by the k_r slice of its row 0 and a
+// row stride, so it may be the k_r line of packed 1152-byte rows or a dense k_r_base
+// pool of 128-byte rows.  c_KV is never read: the kernel only records which shared
+// pool row each destination row refers to (once, by the layer-0 workgroups).
+#define IRM_KR_TILE_ROWS 64u
+
+__global__ __launch_bounds__(256) void reattach_kr_rows(
+    const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
+    uint64_t kr_stride, uint64_t kr_rows, const int32_t *__restrict__ dst_slots,
+    const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
+    int32_t *__restrict__ ckv_index, uint32_t *err)
+{
+    // Lane l of a wave holds 16-byte vector v = l % 8 of row l / 8 (and of row 8 + l / 8):
+    // a wave-wide access covers eight whole 128-byte rows, contiguous when the rows are.
+    // Vectors 0..3 are the first halves of the pairs, 4..7 their partners, four lanes on.
+    const uint32_t n_tiles = plan[0];
+    const uint32_t layer = blockIdx.y;
+    const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
+    const uint32_t v = lane & 7, jq = v & 3;
+    const float sgn = v < 4 ? -1.0f : 1.0f;            // first half: a c - b s; partner: b c + a s
+#pragma nounroll
+    for (uint32_t ti = blockIdx.x; ti < n_tiles; ti += gridDim.x) {
+        const irm_tile *tp = tiles + ti;
+        const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
+        const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
+        const uint32_t n_rows = __builtin_amdgcn_readfirstlane(tp->n_rows);
+        const uint32_t hit = __builtin_amdgcn_readfirstlane(tp->hit);
+        const f32x4 *tq = (const f32x4 *)(trig + (uint64_t)hit * IRM_KR_PAIRS + 8 * jq);
+        const f32x4 t0 = tq[0], t1 = tq[1], t2 = tq[2], t3 = tq[3];
+        u32x4 mine[2];
+        int32_t slot[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const uint32_t r = wave * 16 + q * 8 + (lane >> 3);
+            slot[q] = -1;
+            mine[q] = u32x4{0, 0, 0, 0};
+            if (r < n_rows) {
+                const int32_t sl = dst_slots[(uint64_t)dst_tok0 + r];
+                if (sl < 0 || (uint64_t)(uint32_t)sl >= kr_rows) {
+                    if (v == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+                } else {
+                    slot[q] = sl;
+                }
+                mine[q] = __builtin_nontemporal_load(
+                    (const u32x4 *)((const char *)src_ptrs[layer] + (uint64_t)(src_row0 + r) * src_stride) + v);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const uint32_t r = wave * 16 + q * 8 + (lane >> 3);
+            // the partner vector sits four lanes away (all lanes take part in the exchange)
+            u32x4 other;
+            other.x = __shfl_xor(mine[q].x, 4);
+            other.y = __shfl_xor(mine[q].y, 4);
+            other.z = __shfl_xor(mine[q].z, 4);
+            other.w = __shfl_xor(mine[q].w, 4);
+            if (slot[q] < 0) continue;
+            const f32x4 tt[4] = {t0, t1, t2, t3};
+            const uint32_t mw[4] = {mine[q].x, mine[q].y, mine[q].z, mine[q].w};
+            const uint32_t ow[4] = {other.x, other.y, other.z, other.w};
+            uint32_t res[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const float m0 = bf16_lo(mw[k]), m1 = bf16_hi(mw[k]), o0 = bf16_lo(ow[k]), o1 = bf16_hi(ow[k]);
+                const float r0 = m0 * tt[k].x + sgn * (o0 * tt[k].y);
+                const float r1 = m1 * tt[k].z + sgn * (o1 * tt[k].w);
+                res[k] = f32_to_bf16(r0) | (f32_to_bf16(r1) << 16);
+            }
+            const u32x4 out = {res[0], res[1], res[2], res[3]};
+            __builtin_nontemporal_store(
+                out, (u32x4 *)((char *)kr_ptrs[layer] + (uint64_t)(uint32_t)slot[q] * kr_stride) + v);
+            if (layer == 0 && v == 0) ckv_index[slot[q]] = (int32_t)(src_row0 + r);
+        }
+    }
+}
+
+extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
+                                      uint64_t src_kr_row_stride_bytes, uint64_t src_rows,
+                                      void *const *d_kr_layer_ptrs, uint64_t kr_row_stride_bytes,
+                                      uint64_t kr_rows, int32_t *d_ckv_index, const int32_t *d_dst_slots,
+                                      uint64_t n_slot_tokens, const irm_hit *d_hits,
+                                      const uint32_t *d_n_hits, uint32_t hit_capacity, void *stream)
+{
+    if (!ctx || !d_src_kr_layer_ptrs || !d_kr_layer_ptrs || !d_ckv_index || !d_dst_slots || !d_hits ||
+        !d_n_hits)
+        return IRM_ERR_INVALID_ARG;
+    if (src_kr_row_stride_bytes < IRM_KR_BYTES || kr_row_stride_bytes < IRM_KR_BYTES ||
+        (src_kr_row_stride_bytes & 15) || (kr_row_stride_bytes & 15))
+        return IRM_ERR_INVALID_ARG;
+    if (src_rows < 1 || kr_rows < 1 || src_rows > 0x7FFFFFFFull || kr_rows > 0x7FFFFFFFull || n_slot_tokens < 1)
+        return IRM_ERR_INVALID_ARG;
+    if (hit_capacity < 1) return IRM_ERR_INVALID_ARG;
+    if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(reattach_plan, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,
+                       hit_capacity, ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles,
+                       ctx->tile_cap, IRM_KR_TILE_ROWS, ctx->d_plan, ctx->d_err);
+    uint64_t tile_slots = n_slot_tokens / IRM_KR_TILE_ROWS + hit_capacity;
+    if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
+    const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
+                        (ctx->prof_calls++ % ctx->prof_every) == 0;
+    if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
+    hipLaunchKernelGGL(reattach_kr_rows, dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
+                       d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
+                       kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index, ctx->d_err);
+    if (sample) {
+        IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
+        ++ctx->prof_n;
+    }
+    return irm_launch_status();
+}
+
 extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
                                    uint64_t src_row_stride_bytes, uint64_t src_rows,
                                    void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,

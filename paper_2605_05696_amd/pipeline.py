@@ -130,3 +130,17 @@ class Session:
                      buf["chunk_entry"], buf["hits"], buf["n_hits"], buf["hit_tokens"], stream)
         B.irm_reattach(self.ctx, src_ptrs, src_stride, src_rows, dst_ptrs, dst_stride, dst_rows,
                        d_dst_slots, buf["hits"], buf["n_hits"], stream)
+
+    def serve_kr(self, d_tokens, d_req_offsets, d_pos_base, d_dst_slots, src_ptrs, src_stride, src_rows,
+                 kr_ptrs, kr_stride, kr_rows, d_ckv_index, buf, stream=None):
+        """Same front end, split-pool back end: only k_r is materialised, c_KV is referenced.
+        ``src_ptrs`` point at the k_r slice of source row 0 of every layer."""
+        B.irm_cdc_chunk(self.ctx, d_tokens, d_req_offsets, buf["chunk_start"], buf["chunk_len"],
+                        buf["req_chunk_offsets"], buf["n_chunks"], stream)
+        B.irm_chunk_hash(self.ctx, d_tokens, buf["chunk_start"], buf["chunk_len"], buf["n_chunks"],
+                         buf["chunk_hash"], stream)
+        B.irm_lookup(self.ctx, self.table, buf["chunk_hash"], buf["chunk_start"], buf["chunk_len"],
+                     buf["req_chunk_offsets"], d_req_offsets, d_pos_base, buf["n_chunks"],
+                     buf["chunk_entry"], buf["hits"], buf["n_hits"], buf["hit_tokens"], stream)
+        B.irm_reattach_kr(self.ctx, src_ptrs, src_stride, src_rows, kr_ptrs, kr_stride, kr_rows,
+                          d_ckv_index, d_dst_slots, buf["hits"], buf["n_hits"], stream)

@@ -121,3 +121,44 @@ def test_full_size_sampled(name):
             assert np.abs(hits.delta).max() < 16384 and w.n_req == 64
     finally:
         rig.close()
+
+
+def test_full_size_split_pool_variant_c1():
+    """irm_reattach_kr at the c1 size: every k_r row and every c_KV reference against the oracle."""
+    from tests.gpu_util import ROW, compare_rows, hits_to_dev
+    from paper_2605_05696_amd import binding as B
+    w = wl.make_workload("c1", orc.cdc_chunk, size="full")
+    rig = Rig(w)
+    try:
+        hits = rig.o["hits"]
+        L = w.n_layers
+        kr = torch.empty((L, w.dst_rows, 64), dtype=torch.bfloat16, device=DEV)
+        kr.view(torch.int16).fill_(wl.SENTINEL_BF16)
+        idx = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        d_hits, d_n = hits_to_dev(hits, rig.buf["cap"])
+        B.irm_reattach_kr(rig.s.ctx, B.kr_slice_pointers(rig.src), ROW * 2, w.src_rows, B.kr_layer_pointers(kr), 128,
+                          w.dst_rows, idx, rig.d_dst_slots, d_hits, d_n)
+        assert rig.s.error_flags() == 0
+        # the oracle works on the source rows the hits name, compacted
+        lens = hits.len.astype(np.int64)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        within = np.arange(off[-1]) - np.repeat(off[:-1], lens)
+        src_idx = np.repeat(hits.src_row.astype(np.int64), lens) + within
+        dst_idx = w.dst_slots[np.repeat(hits.dst_tok.astype(np.int64), lens) + within].astype(np.int64)
+        d_src_idx = torch.from_numpy(src_idx).to(DEV)
+        src_c = np.stack([bits(rig.src[l].index_select(0, d_src_idx)) for l in range(L)])
+        want_kr = np.full((L, w.dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
+        want_idx = np.full(w.dst_rows, -1, np.int32)
+        compact = orc.Hits(off[:-1].astype(np.uint32), hits.dst_tok, hits.len, hits.delta)
+        orc.reattach_kr(src_c, want_kr, want_idx, w.dst_slots, compact, w.inv_freq)
+        got_idx = idx.cpu().numpy()
+        touched = want_idx >= 0
+        assert np.array_equal(got_idx >= 0, touched) and int(touched.sum()) == rig.o["hit_tokens"]
+        # compacted index k stands for pool row src_idx[k]
+        assert np.array_equal(got_idx[touched], src_idx[want_idx[touched]])
+        got_kr = bits(kr)
+        pad = lambda k: np.concatenate([np.zeros(k.shape[:2] + (512,), np.uint16), k], axis=2)
+        compare_rows(pad(got_kr), pad(want_kr), what="c1 k_r only")
+        assert np.array_equal(np.sort(dst_idx), np.nonzero(touched)[0])
+    finally:
+        rig.close()

@@ -293,3 +293,47 @@ def test_reattach_no_hits_and_bad_indices_are_skipped_and_flagged():
         assert np.array_equal(written, want)
     finally:
         s.close()
+
+
+# ------------------------------------------------- split pool (k_r only) --
+
+def run_kr_variant(w, hits, src, dense=False):
+    """irm_reattach_kr on a workload; returns (kr bits [L][rows][64], ckv_index).
+    ``dense``: the source k_r comes from a separate [L][rows][64] k_r_base pool."""
+    L = w.n_layers
+    s = Session.for_workload(w, DEV)
+    try:
+        kr = torch.empty((L, w.dst_rows, 64), dtype=torch.bfloat16, device=DEV)
+        kr.view(torch.int16).fill_(wl.SENTINEL_BF16)
+        idx = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        cap = max(len(hits), 1) + 3
+        d_hits, d_n = hits_to_dev(hits, cap)
+        if dense:
+            base = src[:, :, 512:].contiguous()
+            sp, stride = B.kr_layer_pointers(base), 128
+        else:
+            sp, stride = B.kr_slice_pointers(src), ROW * 2
+        B.irm_reattach_kr(s.ctx, sp, stride, w.src_rows, B.kr_layer_pointers(kr), 128,
+                          w.dst_rows, idx, torch.from_numpy(w.dst_slots).to(DEV), d_hits, d_n)
+        assert s.error_flags() == 0
+        return bits(kr), idx.cpu().numpy()
+    finally:
+        s.close()
+
+
+@pytest.mark.parametrize("name", wl.CONFIG_NAMES)
+@pytest.mark.parametrize("slots,dense", [("contiguous", False), ("permuted", False), ("contiguous", True)])
+def test_reattach_kr_small_configs(name, slots, dense):
+    w = small(name, slots=slots)
+    o = oracle_front(w)
+    hits = o["hits"]
+    src = wl.kv_pool_torch(w.n_layers, w.src_rows, wl.kv_seed(name), DEV)
+    got_kr, got_idx = run_kr_variant(w, hits, src, dense=dense)
+    want_kr = np.full((w.n_layers, w.dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
+    want_idx = np.full(w.dst_rows, -1, np.int32)
+    orc.reattach_kr(bits(src), want_kr, want_idx, w.dst_slots, hits, w.inv_freq)
+    assert np.array_equal(got_idx, want_idx)                          # references: bit-exact
+    pad = lambda k: np.concatenate([np.zeros(k.shape[:2] + (512,), np.uint16), k], axis=2)
+    compare_rows(pad(got_kr), pad(want_kr), what=f"{w.name} k_r only")
+    untouched = want_idx < 0
+    assert np.all(got_kr[:, untouched] == wl.SENTINEL_BF16)
