@@ -120,6 +120,36 @@ __device__ __forceinline__ void rotate_word(uint32_t wa, uint32_t wb, float2 cs0
     ob = f32_to_bf16(rb0) | (f32_to_bf16(rb1) << 16);
 }
 
+// One 16-byte vector of a k_r row (8 elements) given its partner vector (the other
+// half of the same 8 pairs) and the pairs' (cos, sin): mine * c + sgn * other * s, with
+// sgn = -1 for the first halves (a c - b s) and +1 for the partners (b c + a s).
+__device__ __forceinline__ u32x4 rotate_vector(u32x4 mine, u32x4 other, f32x4 t0, f32x4 t1, f32x4 t2, f32x4 t3,
+                                               float sgn)
+{
+    const f32x4 tt[4] = {t0, t1, t2, t3};
+    const uint32_t mw[4] = {mine.x, mine.y, mine.z, mine.w};
+    const uint32_t ow[4] = {other.x, other.y, other.z, other.w};
+    uint32_t res[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float m0 = bf16_lo(mw[k]), m1 = bf16_hi(mw[k]), o0 = bf16_lo(ow[k]), o1 = bf16_hi(ow[k]);
+        const float r0 = m0 * tt[k].x + sgn * (o0 * tt[k].y);
+        const float r1 = m1 * tt[k].z + sgn * (o1 * tt[k].w);
+        res[k] = f32_to_bf16(r0) | (f32_to_bf16(r1) << 16);
+    }
+    return u32x4{res[0], res[1], res[2], res[3]};
+}
+
+__device__ __forceinline__ u32x4 partner_vector(u32x4 mine)
+{
+    u32x4 other;                                        // the partner sits four lanes away
+    other.x = __shfl_xor(mine.x, 4);
+    other.y = __shfl_xor(mine.y, 4);
+    other.z = __shfl_xor(mine.z, 4);
+    other.w = __shfl_xor(mine.w, 4);
+    return other;
+}
+
 template <bool NT>
 __device__ __forceinline__ u32x4 ld16(const u32x4 *p)
 {
@@ -338,25 +368,9 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const uint32_t r = wave * 16 + q * 8 + (lane >> 3);
-            // the partner vector sits four lanes away (all lanes take part in the exchange)
-            u32x4 other;
-            other.x = __shfl_xor(mine[q].x, 4);
-            other.y = __shfl_xor(mine[q].y, 4);
-            other.z = __shfl_xor(mine[q].z, 4);
-            other.w = __shfl_xor(mine[q].w, 4);
+            const u32x4 other = partner_vector(mine[q]);          // every lane takes part
             if (slot[q] < 0) continue;
-            const f32x4 tt[4] = {t0, t1, t2, t3};
-            const uint32_t mw[4] = {mine[q].x, mine[q].y, mine[q].z, mine[q].w};
-            const uint32_t ow[4] = {other.x, other.y, other.z, other.w};
-            uint32_t res[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float m0 = bf16_lo(mw[k]), m1 = bf16_hi(mw[k]), o0 = bf16_lo(ow[k]), o1 = bf16_hi(ow[k]);
-                const float r0 = m0 * tt[k].x + sgn * (o0 * tt[k].y);
-                const float r1 = m1 * tt[k].z + sgn * (o1 * tt[k].w);
-                res[k] = f32_to_bf16(r0) | (f32_to_bf16(r1) << 16);
-            }
-            const u32x4 out = {res[0], res[1], res[2], res[3]};
+            const u32x4 out = rotate_vector(mine[q], other, t0, t1, t2, t3, sgn);
             __builtin_nontemporal_store(
                 out, (u32x4 *)((char *)kr_ptrs[layer] + (uint64_t)(uint32_t)slot[q] * kr_stride) + v);
             if (layer == 0 && v == 0) ckv_index[slot[q]] = (int32_t)(src_row0 + r);
