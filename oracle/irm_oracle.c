@@ -26,6 +26,8 @@
  *                        written into the request's slots (Alg. 1 steps 9-10;
  *                        Sec. 7.2 "k_r rotation"; App. C "k_r rotation
  *                        materialisation": gather-rotate-scatter)
+ *   oracle_admit         the miss path: prefilled rows are copied into the pool and
+ *                        registered, insert-if-absent (Alg. 1 steps 11-13)
  *   oracle_reattach_kr   the split-pool variant of the same step: c_KV is only
  *                        referenced, k_r alone is materialised (App. C "Split
  *                        TokenToKVPool")
@@ -333,4 +335,68 @@ int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst,
         }
     }
     return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Miss path (Alg. 1 steps 11-13): after the engine has prefilled a chunk that */
+/* missed, its KV rows sit in the request's slots; they are copied into fresh  */
+/* rows of the shared pool and the registry learns hash -> (rows, p, len).     */
+/*                                                                           */
+/* Chunks are taken in ascending order.  A chunk is admitted when              */
+/*   - the lookup missed it (chunk_entry < 0),                                 */
+/*   - its position p >= carve_out (Alg. 1 prefills p < 32 without inserting), */
+/*   - the registry does not hold its hash yet, neither from before nor from   */
+/*     an earlier chunk of this batch (insert-if-absent),                      */
+/*   - the pool has len free rows left after *cursor; the first chunk that     */
+/*     does not fit closes the pool for the rest of the batch.                 */
+/* An admitted chunk gets rows [*cursor, *cursor + len), every layer's rows are */
+/* copied bit for bit from the request's slots (k_r stays as computed at p, so  */
+/* p_src = p), *cursor advances, and admitted_row[c] is the first row; all      */
+/* other chunks get admitted_row[c] = -1.  new_* receive the registry entries   */
+/* in admission order (entry_id = first pool row).  Returns their number.       */
+/* req is [n_layers][req_rows][576], pool is [n_layers][pool_rows][576].        */
+/* ------------------------------------------------------------------------- */
+int64_t oracle_admit(const uint64_t *reg_hash, uint64_t n_reg, const uint64_t *chunk_hash,
+                     const uint32_t *chunk_start, const uint32_t *chunk_len,
+                     const uint32_t *req_chunk_offsets, const uint32_t *req_offsets,
+                     const int32_t *pos_base, uint32_t n_req, uint32_t carve_out,
+                     const int32_t *chunk_entry, const uint16_t *req, uint64_t req_rows,
+                     const int32_t *slots, uint16_t *pool, uint64_t pool_rows, uint32_t n_layers,
+                     uint32_t *cursor, int32_t *admitted_row, uint64_t *new_hash,
+                     uint32_t *new_src_row, int32_t *new_p_src, uint32_t *new_len)
+{
+    int64_t n_new = 0;
+    int pool_closed = 0;
+    for (uint32_t r = 0; r < n_req; ++r) {
+        for (uint32_t c = req_chunk_offsets[r]; c < req_chunk_offsets[r + 1]; ++c) {
+            admitted_row[c] = -1;
+            int64_t p = (int64_t)pos_base[r] + (int64_t)(chunk_start[c] - req_offsets[r]);
+            if (chunk_entry[c] >= 0 || p < (int64_t)carve_out || chunk_len[c] == 0) continue;
+            int known = 0;
+            for (uint64_t k = 0; k < n_reg && !known; ++k) known = reg_hash[k] == chunk_hash[c];
+            for (int64_t k = 0; k < n_new && !known; ++k) known = new_hash[k] == chunk_hash[c];
+            if (known) continue;
+            if (pool_closed || (uint64_t)*cursor + chunk_len[c] > pool_rows) {
+                pool_closed = 1;
+                continue;
+            }
+            for (uint32_t l = 0; l < n_layers; ++l) {
+                for (uint32_t j = 0; j < chunk_len[c]; ++j) {
+                    int64_t slot = slots[(uint64_t)chunk_start[c] + j];
+                    if (slot < 0 || (uint64_t)slot >= req_rows) return -1;
+                    memcpy(pool + ((uint64_t)l * pool_rows + *cursor + j) * ORACLE_ROW_DIM,
+                           req + ((uint64_t)l * req_rows + (uint64_t)slot) * ORACLE_ROW_DIM,
+                           ORACLE_ROW_DIM * sizeof(uint16_t));
+                }
+            }
+            admitted_row[c] = (int32_t)*cursor;
+            new_hash[n_new] = chunk_hash[c];
+            new_src_row[n_new] = *cursor;
+            new_p_src[n_new] = (int32_t)p;
+            new_len[n_new] = chunk_len[c];
+            ++n_new;
+            *cursor += chunk_len[c];
+        }
+    }
+    return n_new;
 }

@@ -49,6 +49,7 @@ def lib():
         L.oracle_lookup.restype = ctypes.c_int
         L.oracle_reattach.restype = ctypes.c_int
         L.oracle_reattach_kr.restype = ctypes.c_int
+        L.oracle_admit.restype = ctypes.c_int64
         L.oracle_bf16_to_f64.restype = ctypes.c_double
         L.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
         L.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -229,3 +230,43 @@ def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq) -
         _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
     if rc != 0:
         raise IndexError("oracle_reattach_kr: a hit or slot points outside its pool")
+
+
+def admit(reg_hash, chunk_hash_, chunk_start, chunk_len, req_chunk_offsets, req_offsets, pos_base,
+          carve_out, chunk_entry, req_bits, slots, pool_bits, cursor):
+    """Miss path, in place on ``pool_bits``.
+    -> (admitted_row i32[C], new registry entries as a dict of arrays, new cursor)"""
+    reg_hash = _arr(reg_hash, np.uint64)
+    chunk_hash_ = _arr(chunk_hash_, np.uint64)
+    chunk_start = _arr(chunk_start, np.uint32)
+    chunk_len = _arr(chunk_len, np.uint32)
+    rco = _arr(req_chunk_offsets, np.uint32)
+    req_offsets = _arr(req_offsets, np.uint32)
+    pos_base = _arr(pos_base, np.int32)
+    chunk_entry = _arr(chunk_entry, np.int32)
+    slots = _arr(slots, np.int32)
+    assert req_bits.dtype == np.uint16 and pool_bits.dtype == np.uint16
+    assert req_bits.flags.c_contiguous and pool_bits.flags.c_contiguous
+    assert req_bits.ndim == 3 and pool_bits.ndim == 3 and req_bits.shape[2] == ROW_DIM == pool_bits.shape[2]
+    assert req_bits.shape[0] == pool_bits.shape[0]
+    C = len(chunk_hash_)
+    cur = ctypes.c_uint32(int(cursor))
+    admitted = np.full(C, -1, np.int32)
+    nh = np.zeros(C, np.uint64)
+    ns = np.zeros(C, np.uint32)
+    npos = np.zeros(C, np.int32)
+    nl = np.zeros(C, np.uint32)
+    n = lib().oracle_admit(
+        _p(reg_hash, ctypes.c_uint64), ctypes.c_uint64(len(reg_hash)), _p(chunk_hash_, ctypes.c_uint64),
+        _p(chunk_start, ctypes.c_uint32), _p(chunk_len, ctypes.c_uint32), _p(rco, ctypes.c_uint32),
+        _p(req_offsets, ctypes.c_uint32), _p(pos_base, ctypes.c_int32), ctypes.c_uint32(len(req_offsets) - 1),
+        ctypes.c_uint32(carve_out), _p(chunk_entry, ctypes.c_int32), _p(req_bits, ctypes.c_uint16),
+        ctypes.c_uint64(req_bits.shape[1]), _p(slots, ctypes.c_int32), _p(pool_bits, ctypes.c_uint16),
+        ctypes.c_uint64(pool_bits.shape[1]), ctypes.c_uint32(req_bits.shape[0]), ctypes.byref(cur),
+        _p(admitted, ctypes.c_int32), _p(nh, ctypes.c_uint64), _p(ns, ctypes.c_uint32),
+        _p(npos, ctypes.c_int32), _p(nl, ctypes.c_uint32))
+    if n < 0:
+        raise IndexError("oracle_admit: a slot points outside the request pool")
+    new = dict(hash=nh[:n].copy(), src_row=ns[:n].copy(), p_src=npos[:n].copy(), len=nl[:n].copy(),
+               entry_id=ns[:n].copy())
+    return admitted, new, int(cur.value)
