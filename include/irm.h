@@ -249,6 +249,32 @@ irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
                            const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
                            void *stream);
 
+/* Miss path (Alg. 1 steps 11-13).  Chunks the lookup missed have been prefilled by the
+ * engine into the request's slots; irm_admit copies their rows into fresh rows of the
+ * shared pool and registers them, insert-if-absent.  Chunks are taken in ascending order;
+ * chunk c is admitted when d_chunk_entry[c] < 0, its position p >= carve_out, its hash is
+ * not registered yet (earlier batches win, then the lowest chunk of this batch), and the
+ * pool still has len rows behind *d_cursor; the first chunk that does not fit closes the
+ * pool for the rest of the batch (refused chunks leave the registry as it was).  An admitted chunk gets rows [cursor, cursor + len): every layer's rows are
+ * copied bit for bit from req[l][d_slots[chunk_start + j]], the registry learns
+ * hash -> {src_row = first row, p_src = p, len, entry_id = first row}, the cursor advances.
+ *   d_chunk_* / d_req_* / d_pos_base / d_n_chunks   as written by irm_cdc_chunk / irm_chunk_hash
+ *   d_chunk_entry        int32[chunk_capacity] as written by irm_lookup for the same batch
+ *   d_req_layer_ptrs     request KV pool, rows of 576 bf16 (read);  d_pool_layer_ptrs: shared pool (written)
+ *   d_cursor             uint32[1] in/out: first free pool row
+ *   d_admitted_row       int32[chunk_capacity] out: first pool row of chunk c, or -1
+ * Deterministic.  Needs table n_slots < 2^32 - 16.  Not to be overlapped with lookups of
+ * the same table. */
+irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *d_chunk_hash,
+                     const uint32_t *d_chunk_start, const uint32_t *d_chunk_len,
+                     const uint32_t *d_req_chunk_offsets, const uint32_t *d_req_offsets,
+                     const int32_t *d_pos_base, uint32_t n_req, const uint32_t *d_n_chunks,
+                     uint32_t chunk_capacity, const int32_t *d_chunk_entry,
+                     const void *const *d_req_layer_ptrs, uint64_t req_row_stride_bytes, uint64_t req_rows,
+                     const int32_t *d_slots, uint64_t n_slot_tokens, void *const *d_pool_layer_ptrs,
+                     uint64_t pool_row_stride_bytes, uint64_t pool_rows, uint32_t *d_cursor,
+                     int32_t *d_admitted_row, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

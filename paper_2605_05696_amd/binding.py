@@ -23,7 +23,7 @@ IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_C
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
-           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr")
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit")
 
 
 class IrmError(RuntimeError):
@@ -72,6 +72,8 @@ def lib():
         L.irm_chunk_hash.argtypes = [vp, vp, u64, vp, vp, vp, u32, vp, vp]
         L.irm_lookup.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
         L.irm_reattach.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, u64, vp, vp, u32, vp]
+        L.irm_admit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, u64, u64, vp, u64, vp,
+                                u64, u64, vp, vp, vp]
         L.irm_reattach_kr.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, vp, u64, vp, vp, u32, vp]
         for name in SYMBOLS:
             getattr(L, name).restype = ctypes.c_int
@@ -279,3 +281,26 @@ def irm_reattach_kr(ctx, d_src_kr_layer_ptrs, src_kr_row_stride_bytes, src_rows,
         _dev(d_kr_layer_ptrs, i64, "d_kr_layer_ptrs"), kr_row_stride_bytes, kr_rows,
         _dev(d_ckv_index, i32, "d_ckv_index"), _dev(d_dst_slots, i32, "d_dst_slots"), d_dst_slots.numel(),
         _dev(d_hits, i32, "d_hits"), _dev(d_n_hits, i32, "d_n_hits"), d_hits.shape[0], _stream(stream)))
+
+
+def irm_admit(ctx, table, d_chunk_hash, d_chunk_start, d_chunk_len, d_req_chunk_offsets, d_req_offsets,
+              d_pos_base, d_n_chunks, d_chunk_entry, d_req_layer_ptrs, req_row_stride_bytes, req_rows,
+              d_slots, d_pool_layer_ptrs, pool_row_stride_bytes, pool_rows, d_cursor, d_admitted_row,
+              stream=None) -> None:
+    import torch
+    i32, i64 = torch.int32, torch.int64
+    n_req = d_req_offsets.numel() - 1
+    cap = d_chunk_entry.numel()
+    if (d_admitted_row.numel() != cap or d_chunk_hash.numel() < cap or d_chunk_start.numel() < cap
+            or d_chunk_len.numel() < cap or d_pos_base.numel() != n_req or d_cursor.numel() != 1
+            or d_req_layer_ptrs.numel() != d_pool_layer_ptrs.numel()):
+        raise TypeError("irm_admit: array sizes do not match")
+    _check("irm_admit", lib().irm_admit(
+        ctx, table, _dev(d_chunk_hash, i64, "d_chunk_hash"), _dev(d_chunk_start, i32, "d_chunk_start"),
+        _dev(d_chunk_len, i32, "d_chunk_len"), _dev(d_req_chunk_offsets, i32, "d_req_chunk_offsets"),
+        _dev(d_req_offsets, i32, "d_req_offsets"), _dev(d_pos_base, i32, "d_pos_base"), n_req,
+        _dev(d_n_chunks, i32, "d_n_chunks"), cap, _dev(d_chunk_entry, i32, "d_chunk_entry"),
+        _dev(d_req_layer_ptrs, i64, "d_req_layer_ptrs"), req_row_stride_bytes, req_rows,
+        _dev(d_slots, i32, "d_slots"), d_slots.numel(), _dev(d_pool_layer_ptrs, i64, "d_pool_layer_ptrs"),
+        pool_row_stride_bytes, pool_rows, _dev(d_cursor, i32, "d_cursor"),
+        _dev(d_admitted_row, i32, "d_admitted_row"), _stream(stream)))

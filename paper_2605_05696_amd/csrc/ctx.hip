@@ -57,6 +57,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     const uint64_t o_ht = take((uint64_t)c->chunk_cap * sizeof(irm_hit));
     const uint64_t o_tiles = take((uint64_t)c->tile_cap * sizeof(irm_tile));
     const uint64_t o_trig = take((uint64_t)c->chunk_cap * IRM_KR_PAIRS * sizeof(float2));
+    const uint64_t o_so = take((uint64_t)c->chunk_cap * 4);
     const uint64_t o_plan = take(16);
     if (hipMalloc(&c->slab, off) != hipSuccess) {
         (void)hipGetLastError();
@@ -74,6 +75,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     c->d_hit_tmp = (irm_hit *)(base + o_ht);
     c->d_tiles = (irm_tile *)(base + o_tiles);
     c->d_trig = (float2 *)(base + o_trig);
+    c->d_slot_of = (uint32_t *)(base + o_so);
     c->d_plan = (uint32_t *)(base + o_plan);
     if (hipMemset(c->slab, 0, off) != hipSuccess ||
         hipMemcpy(c->d_gear, cfg->gear, 256 * 4, hipMemcpyHostToDevice) != hipSuccess ||
@@ -248,20 +250,6 @@ extern "C" irm_status irm_table_destroy(irm_table *table)
     return st;
 }
 
-// Walk the probe sequence of `key` until its slot is found or claimed.
-// Returns the slot, or n_slots + 1 when the table has no room.
-__device__ __forceinline__ uint64_t claim_slot(uint64_t *keys, uint64_t n_slots, uint64_t key)
-{
-    if (key == 0) return n_slots;                       // reserved slot: 0 marks "empty" elsewhere
-    uint64_t s = irm_slot_of(key, n_slots);
-    for (uint64_t tries = 0; tries < n_slots; ++tries) {
-        unsigned long long seen = atomicCAS((unsigned long long *)&keys[s], 0ull, (unsigned long long)key);
-        if (seen == 0ull || seen == key) return s;
-        s = (s + 1 == n_slots) ? 0 : s + 1;
-    }
-    return n_slots + 1;
-}
-
 // pass 1: claim a slot per key and record the lowest offer rank that wants it
 __global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *owner, uint64_t n_slots,
                                                    const uint64_t *hash, uint32_t n, uint32_t rank0,
@@ -269,7 +257,7 @@ __global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *own
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    uint64_t s = claim_slot(keys, n_slots, hash[i]);
+    uint64_t s = irm_claim_slot(keys, n_slots, hash[i]);
     if (s > n_slots) {
         atomicOr(err, IRM_FLAG_TABLE_FULL);
         return;

@@ -47,7 +47,8 @@ struct irm_ctx {
     irm_hit *d_hit_tmp;     // [chunk_cap] per-chunk probe result, len == 0 for a miss
     irm_tile *d_tiles;      // [tile_cap]
     float2 *d_trig;         // [chunk_cap][32] (cos, sin) per hit and pair
-    uint32_t *d_plan;       // [4]: n_tiles
+    uint32_t *d_slot_of;    // [chunk_cap] table slot a chunk claimed while being admitted
+    uint32_t *d_plan;       // [4]: n_tiles, then the ticket counters of cdc, lookup and admit
     // optional timing of the row kernel
     hipEvent_t *prof_events; // [2 * prof_cap]
     uint32_t prof_cap, prof_n, prof_every, prof_calls;
@@ -84,6 +85,34 @@ __device__ __forceinline__ uint64_t irm_slot_of(uint64_t key, uint64_t n_slots)
     uint64_t m = key * 0x9E3779B97F4A7C15ull;
     m ^= m >> 29;
     return __umul64hi(m, n_slots);
+}
+
+// Walk the probe sequence of `key` until its slot is found or claimed.
+// Returns the slot, or n_slots + 1 when the table has no room.
+__device__ __forceinline__ uint64_t irm_claim_slot(uint64_t *keys, uint64_t n_slots, uint64_t key)
+{
+    if (key == 0) return n_slots;                       // reserved slot: 0 marks "empty" elsewhere
+    uint64_t s = irm_slot_of(key, n_slots);
+    for (uint64_t tries = 0; tries < n_slots; ++tries) {
+        unsigned long long seen = atomicCAS((unsigned long long *)&keys[s], 0ull, (unsigned long long)key);
+        if (seen == 0ull || seen == key) return s;
+        s = (s + 1 == n_slots) ? 0 : s + 1;
+    }
+    return n_slots + 1;
+}
+
+// absolute position of chunk c: pos_base of its request + offset of its first token there
+__device__ __forceinline__ int64_t irm_chunk_pos(const uint32_t *__restrict__ req_chunk_offsets,
+                                                 const uint32_t *__restrict__ req_offsets,
+                                                 const int32_t *__restrict__ pos_base, uint32_t n_req,
+                                                 uint32_t c, uint32_t start)
+{
+    uint32_t lo = 0, hi = n_req;                        // last r with req_chunk_offsets[r] <= c
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (req_chunk_offsets[mid] <= c) lo = mid; else hi = mid;
+    }
+    return (int64_t)pos_base[lo] + ((int64_t)start - (int64_t)req_offsets[lo]);
 }
 
 __device__ __forceinline__ uint32_t irm_wave_id()

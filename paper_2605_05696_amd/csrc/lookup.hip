@@ -82,15 +82,8 @@ __device__ __forceinline__ void probe_one(const uint64_t *__restrict__ keys, con
                                           uint32_t carve_out, uint32_t c, int32_t *__restrict__ chunk_entry,
                                           irm_hit *hit_tmp)
 {
-    // request of chunk c: last r with req_chunk_offsets[r] <= c
-    uint32_t lo = 0, hi = n_req;
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (req_chunk_offsets[mid] <= c) lo = mid; else hi = mid;
-    }
-    const uint32_t r = lo;
     const uint32_t start = chunk_start[c], len = chunk_len[c];
-    const int64_t pos = (int64_t)pos_base[r] + ((int64_t)start - (int64_t)req_offsets[r]);
+    const int64_t pos = irm_chunk_pos(req_chunk_offsets, req_offsets, pos_base, n_req, c, start);
     irm_hit out = {0u, start, 0u, 0};
     int32_t entry = -1;
     if (pos >= (int64_t)carve_out && len != 0) {

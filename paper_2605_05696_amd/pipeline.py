@@ -144,3 +144,13 @@ class Session:
                      buf["chunk_entry"], buf["hits"], buf["n_hits"], buf["hit_tokens"], stream)
         B.irm_reattach_kr(self.ctx, src_ptrs, src_stride, src_rows, kr_ptrs, kr_stride, kr_rows,
                           d_ckv_index, d_dst_slots, buf["hits"], buf["n_hits"], stream)
+
+    def admit(self, d_req_offsets, d_pos_base, d_slots, req_ptrs, req_stride, req_rows, pool_ptrs, pool_stride,
+              pool_rows, d_cursor, d_admitted_row, buf, stream=None):
+        """Miss path after the engine prefilled the missed chunks into the request's slots:
+        copy them into free pool rows and register them.  ``buf`` holds the chunk arrays and
+        chunk_entry of the lookup of the same batch."""
+        B.irm_admit(self.ctx, self.table, buf["chunk_hash"], buf["chunk_start"], buf["chunk_len"],
+                    buf["req_chunk_offsets"], d_req_offsets, d_pos_base, buf["n_chunks"], buf["chunk_entry"],
+                    req_ptrs, req_stride, req_rows, d_slots, pool_ptrs, pool_stride, pool_rows, d_cursor,
+                    d_admitted_row, stream)
