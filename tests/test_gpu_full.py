@@ -162,3 +162,54 @@ def test_full_size_split_pool_variant_c1():
         assert np.array_equal(np.sort(dst_idx), np.nonzero(touched)[0])
     finally:
         rig.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_full_size_admit(name):
+    """irm_admit on the misses of a full-size batch.  The oracle decides who is admitted and
+    where (it sees layer 0 only, and the free tail of the pool as rows 0.. of its own array);
+    layer 0 of the free tail is compared with it byte for byte, every other layer on the
+    device: admitted pool rows equal the request rows their tokens were prefilled into."""
+    from tests.gpu_util import ROW
+    w = wl.make_workload(name, orc.cdc_chunk, size="full")
+    rig = Rig(w)
+    try:
+        o, L = rig.o, w.n_layers
+        n_chunks = len(o["start"])
+        miss_tokens = int(o["len"][o["entry"] < 0].sum())
+        cursor0 = w.src_rows - miss_tokens + 100                   # the last eligible chunks will not fit
+        gen = torch.Generator(device=DEV).manual_seed(31)
+        for l in range(L):                                         # "prefilled" request pool: random bit patterns
+            rig.dst[l].view(torch.int16).random_(-32768, 32767, generator=gen)
+        rig.serve()
+        torch.cuda.synchronize()
+        assert rig.s.error_flags() == 0
+        assert np.array_equal(rig.buf["chunk_entry"].cpu().numpy()[:n_chunks], o["entry"])
+        d_cursor = torch.tensor([cursor0], dtype=torch.int32, device=DEV)
+        d_adm = torch.full((rig.buf["cap"],), -7, dtype=torch.int32, device=DEV)
+        rig.s.admit(rig.d_req_offsets, rig.d_pos_base, rig.d_dst_slots, rig.dst_ptrs, ROW * 2, w.dst_rows,
+                    rig.src_ptrs, ROW * 2, w.src_rows, d_cursor, d_adm, rig.buf)
+        torch.cuda.synchronize()
+        assert rig.s.error_flags() == 0
+        req0 = bits(rig.dst[0])[None]
+        tail = np.full((1, w.src_rows - cursor0, 576), wl.SENTINEL_BF16, np.uint16)
+        want, new, cur = orc.admit(o["reg"]["hash"], o["hash"], o["start"], o["len"], o["rco"], w.req_offsets,
+                                   w.pos_base, w.carve_out, o["entry"], req0, w.dst_slots, tail, 0)
+        got = d_adm.cpu().numpy()[:n_chunks]
+        assert np.array_equal(got, np.where(want >= 0, want + cursor0, -1))
+        assert int(d_cursor.item()) == cur + cursor0 and cur + cursor0 <= w.src_rows
+        assert (want >= 0).sum() > 0.8 * (o["entry"] < 0).sum() and (want < 0)[o["entry"] < 0].any()
+        written = cur
+        assert np.array_equal(bits(rig.src[0, cursor0:cursor0 + written]), tail[0, :written])
+        sel = want >= 0
+        lens = o["len"][sel].astype(np.int64)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        within = np.arange(off[-1]) - np.repeat(off[:-1], lens)
+        tok = np.repeat(o["start"][sel].astype(np.int64), lens) + within
+        d_req_idx = torch.from_numpy(w.dst_slots[tok].astype(np.int64)).to(DEV)
+        for l in range(L):
+            a = rig.src[l, cursor0:cursor0 + written].view(torch.int16)
+            b = rig.dst[l].index_select(0, d_req_idx).view(torch.int16)
+            assert torch.equal(a, b), f"layer {l}"
+    finally:
+        rig.close()
