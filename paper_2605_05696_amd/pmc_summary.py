@@ -1,6 +1,10 @@
 """Reduce rocprofv3 --pmc CSV output to per-kernel averages.
 
 usage: python -m paper_2605_05696_amd.pmc_summary <counter_collection.csv> [<more.csv> ...]
+       python -m paper_2605_05696_amd.pmc_summary --stats <kernel_stats.csv>
+
+The second form shortens the per-kernel table ``rocprofv3 --kernel-trace --stats
+--output-format csv`` writes (calls, average / min / max duration in us, share).
 
 Prints, per counter and kernel, the number of dispatches and the mean counter
 value per dispatch.  FETCH_SIZE and WRITE_SIZE are reported by the hardware in
@@ -29,10 +33,22 @@ def summarise(paths):
     return {k: (n, total / n) for k, (n, total) in acc.items() if n}
 
 
+def stats_table(path, top=24):
+    with open(path, newline="") as f:
+        rows = list(csv.DictReader(f))
+    print(f"{'kernel':72s} {'calls':>6s} {'avg_us':>10s} {'min_us':>10s} {'max_us':>10s} {'pct':>6s}")
+    for row in rows[:top]:
+        print(f"{row['Name'][:72]:72s} {int(row['Calls']):6d} {float(row['AverageNs']) / 1e3:10.2f} "
+              f"{float(row['MinNs']) / 1e3:10.2f} {float(row['MaxNs']) / 1e3:10.2f} {float(row['Percentage']):6.2f}")
+    return 0
+
+
 def main(argv):
     if len(argv) < 2:
         print(__doc__)
         return 2
+    if argv[1] == "--stats":
+        return stats_table(argv[2])
     table = summarise(argv[1:])
     print(f"{'counter':14s} {'kernel':44s} {'dispatches':>10s} {'mean per dispatch':>20s}")
     for (counter, kernel), (n, mean) in sorted(table.items()):
