@@ -4,17 +4,21 @@
 // Two launches.
 //   reattach_plan  per hit: the 32 (cos, sin) of delta * inv_freq[i], angle as an
 //                  fp64 product with fp64 range reduction (|delta| reaches 1e5, an
-//                  fp32 angle would already cost half a bf16 ulp); workgroup 0 also
-//                  cuts the hits into tiles of up to 64 rows.
-//   reattach_rows  persistent workgroups stream the tiles, layer-outer: a tile's
-//                  source rows are one contiguous span; each wave moves 16 rows of
-//                  c_KV with one 16-byte load and store per lane and row (a row's
-//                  1024 c_KV bytes are exactly one wave-wide access), and every
-//                  lane rotates 8 pairs of one row's k_r: the two 16-byte vectors
-//                  that hold elements 8j.. and 32+8j.. sit in the same lane, so the
-//                  half-split partners never cross lanes.  The row's 128 k_r bytes
-//                  are one cache line.  Loads and stores are non-temporal: every
-//                  byte is touched once.
+//                  fp32 angle would already cost half a bf16 ulp); the hits are cut
+//                  into tiles of up to 16 rows, the tile list is written by all
+//                  workgroups at once.
+//   reattach_rows  grid (tile slots, layers), one workgroup per tile and layer: a
+//                  tile's source rows are one contiguous span; each of the 8 waves
+//                  moves 2 rows of c_KV with one 16-byte load and store per lane and
+//                  row (a row's 1024 c_KV bytes are exactly one wave-wide access),
+//                  and four lanes of wave 0 rotate one row's k_r each: the two
+//                  16-byte vectors that hold elements 8j.. and 32+8j.. sit in the
+//                  same lane, so the half-split partners never cross lanes.  The
+//                  row's 128 k_r bytes are one cache line.  Loads and stores are
+//                  non-temporal: every byte is touched once.
+//   reattach_kr_rows  the split-pool variant (App. C): only the k_r slice is
+//                  materialised, c_KV is handed on as a row index; eight lanes per
+//                  row, whole 128-byte lines per access, partners four lanes apart.
 #include "irm_internal.hpp"
 
 // ---- plan --------------------------------------------------------------------
