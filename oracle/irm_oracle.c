@@ -250,31 +250,36 @@ uint16_t oracle_f64_to_bf16(double x)
 }
 
 /* R(delta) on one 64-element k_r vector, fp64 in and out, no rounding.
- * Half-split pairs: element i is paired with element i+32 and the pair is
- * turned counter-clockwise by the angle delta * inv_freq[i] (standard RoPE;
- * R(a)R(b) = R(a+b), Alg. 1 step 9).  inv_freq are the model's fp32 rotary
- * frequencies (App. D: cos/sin are derived from the inv_freq buffer itself);
- * the angle is the fp64 product of delta and that fp32 value. */
+ * Pair i is turned counter-clockwise by the angle delta * inv_freq[i] (standard
+ * RoPE; R(a)R(b) = R(a+b), Alg. 1 step 9).  Which two elements form pair i is the
+ * model's rotary layout (App. D speaks of DSv2-form and DSv3-form rotaries):
+ *   pair_mode 0, half-split:  elements i and i + 32;
+ *   pair_mode 1, interleaved: elements 2i and 2i + 1.
+ * inv_freq are the model's fp32 rotary frequencies (App. D: cos/sin are derived
+ * from the inv_freq buffer itself); the angle is the fp64 product of delta and
+ * that fp32 value. */
 void oracle_rotate_kr_f64(const double *k_in /* [64] */, int64_t delta,
-                          const float *inv_freq /* [32] */, double *k_out /* [64] */)
+                          const float *inv_freq /* [32] */, uint32_t pair_mode,
+                          double *k_out /* [64] */)
 {
     for (int i = 0; i < ORACLE_KR_PAIRS; ++i) {
         double phi = (double)delta * (double)inv_freq[i];
         double c = cos(phi), s = sin(phi);
-        double a = k_in[i], b = k_in[i + ORACLE_KR_PAIRS];
-        k_out[i] = a * c - b * s;
-        k_out[i + ORACLE_KR_PAIRS] = b * c + a * s;
+        int ia = pair_mode ? 2 * i : i, ib = pair_mode ? 2 * i + 1 : i + ORACLE_KR_PAIRS;
+        double a = k_in[ia], b = k_in[ib];
+        k_out[ia] = a * c - b * s;
+        k_out[ib] = b * c + a * s;
     }
 }
 
 /* One 576-element bf16 KV row: c_KV bits copied, k_r rotated and rounded once. */
 void oracle_reattach_row(const uint16_t *row_in, int32_t delta, const float *inv_freq,
-                         uint16_t *row_out)
+                         uint32_t pair_mode, uint16_t *row_out)
 {
     for (int d = 0; d < ORACLE_CKV_DIM; ++d) row_out[d] = row_in[d];
     double k[ORACLE_KR_DIM], kr[ORACLE_KR_DIM];
     for (int d = 0; d < ORACLE_KR_DIM; ++d) k[d] = oracle_bf16_to_f64(row_in[ORACLE_CKV_DIM + d]);
-    oracle_rotate_kr_f64(k, (int64_t)delta, inv_freq, kr);
+    oracle_rotate_kr_f64(k, (int64_t)delta, inv_freq, pair_mode, kr);
     for (int d = 0; d < ORACLE_KR_DIM; ++d) row_out[ORACLE_CKV_DIM + d] = oracle_f64_to_bf16(kr[d]);
 }
 
@@ -286,7 +291,8 @@ void oracle_reattach_row(const uint16_t *row_in, int32_t delta, const float *inv
 int oracle_reattach(const uint16_t *src, uint64_t src_rows, uint16_t *dst, uint64_t dst_rows,
                     uint32_t n_layers, const int32_t *dst_slots, const uint32_t *hit_src_row,
                     const uint32_t *hit_dst_tok, const uint32_t *hit_len,
-                    const int32_t *hit_delta, uint32_t n_hits, const float *inv_freq)
+                    const int32_t *hit_delta, uint32_t n_hits, const float *inv_freq,
+                    uint32_t pair_mode)
 {
     for (uint32_t h = 0; h < n_hits; ++h) {
         for (uint32_t l = 0; l < n_layers; ++l) {
@@ -296,7 +302,7 @@ int oracle_reattach(const uint16_t *src, uint64_t src_rows, uint16_t *dst, uint6
                 if (srow >= src_rows || drow < 0 || (uint64_t)drow >= dst_rows) return -1;
                 const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * ORACLE_ROW_DIM;
                 uint16_t *out = dst + ((uint64_t)l * dst_rows + (uint64_t)drow) * ORACLE_ROW_DIM;
-                oracle_reattach_row(in, hit_delta[h], inv_freq, out);
+                oracle_reattach_row(in, hit_delta[h], inv_freq, pair_mode, out);
             }
         }
     }
@@ -316,7 +322,7 @@ int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst,
                        int32_t *ckv_index, uint32_t n_layers, const int32_t *dst_slots,
                        const uint32_t *hit_src_row, const uint32_t *hit_dst_tok,
                        const uint32_t *hit_len, const int32_t *hit_delta, uint32_t n_hits,
-                       const float *inv_freq)
+                       const float *inv_freq, uint32_t pair_mode)
 {
     for (uint32_t h = 0; h < n_hits; ++h) {
         for (uint32_t j = 0; j < hit_len[h]; ++j) {
@@ -329,7 +335,7 @@ int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst,
                 uint16_t *out = kr_dst + ((uint64_t)l * kr_rows + (uint64_t)slot) * ORACLE_KR_DIM;
                 double k[ORACLE_KR_DIM], kr[ORACLE_KR_DIM];
                 for (int d = 0; d < ORACLE_KR_DIM; ++d) k[d] = oracle_bf16_to_f64(in[d]);
-                oracle_rotate_kr_f64(k, (int64_t)hit_delta[h], inv_freq, kr);
+                oracle_rotate_kr_f64(k, (int64_t)hit_delta[h], inv_freq, pair_mode, kr);
                 for (int d = 0; d < ORACLE_KR_DIM; ++d) out[d] = oracle_f64_to_bf16(kr[d]);
             }
         }

@@ -166,27 +166,29 @@ def f64_to_bf16(x) -> np.ndarray:
     return np.array([f(float(v)) for v in x.ravel()], np.uint16).reshape(x.shape)
 
 
-def rotate_kr_f64(k, delta, inv_freq) -> np.ndarray:
+def rotate_kr_f64(k, delta, inv_freq, pair_mode=0) -> np.ndarray:
     k = _arr(k, np.float64)
     inv_freq = _arr(inv_freq, np.float32)
     assert k.shape == (KR_DIM,) and inv_freq.shape == (KR_DIM // 2,)
     out = np.zeros(KR_DIM, np.float64)
     lib().oracle_rotate_kr_f64(_p(k, ctypes.c_double), ctypes.c_int64(int(delta)),
-                               _p(inv_freq, ctypes.c_float), _p(out, ctypes.c_double))
+                               _p(inv_freq, ctypes.c_float), ctypes.c_uint32(pair_mode),
+                               _p(out, ctypes.c_double))
     return out
 
 
-def reattach_row(row_bits, delta, inv_freq) -> np.ndarray:
+def reattach_row(row_bits, delta, inv_freq, pair_mode=0) -> np.ndarray:
     row_bits = _arr(row_bits, np.uint16)
     inv_freq = _arr(inv_freq, np.float32)
     assert row_bits.shape == (ROW_DIM,) and inv_freq.shape == (KR_DIM // 2,)
     out = np.zeros(ROW_DIM, np.uint16)
     lib().oracle_reattach_row(_p(row_bits, ctypes.c_uint16), ctypes.c_int32(int(delta)),
-                              _p(inv_freq, ctypes.c_float), _p(out, ctypes.c_uint16))
+                              _p(inv_freq, ctypes.c_float), ctypes.c_uint32(pair_mode),
+                              _p(out, ctypes.c_uint16))
     return out
 
 
-def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq) -> None:
+def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq, pair_mode=0) -> None:
     """In place on ``dst_bits``.  src_bits [L][src_rows][576] u16, dst_bits [L][dst_rows][576] u16."""
     assert src_bits.dtype == np.uint16 and dst_bits.dtype == np.uint16
     assert src_bits.flags.c_contiguous and dst_bits.flags.c_contiguous
@@ -205,12 +207,13 @@ def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq) -> None:
         _p(dst_bits, ctypes.c_uint16), ctypes.c_uint64(dst_bits.shape[1]),
         ctypes.c_uint32(src_bits.shape[0]), _p(dst_slots, ctypes.c_int32),
         _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32),
-        _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
+        _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float),
+        ctypes.c_uint32(pair_mode))
     if rc != 0:
         raise IndexError("oracle_reattach: a hit or slot points outside its pool")
 
 
-def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq) -> None:
+def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq, pair_mode=0) -> None:
     """Split-pool variant, in place on ``kr_bits`` [L][kr_rows][64] u16 and ``ckv_index`` i32[kr_rows]."""
     assert src_bits.dtype == np.uint16 and kr_bits.dtype == np.uint16 and ckv_index.dtype == np.int32
     assert src_bits.flags.c_contiguous and kr_bits.flags.c_contiguous and ckv_index.flags.c_contiguous
@@ -227,7 +230,8 @@ def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq) -
         _p(kr_bits, ctypes.c_uint16), ctypes.c_uint64(kr_bits.shape[1]), _p(ckv_index, ctypes.c_int32),
         ctypes.c_uint32(src_bits.shape[0]), _p(dst_slots, ctypes.c_int32),
         _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32),
-        _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
+        _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float),
+        ctypes.c_uint32(pair_mode))
     if rc != 0:
         raise IndexError("oracle_reattach_kr: a hit or slot points outside its pool")
 

@@ -274,3 +274,63 @@ def test_split_pool_variant_references_ckv_and_materialises_only_kr():
     for l in range(L):
         assert np.array_equal(src[l, idx[touched], :512], full[l, touched, :512])   # the referenced c_KV
     assert np.all(full[:, ~touched, :512] == wl.SENTINEL_BF16)
+
+
+# ------------------------------------------------- interleaved pair layout --
+
+def to_half_split(x):
+    """interleaved layout (pair i = elements 2i, 2i+1) -> half-split (i, i+32)"""
+    return np.concatenate([x[..., 0::2], x[..., 1::2]], axis=-1)
+
+
+def to_interleaved(x):
+    out = np.empty_like(x)
+    out[..., 0::2], out[..., 1::2] = x[..., :32], x[..., 32:]
+    return out
+
+
+@pytest.mark.parametrize("inv", [INV, wl.inv_freq_yarn()], ids=["plain", "yarn"])
+def test_interleaved_layout_is_the_half_split_rotation_under_the_pair_permutation(inv):
+    rng = np.random.default_rng(21)
+    for delta in (0, 1, -7, 4097, -99999):
+        k = rng.standard_normal(64)
+        got = orc.rotate_kr_f64(k, delta, inv, pair_mode=1)
+        want = to_interleaved(orc.rotate_kr_f64(to_half_split(k), delta, inv, pair_mode=0))
+        assert np.array_equal(got, want)                   # same operations on the same numbers
+        z = (k[0::2] + 1j * k[1::2]) * np.exp(1j * delta * inv.astype(np.float64))
+        assert np.max(np.abs(got[0::2] - z.real)) < 1e-12 and np.max(np.abs(got[1::2] - z.imag)) < 1e-12
+
+
+def test_interleaved_single_pair_moves_its_neighbour_not_its_far_partner():
+    k = np.zeros(64)
+    k[6] = 1.0                                             # "a" of pair 3 in the interleaved layout
+    inv = np.zeros(32, np.float32)
+    inv[3] = np.float32(0.001)
+    out = orc.rotate_kr_f64(k, 100, inv, pair_mode=1)
+    want = np.zeros(64)
+    want[6], want[7] = np.cos(100 * float(inv[3])), np.sin(100 * float(inv[3]))
+    assert np.max(np.abs(out - want)) < 1e-15 and out[7] > 0 and out[38] == 0.0
+
+
+def test_interleaved_rows_through_the_gather_rotate_scatter():
+    rng = np.random.default_rng(22)
+    L, src_rows, dst_rows = 2, 40, 50
+    src = bf16_bits(rng.standard_normal((L, src_rows, 576)))
+    slots = rng.permutation(dst_rows).astype(np.int32)[:30]
+    hits = orc.Hits(np.array([3, 20], np.uint32), np.array([0, 12], np.uint32), np.array([12, 18], np.uint32),
+                    np.array([-513, 77], np.int32))
+    got = np.full((L, dst_rows, 576), 0x7FC1, np.uint16)
+    orc.reattach(src, got, slots, hits, INV, pair_mode=1)
+    # the same through the half-split path on permuted k_r columns
+    src_hs = src.copy()
+    src_hs[..., 512:] = to_half_split(src[..., 512:])
+    want = np.full((L, dst_rows, 576), 0x7FC1, np.uint16)
+    orc.reattach(src_hs, want, slots, hits, INV, pair_mode=0)
+    touched = np.zeros(dst_rows, bool)
+    touched[slots] = True
+    want[:, touched, 512:] = to_interleaved(want[:, touched, 512:])
+    assert np.array_equal(got, want)
+    kr = np.full((L, dst_rows, 64), 0x7FC1, np.uint16)
+    idx = np.full(dst_rows, -1, np.int32)
+    orc.reattach_kr(src, kr, idx, slots, hits, INV, pair_mode=1)
+    assert np.array_equal(kr[:, touched], got[:, touched, 512:]) and np.all(kr[:, ~touched] == 0x7FC1)
