@@ -61,7 +61,9 @@ typedef enum irm_status {
 #define IRM_FLAG_ROW_RANGE 0x4u      /* a hit or slot pointed outside its pool; row skipped      */
 #define IRM_FLAG_BAD_CHUNK 0x8u      /* a chunk record pointed outside the token array; skipped  */
 
-#define IRM_PAIR_HALF_SPLIT 0u
+/* which two k_r elements form rotary pair i (App. D: DSv2-form and DSv3-form rotaries) */
+#define IRM_PAIR_HALF_SPLIT 0u  /* elements i and i + 32 */
+#define IRM_PAIR_INTERLEAVED 1u /* elements 2i and 2i + 1 */
 #define IRM_KR_PAIRS 32
 
 typedef struct irm_config {
@@ -72,7 +74,7 @@ typedef struct irm_config {
     uint32_t max_chunk;   /* >= min_chunk, <= 65536                                         */
     /* lookup (Sec. 7.1): chunks at absolute position < carve_out are never served; 0 = off */
     uint32_t carve_out;
-    /* KV geometry: only 512 + 64, half-split pairs */
+    /* KV geometry: only 512 + 64; pair_mode is IRM_PAIR_HALF_SPLIT or IRM_PAIR_INTERLEAVED */
     uint32_t n_layers;
     uint32_t ckv_dim;
     uint32_t kr_dim;

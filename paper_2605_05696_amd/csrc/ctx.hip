@@ -11,7 +11,7 @@ static inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a
 extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
 {
     if (!cfg || !out) return IRM_ERR_INVALID_ARG;
-    if (cfg->ckv_dim != 512 || cfg->kr_dim != 64 || cfg->pair_mode != IRM_PAIR_HALF_SPLIT)
+    if (cfg->ckv_dim != 512 || cfg->kr_dim != 64 || cfg->pair_mode > IRM_PAIR_INTERLEAVED)
         return IRM_ERR_UNSUPPORTED;
     const uint64_t m = cfg->mask;
     if ((m & (m + 1)) != 0) return IRM_ERR_UNSUPPORTED;        // mask must be 2^k - 1

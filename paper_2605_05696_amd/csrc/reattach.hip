@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
                                                      uint32_t hit_capacity, const float *__restrict__ inv_freq,
                                                      uint64_t src_rows, uint64_t n_slot_tokens,
                                                      float2 *__restrict__ trig, irm_tile *__restrict__ tiles,
-                                                     uint32_t tile_cap, uint32_t tile_rows,
+                                                     uint32_t tile_cap, uint32_t tile_rows, uint32_t pair_mode,
                                                      uint32_t *__restrict__ plan, uint32_t *err)
 {
     __shared__ uint32_t lds[17];
@@ -68,7 +68,12 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
             sincos(phi, &sn, &cn);
             cs = make_float2((float)cn, (float)sn);
         }
-        trig[(uint64_t)h * IRM_KR_PAIRS + i] = cs;
+        // Table order.  Half-split: entry i is pair i.  Interleaved: the lane that holds the
+        // 16-byte vectors j and 4+j of a row owns pairs 4j+w and 16+4j+w (w < 4); they are
+        // stored side by side at entries 8j+2w and 8j+2w+1, where the half-split kernel
+        // code finds the (cos, sin) of the two halves of word w.
+        const uint32_t at = pair_mode ? 8u * ((i & 15u) >> 2) + 2u * (i & 3u) + (i >> 4) : i;
+        trig[(uint64_t)h * IRM_KR_PAIRS + at] = cs;
         if (i == 0 && nt == 0 && hit.len != 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
     }
     if (i == 0) local_nt[threadIdx.x >> 5] = nt;
@@ -124,6 +129,30 @@ __device__ __forceinline__ void rotate_word(uint32_t wa, uint32_t wb, float2 cs0
     ob = f32_to_bf16(rb0) | (f32_to_bf16(rb1) << 16);
 }
 
+// (x.lo, x.hi), (y.lo, y.hi) -> (x.lo, y.lo), (x.hi, y.hi); its own inverse
+__device__ __forceinline__ void pair_regroup(uint32_t &x, uint32_t &y)
+{
+    const uint32_t lo = (x & 0xFFFFu) | (y << 16), hi = (x >> 16) | (y & 0xFFFF0000u);
+    x = lo;
+    y = hi;
+}
+
+// Interleaved layout, one 16-byte vector = four whole pairs (a in the low half of a word,
+// b in the high half); t[k].xy or t[k].zw (upper) is the (cos, sin) of word k's pair.
+__device__ __forceinline__ u32x4 rotate_vector_pairs(u32x4 mine, f32x4 t0, f32x4 t1, f32x4 t2, f32x4 t3, bool upper)
+{
+    const f32x4 tt[4] = {t0, t1, t2, t3};
+    const uint32_t mw[4] = {mine.x, mine.y, mine.z, mine.w};
+    uint32_t res[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float a = bf16_lo(mw[k]), b = bf16_hi(mw[k]);
+        const float c = upper ? tt[k].z : tt[k].x, s = upper ? tt[k].w : tt[k].y;
+        res[k] = f32_to_bf16(a * c - b * s) | (f32_to_bf16(b * c + a * s) << 16);
+    }
+    return u32x4{res[0], res[1], res[2], res[3]};
+}
+
 // One 16-byte vector of a k_r row (8 elements) given its partner vector (the other
 // half of the same 8 pairs) and the pairs' (cos, sin): mine * c + sgn * other * s, with
 // sgn = -1 for the first halves (a c - b s) and +1 for the partners (b c + a s).
@@ -175,7 +204,7 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
                                               char *__restrict__ dbase, uint64_t dst_stride,
                                               const int32_t (&slot)[(WAVES * RPW + 63) / 64],
                                               uint32_t n_rows, const float2 *__restrict__ trig_hit,
-                                              uint32_t wave, uint32_t lane)
+                                              uint32_t wave, uint32_t lane, bool il)
 {
     constexpr int TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
     const uint32_t row0 = wave * RPW;
@@ -220,11 +249,24 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
         }
     }
     if (kr_on && kr_slot >= 0) {
+        // interleaved layout: a word holds one whole pair (a, b); regroup the words of the
+        // two vectors into (a, a') and (b, b'), rotate as usual, and put them back
+        uint32_t wa[4] = {ka.x, ka.y, ka.z, ka.w}, wb[4] = {kb.x, kb.y, kb.z, kb.w};
+        if (il) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) pair_regroup(wa[k], wb[k]);
+        }
         uint32_t a0, a1, a2, a3, b0, b1, b2, b3;
-        rotate_word(ka.x, kb.x, make_float2(t0.x, t0.y), make_float2(t0.z, t0.w), a0, b0);
-        rotate_word(ka.y, kb.y, make_float2(t1.x, t1.y), make_float2(t1.z, t1.w), a1, b1);
-        rotate_word(ka.z, kb.z, make_float2(t2.x, t2.y), make_float2(t2.z, t2.w), a2, b2);
-        rotate_word(ka.w, kb.w, make_float2(t3.x, t3.y), make_float2(t3.z, t3.w), a3, b3);
+        rotate_word(wa[0], wb[0], make_float2(t0.x, t0.y), make_float2(t0.z, t0.w), a0, b0);
+        rotate_word(wa[1], wb[1], make_float2(t1.x, t1.y), make_float2(t1.z, t1.w), a1, b1);
+        rotate_word(wa[2], wb[2], make_float2(t2.x, t2.y), make_float2(t2.z, t2.w), a2, b2);
+        rotate_word(wa[3], wb[3], make_float2(t3.x, t3.y), make_float2(t3.z, t3.w), a3, b3);
+        if (il) {
+            pair_regroup(a0, b0);
+            pair_regroup(a1, b1);
+            pair_regroup(a2, b2);
+            pair_regroup(a3, b3);
+        }
         const u32x4 oa = {a0, a1, a2, a3}, ob = {b0, b1, b2, b3};
         u32x4 *out = (u32x4 *)(dbase + (uint64_t)(uint32_t)kr_slot * dst_stride + IRM_CKV_BYTES);
         st16<NT_ST>(oa, out + j);
@@ -242,9 +284,10 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ dst_ptrs,
     uint64_t dst_stride, uint64_t dst_rows, const int32_t *__restrict__ dst_slots,
     const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
-    uint32_t xcd_ranges, uint32_t *err)
+    uint32_t xcd_ranges, uint32_t pair_mode, uint32_t *err)
 {
     constexpr uint32_t TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
+    const bool il = pair_mode != 0;
     const uint32_t n_tiles = plan[0];
     const uint32_t layer = blockIdx.y;
     const uint32_t lane = threadIdx.x & 63;
@@ -275,16 +318,16 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
         const float2 *trig_hit = trig + (uint64_t)hit * IRM_KR_PAIRS;
         if (n_rows == TILE)
             reattach_tile<WAVES, RPW, true, NT_LD, NT_ST>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
-                                                          trig_hit, wave, lane);
+                                                          trig_hit, wave, lane, il);
         else
             reattach_tile<WAVES, RPW, false, NT_LD, NT_ST>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
-                                                           trig_hit, wave, lane);
+                                                           trig_hit, wave, lane, il);
     }
 }
 
 typedef void (*rows_kernel_t)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t,
                               const int32_t *, const irm_tile *, const uint32_t *, const float2 *, uint32_t,
-                              uint32_t *);
+                              uint32_t, uint32_t *);
 
 template <int WAVES, int RPW>
 static rows_kernel_t pick_mode(uint32_t mode)
@@ -332,7 +375,7 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
     uint64_t kr_stride, uint64_t kr_rows, const int32_t *__restrict__ dst_slots,
     const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
-    int32_t *__restrict__ ckv_index, uint32_t *err)
+    int32_t *__restrict__ ckv_index, uint32_t pair_mode, uint32_t *err)
 {
     // Lane l of a wave holds 16-byte vector v = l % 8 of row l / 8 (and of row 8 + l / 8):
     // a wave-wide access covers eight whole 128-byte rows, contiguous when the rows are.
@@ -374,7 +417,8 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
             const uint32_t r = wave * 16 + q * 8 + (lane >> 3);
             const u32x4 other = partner_vector(mine[q]);          // every lane takes part
             if (slot[q] < 0) continue;
-            const u32x4 out = rotate_vector(mine[q], other, t0, t1, t2, t3, sgn);
+            const u32x4 out = pair_mode ? rotate_vector_pairs(mine[q], t0, t1, t2, t3, v >= 4)
+                                        : rotate_vector(mine[q], other, t0, t1, t2, t3, sgn);
             __builtin_nontemporal_store(
                 out, (u32x4 *)((char *)kr_ptrs[layer] + (uint64_t)(uint32_t)slot[q] * kr_stride) + v);
             if (layer == 0 && v == 0) ckv_index[slot[q]] = (int32_t)(src_row0 + r);
@@ -402,7 +446,7 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(reattach_plan, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,
                        hit_capacity, ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles,
-                       ctx->tile_cap, IRM_KR_TILE_ROWS, ctx->d_plan, ctx->d_err);
+                       ctx->tile_cap, IRM_KR_TILE_ROWS, ctx->cfg.pair_mode, ctx->d_plan, ctx->d_err);
     uint64_t tile_slots = n_slot_tokens / IRM_KR_TILE_ROWS + hit_capacity;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
@@ -410,7 +454,8 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
     hipLaunchKernelGGL(reattach_kr_rows, dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
                        d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
-                       kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index, ctx->d_err);
+                       kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index,
+                       ctx->cfg.pair_mode, ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;
@@ -440,7 +485,7 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     const uint32_t plan_blocks = (hit_capacity + 7) / 8;
     hipLaunchKernelGGL(reattach_plan, dim3(plan_blocks), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
                        ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles, ctx->tile_cap,
-                       tile_rows, ctx->d_plan, ctx->d_err);
+                       tile_rows, ctx->cfg.pair_mode, ctx->d_plan, ctx->d_err);
     // one workgroup per tile slot and layer: the hardware dispatcher balances the load
     // (measured faster than a persistent grid of resident size); the slot count can only
     // be bounded on the host, surplus workgroups exit on their first compare
@@ -454,7 +499,8 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode),
                        dim3(grid_x, ctx->cfg.n_layers), dim3(ctx->block_waves * 64), 0, s,
                        d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
-                       d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->xcd_ranges, ctx->d_err);
+                       d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->xcd_ranges, ctx->cfg.pair_mode,
+                       ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;

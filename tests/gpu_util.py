@@ -72,7 +72,7 @@ def compare_rows(got: np.ndarray, want: np.ndarray, what=""):
                 exact=float((step == 0).mean()) if step.size else 1.0)
 
 
-def verify_reattach(w, hits: orc.Hits, src_dev, dst_dev, hit_sel=None, layers=None, what=""):
+def verify_reattach(w, hits: orc.Hits, src_dev, dst_dev, hit_sel=None, layers=None, what="", pair_mode=0):
     """Recompute the selected hits x layers with the oracle from D2H copies of the
     source rows and compare with the rows the GPU wrote."""
     L = src_dev.shape[0]
@@ -93,7 +93,7 @@ def verify_reattach(w, hits: orc.Hits, src_dev, dst_dev, hit_sel=None, layers=No
     want = np.full_like(got, wl.SENTINEL_BF16)
     compact = orc.Hits(off[:-1].astype(np.uint32), off[:-1].astype(np.uint32), lens.astype(np.uint32),
                        hits.delta[sel].copy())
-    orc.reattach(src_c, want, np.arange(off[-1], dtype=np.int32), compact, w.inv_freq)
+    orc.reattach(src_c, want, np.arange(off[-1], dtype=np.int32), compact, w.inv_freq, pair_mode)
     out = compare_rows(got, want, what)
     out["rows"] = int(off[-1]) * len(layers)
     return out
@@ -110,10 +110,10 @@ def covered_rows(w, hits: orc.Hits) -> np.ndarray:
 class Rig:
     """A workload on the device: session, token arrays, pools, table."""
 
-    def __init__(self, w, o=None, with_pools=True, with_table=True):
+    def __init__(self, w, o=None, with_pools=True, with_table=True, pair_mode=0):
         self.w = w
         self.o = o if o is not None else oracle_front(w)
-        self.s = Session.for_workload(w, DEV)
+        self.s = Session.for_workload(w, DEV, pair_mode=pair_mode)
         self.d_tokens = torch.from_numpy(w.tokens).to(DEV)
         self.d_req_offsets = self.s.to_dev_u32(w.req_offsets)
         self.d_pos_base = torch.from_numpy(w.pos_base).to(DEV)

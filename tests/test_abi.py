@@ -44,7 +44,7 @@ def good_config(**over):
     (dict(mask=0xFE), B.IRM_ERR_UNSUPPORTED),               # not 2^k - 1
     (dict(ckv_dim=256), B.IRM_ERR_UNSUPPORTED),
     (dict(kr_dim=128), B.IRM_ERR_UNSUPPORTED),
-    (dict(pair_mode=1), B.IRM_ERR_UNSUPPORTED),
+    (dict(pair_mode=2), B.IRM_ERR_UNSUPPORTED),
     (dict(min_chunk=4), B.IRM_ERR_INVALID_ARG),             # window of 8 tokens needs min >= 8
     (dict(min_chunk=0), B.IRM_ERR_INVALID_ARG),
     (dict(min_chunk=2000), B.IRM_ERR_INVALID_ARG),          # min > max

@@ -297,11 +297,11 @@ def test_reattach_no_hits_and_bad_indices_are_skipped_and_flagged():
 
 # ------------------------------------------------- split pool (k_r only) --
 
-def run_kr_variant(w, hits, src, dense=False):
+def run_kr_variant(w, hits, src, dense=False, pair_mode=0):
     """irm_reattach_kr on a workload; returns (kr bits [L][rows][64], ckv_index).
     ``dense``: the source k_r comes from a separate [L][rows][64] k_r_base pool."""
     L = w.n_layers
-    s = Session.for_workload(w, DEV)
+    s = Session.for_workload(w, DEV, pair_mode=pair_mode)
     try:
         kr = torch.empty((L, w.dst_rows, 64), dtype=torch.bfloat16, device=DEV)
         kr.view(torch.int16).fill_(wl.SENTINEL_BF16)
@@ -337,3 +337,66 @@ def test_reattach_kr_small_configs(name, slots, dense):
     compare_rows(pad(got_kr), pad(want_kr), what=f"{w.name} k_r only")
     untouched = want_idx < 0
     assert np.all(got_kr[:, untouched] == wl.SENTINEL_BF16)
+
+
+# ------------------------------------------------ interleaved rotary pairs --
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4"])
+@pytest.mark.parametrize("slots", ["contiguous", "permuted"])
+def test_interleaved_pairs_small_configs(name, slots):
+    """pair i = elements (2i, 2i+1) of k_r: the whole path, then the k_r-only variant."""
+    w = small(name, slots=slots)
+    rig = Rig(w, pair_mode=1)
+    try:
+        rig.serve()
+        assert rig.s.error_flags() == 0
+        hits = rig.o["hits"]
+        stats = verify_reattach(w, hits, rig.src, rig.dst, what=f"{w.name} interleaved", pair_mode=1)
+        assert stats["rows"] == rig.o["hit_tokens"] * w.n_layers and stats["exact"] > 0.95
+        # the half-split answer is a different one: the switch really switched
+        half = np.full((1, w.dst_rows, 576), wl.SENTINEL_BF16, np.uint16)
+        one = orc.Hits(hits.src_row[:1], hits.dst_tok[:1], hits.len[:1], hits.delta[:1])
+        orc.reattach(bits(rig.src[:1]), half, w.dst_slots, one, w.inv_freq, 0)
+        rows = w.dst_slots[int(one.dst_tok[0]):int(one.dst_tok[0]) + int(one.len[0])]
+        assert one.delta[0] != 0 and not np.array_equal(half[0, rows], bits(rig.dst[0])[rows])
+        got_kr, got_idx = run_kr_variant(w, hits, rig.src, pair_mode=1)
+        want_kr = np.full((w.n_layers, w.dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
+        want_idx = np.full(w.dst_rows, -1, np.int32)
+        orc.reattach_kr(bits(rig.src), want_kr, want_idx, w.dst_slots, hits, w.inv_freq, 1)
+        assert np.array_equal(got_idx, want_idx)
+        pad = lambda k: np.concatenate([np.zeros(k.shape[:2] + (512,), np.uint16), k], axis=2)
+        compare_rows(pad(got_kr), pad(want_kr), what=f"{w.name} interleaved k_r only")
+    finally:
+        rig.close()
+
+
+def test_interleaved_pairs_special_deltas():
+    """delta = 0 stays the exact identity; tile tails; extreme |delta| (YaRN frequencies)."""
+    rng = np.random.default_rng(6)
+    L, src_rows, dst_rows = 2, 1500, 1400
+    lens = np.array([1, 15, 16, 17, 33, 1024, 7], np.uint32)
+    src_row = np.array([0, 10, 100, 200, 300, 400, 1490], np.uint32)
+    dst_tok = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.uint32)
+    delta = np.array([0, 1, -1, 131071, -2**31, 2**31 - 1, 0], np.int32)
+    hits = orc.Hits(src_row, dst_tok, lens, delta)
+    n_tok = int(lens.sum())
+    inv = wl.inv_freq_yarn()
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, L, inv, 4096, 1, DEV, pair_mode=1)
+    try:
+        src = wl.kv_pool_torch(L, src_rows, 77, DEV)
+        dst = wl.sentinel_pool_torch(L, dst_rows, DEV)
+        slots = rng.permutation(dst_rows)[:n_tok].astype(np.int32)
+        d_hits, d_n = hits_to_dev(hits, 16)
+        B.irm_reattach(s.ctx, B.layer_pointers(src), ROW * 2, src_rows, B.layer_pointers(dst), ROW * 2, dst_rows,
+                       torch.from_numpy(slots).to(DEV), d_hits, d_n)
+        assert s.error_flags() == 0
+
+        class W:
+            dst_slots, inv_freq = slots, inv
+        stats = verify_reattach(W, hits, src, dst, what="interleaved special", pair_mode=1)
+        assert stats["rows"] == n_tok * L
+        for h in (0, 6):
+            for j in range(int(lens[h])):
+                assert np.array_equal(bits(src[:, int(src_row[h]) + j]), bits(dst[:, int(slots[int(dst_tok[h]) + j])]))
+    finally:
+        s.close()
