@@ -406,3 +406,47 @@ int64_t oracle_admit(const uint64_t *reg_hash, uint64_t n_reg, const uint64_t *c
     }
     return n_new;
 }
+
+/* ------------------------------------------------------------------------- */
+/* S1, detect-and-recover (Sec. 4 "CDC+fallback"; App. G "S1"): a chunk whose  */
+/* fingerprint missed is sub-divided into fixed windows of `window` tokens     */
+/* (the paper's 128) and every window is fingerprinted and looked up on its    */
+/* own, so content that is shared but sits in a chunk with drifted boundaries  */
+/* is still found.  This function is the sub-division only; the windows it     */
+/* lists are then fingerprinted and looked up exactly like chunks              */
+/* (oracle_chunk_hash, oracle_lookup with req_win_offsets as the CSR).         */
+/*                                                                           */
+/* For every request r and every chunk c of r with expand[c] != 0, in order:   */
+/* n = len[c] / window whole windows; a remainder shorter than a window is not */
+/* probed.  anchor 0: the windows start at the chunk's first token,            */
+/* [s + j w, s + (j+1) w); anchor 1: they end at the chunk's last token,       */
+/* [e - (n-j) w, e - (n-j-1) w) with e = s + len.  (A chunk's end is fixed by  */
+/* content alone; its start also depends on what came before it.  Which side   */
+/* the paper anchors is not stated: both are offered.)                         */
+/* Windows come out in ascending token order.  win_start, win_parent receive   */
+/* one entry per window (first token, index of the chunk it was cut from);     */
+/* req_win_offsets[n_req + 1] is the CSR over requests.  Returns the count.    */
+/* ------------------------------------------------------------------------- */
+int64_t oracle_s1_windows(const uint32_t *chunk_start, const uint32_t *chunk_len,
+                          const uint32_t *req_chunk_offsets, uint32_t n_req,
+                          const uint8_t *expand, uint32_t window, uint32_t anchor,
+                          uint32_t *win_start, uint32_t *win_parent, uint32_t *req_win_offsets)
+{
+    int64_t n_win = 0;
+    if (window == 0) return -1;
+    for (uint32_t r = 0; r < n_req; ++r) {
+        req_win_offsets[r] = (uint32_t)n_win;
+        for (uint32_t c = req_chunk_offsets[r]; c < req_chunk_offsets[r + 1]; ++c) {
+            if (!expand[c]) continue;
+            uint32_t n = chunk_len[c] / window;
+            uint32_t first = anchor ? chunk_start[c] + chunk_len[c] - n * window : chunk_start[c];
+            for (uint32_t j = 0; j < n; ++j) {
+                win_start[n_win] = first + j * window;
+                win_parent[n_win] = c;
+                ++n_win;
+            }
+        }
+    }
+    req_win_offsets[n_req] = (uint32_t)n_win;
+    return n_win;
+}

@@ -50,6 +50,7 @@ def lib():
         L.oracle_reattach.restype = ctypes.c_int
         L.oracle_reattach_kr.restype = ctypes.c_int
         L.oracle_admit.restype = ctypes.c_int64
+        L.oracle_s1_windows.restype = ctypes.c_int64
         L.oracle_bf16_to_f64.restype = ctypes.c_double
         L.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
         L.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -274,3 +275,23 @@ def admit(reg_hash, chunk_hash_, chunk_start, chunk_len, req_chunk_offsets, req_
     new = dict(hash=nh[:n].copy(), src_row=ns[:n].copy(), p_src=npos[:n].copy(), len=nl[:n].copy(),
                entry_id=ns[:n].copy())
     return admitted, new, int(cur.value)
+
+
+def s1_windows(chunk_start, chunk_len, req_chunk_offsets, expand, window=128, anchor=0):
+    """S1 sub-division of the chunks marked in ``expand`` into fixed windows.
+    -> (win_start u32[W], win_len u32[W] (all = window), win_parent u32[W], req_win_offsets u32[R+1])"""
+    chunk_start = _arr(chunk_start, np.uint32)
+    chunk_len = _arr(chunk_len, np.uint32)
+    rco = _arr(req_chunk_offsets, np.uint32)
+    expand = np.ascontiguousarray(np.asarray(expand).astype(np.uint8))
+    assert len(expand) == len(chunk_start) == len(chunk_len) and window >= 1 and anchor in (0, 1)
+    cap = int((chunk_len.astype(np.int64) // window).sum()) + 1
+    ws = np.zeros(cap, np.uint32)
+    wp = np.zeros(cap, np.uint32)
+    rwo = np.zeros(len(rco), np.uint32)
+    n = lib().oracle_s1_windows(_p(chunk_start, ctypes.c_uint32), _p(chunk_len, ctypes.c_uint32),
+                                _p(rco, ctypes.c_uint32), ctypes.c_uint32(len(rco) - 1),
+                                _p(expand, ctypes.c_uint8), ctypes.c_uint32(window), ctypes.c_uint32(anchor),
+                                _p(ws, ctypes.c_uint32), _p(wp, ctypes.c_uint32), _p(rwo, ctypes.c_uint32))
+    assert 0 <= n < cap + 1
+    return ws[:n].copy(), np.full(n, window, np.uint32), wp[:n].copy(), rwo
