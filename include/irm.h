@@ -251,6 +251,47 @@ irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
                            const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
                            void *stream);
 
+/* irm_table_insert with the count kept on the device: the first min(*d_n, capacity)
+ * pairs are offered (for lists another call of this library produced). */
+irm_status irm_table_insert_counted(irm_table *table, const uint64_t *d_hash, const irm_entry *d_val,
+                                    const uint32_t *d_n, uint32_t capacity, void *stream);
+
+/* S1, detect-and-recover (Sec. 4 "CDC+fallback"; App. G "S1"): chunks whose fingerprint
+ * missed are sub-divided into fixed windows of `window` tokens (the paper's 128), which are
+ * then fingerprinted and looked up like chunks: hand the window list to irm_chunk_hash and
+ * irm_lookup (d_req_win_offsets in the place of d_req_chunk_offsets, d_n_windows in the
+ * place of d_n_chunks) and the hits to irm_reattach.  This call is the sub-division.
+ * A selected chunk of length len yields floor(len / window) whole windows; a remainder is
+ * not probed.  anchor IRM_S1_ANCHOR_START counts them from the chunk's first token,
+ * IRM_S1_ANCHOR_END back from its last token (the paper does not say; a chunk's end is
+ * fixed by content alone, its start also by what precedes it).
+ *   d_select / select_mode   which chunks: IRM_S1_SELECT_NEGATIVE (d_select[c] < 0: the
+ *                            misses of irm_lookup's d_chunk_entry), IRM_S1_SELECT_NONNEGATIVE
+ *                            (d_select[c] >= 0: the chunks irm_admit placed, d_admitted_row),
+ *                            IRM_S1_SELECT_ALL (d_select may be null)
+ *   d_win_start, d_win_len, d_win_parent   uint32[window_capacity] out: first token, length
+ *                            (= window), index of the chunk the window was cut from;
+ *                            ascending token order
+ *   d_req_win_offsets        uint32[n_req + 1] out, CSR over requests;  d_n_windows uint32[1] out
+ *   d_win_entry              optional irm_entry[window_capacity] out, only with
+ *                            IRM_S1_SELECT_NONNEGATIVE and d_select = irm_admit's d_admitted_row:
+ *                            the registry value of each window (rows inside its chunk's pool
+ *                            rows, its own position), ready for irm_table_insert_counted;
+ *                            needs d_req_offsets and d_pos_base (else they may be null)
+ * More windows than window_capacity: the surplus is dropped, IRM_FLAG_CHUNK_OVERFLOW. */
+#define IRM_S1_SELECT_NEGATIVE 0u
+#define IRM_S1_SELECT_NONNEGATIVE 1u
+#define IRM_S1_SELECT_ALL 2u
+#define IRM_S1_ANCHOR_START 0u
+#define IRM_S1_ANCHOR_END 1u
+irm_status irm_s1_windows(irm_ctx *ctx, const uint32_t *d_chunk_start, const uint32_t *d_chunk_len,
+                          const uint32_t *d_req_chunk_offsets, uint32_t n_req, const uint32_t *d_n_chunks,
+                          uint32_t chunk_capacity, const int32_t *d_select, uint32_t select_mode,
+                          uint32_t window, uint32_t anchor, const uint32_t *d_req_offsets,
+                          const int32_t *d_pos_base, uint32_t *d_win_start, uint32_t *d_win_len,
+                          uint32_t *d_win_parent, uint32_t *d_req_win_offsets, uint32_t *d_n_windows,
+                          uint32_t window_capacity, irm_entry *d_win_entry, void *stream);
+
 /* Miss path (Alg. 1 steps 11-13).  Chunks the lookup missed have been prefilled by the
  * engine into the request's slots; irm_admit copies their rows into fresh rows of the
  * shared pool and registers them, insert-if-absent.  Chunks are taken in ascending order;

@@ -23,7 +23,7 @@ IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_C
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
-           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit")
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows")
 
 
 class IrmError(RuntimeError):
@@ -72,6 +72,9 @@ def lib():
         L.irm_chunk_hash.argtypes = [vp, vp, u64, vp, vp, vp, u32, vp, vp]
         L.irm_lookup.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
         L.irm_reattach.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, u64, vp, vp, u32, vp]
+        L.irm_table_insert_counted.argtypes = [vp, vp, vp, vp, u32, vp]
+        L.irm_s1_windows.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, u32,
+                                     vp, vp]
         L.irm_admit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, u64, u64, vp, u64, vp,
                                 u64, u64, vp, vp, vp]
         L.irm_reattach_kr.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, vp, u64, vp, vp, u32, vp]
@@ -175,6 +178,44 @@ def irm_table_insert(table, d_hash, d_val, stream=None) -> None:
         raise TypeError("d_val: need shape [n, 4]")
     _check("irm_table_insert", lib().irm_table_insert(
         table, _dev(d_hash, torch.int64, "d_hash"), _dev(d_val, torch.int32, "d_val"), n, _stream(stream)))
+
+
+def irm_table_insert_counted(table, d_hash, d_val, d_n, stream=None) -> None:
+    """As irm_table_insert, the number of pairs read from the device word d_n (at most len(d_hash))."""
+    import torch
+    cap = d_hash.numel()
+    if d_val.shape != (cap, 4) or d_n.numel() != 1:
+        raise TypeError("d_val: need shape [n, 4]; d_n: one element")
+    _check("irm_table_insert_counted", lib().irm_table_insert_counted(
+        table, _dev(d_hash, torch.int64, "d_hash"), _dev(d_val, torch.int32, "d_val"),
+        _dev(d_n, torch.int32, "d_n"), cap, _stream(stream)))
+
+
+S1_SELECT_NEGATIVE, S1_SELECT_NONNEGATIVE, S1_SELECT_ALL = 0, 1, 2
+S1_ANCHOR_START, S1_ANCHOR_END = 0, 1
+
+
+def irm_s1_windows(ctx, d_chunk_start, d_chunk_len, d_req_chunk_offsets, d_n_chunks, d_select, select_mode,
+                   window, anchor, d_win_start, d_win_len, d_win_parent, d_req_win_offsets, d_n_windows,
+                   d_req_offsets=None, d_pos_base=None, d_win_entry=None, stream=None) -> None:
+    import torch
+    i32 = torch.int32
+    n_req = d_req_chunk_offsets.numel() - 1
+    cap = d_win_start.numel()
+    if (d_win_len.numel() != cap or d_win_parent.numel() != cap or d_req_win_offsets.numel() != n_req + 1
+            or d_chunk_len.numel() != d_chunk_start.numel() or d_n_windows.numel() != 1
+            or (d_select is not None and d_select.numel() != d_chunk_start.numel())
+            or (d_win_entry is not None and d_win_entry.shape != (cap, 4))):
+        raise TypeError("irm_s1_windows: array sizes do not match")
+    opt = lambda t, name: None if t is None else _dev(t, i32, name)
+    _check("irm_s1_windows", lib().irm_s1_windows(
+        ctx, _dev(d_chunk_start, i32, "d_chunk_start"), _dev(d_chunk_len, i32, "d_chunk_len"),
+        _dev(d_req_chunk_offsets, i32, "d_req_chunk_offsets"), n_req, _dev(d_n_chunks, i32, "d_n_chunks"),
+        d_chunk_start.numel(), opt(d_select, "d_select"), select_mode, window, anchor,
+        opt(d_req_offsets, "d_req_offsets"), opt(d_pos_base, "d_pos_base"), _dev(d_win_start, i32, "d_win_start"),
+        _dev(d_win_len, i32, "d_win_len"), _dev(d_win_parent, i32, "d_win_parent"),
+        _dev(d_req_win_offsets, i32, "d_req_win_offsets"), _dev(d_n_windows, i32, "d_n_windows"), cap,
+        opt(d_win_entry, "d_win_entry"), _stream(stream)))
 
 
 def irm_cdc_chunk(ctx, d_tokens, d_req_offsets, d_chunk_start, d_chunk_len, d_req_chunk_offsets,

@@ -252,10 +252,11 @@ extern "C" irm_status irm_table_destroy(irm_table *table)
 
 // pass 1: claim a slot per key and record the lowest offer rank that wants it
 __global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *owner, uint64_t n_slots,
-                                                   const uint64_t *hash, uint32_t n, uint32_t rank0,
-                                                   uint32_t *err)
+                                                   const uint64_t *hash, uint32_t n, const uint32_t *n_p,
+                                                   uint32_t rank0, uint32_t *err)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n_p && *n_p < n) n = *n_p;                      // count kept on the device
     if (i >= n) return;
     uint64_t s = irm_claim_slot(keys, n_slots, hash[i]);
     if (s > n_slots) {
@@ -269,9 +270,10 @@ __global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *own
 __global__ __launch_bounds__(256) void table_fill(const uint64_t *keys, const uint32_t *owner,
                                                   irm_entry *vals, uint64_t n_slots,
                                                   const uint64_t *hash, const irm_entry *val,
-                                                  uint32_t n, uint32_t rank0)
+                                                  uint32_t n, const uint32_t *n_p, uint32_t rank0)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n_p && *n_p < n) n = *n_p;
     if (i >= n) return;
     const uint64_t key = hash[i];
     uint64_t s = n_slots;
@@ -286,8 +288,8 @@ __global__ __launch_bounds__(256) void table_fill(const uint64_t *keys, const ui
     if (owner[s] == rank0 + i) vals[s] = val[i];
 }
 
-extern "C" irm_status irm_table_insert(irm_table *table, const uint64_t *d_hash,
-                                       const irm_entry *d_val, uint32_t n, void *stream)
+static irm_status table_insert(irm_table *table, const uint64_t *d_hash, const irm_entry *d_val, uint32_t n,
+                               const uint32_t *d_n, void *stream)
 {
     if (!table || (!d_hash && n) || (!d_val && n)) return IRM_ERR_INVALID_ARG;
     if (n == 0) return IRM_OK;
@@ -296,9 +298,23 @@ extern "C" irm_status irm_table_insert(irm_table *table, const uint64_t *d_hash,
     const uint32_t rank0 = (uint32_t)table->offered;
     const uint32_t blocks = (n + 255) / 256;
     hipLaunchKernelGGL(table_claim, dim3(blocks), dim3(256), 0, s, table->d_keys, table->d_owner,
-                       table->n_slots, d_hash, n, rank0, table->ctx->d_err);
+                       table->n_slots, d_hash, n, d_n, rank0, table->ctx->d_err);
     hipLaunchKernelGGL(table_fill, dim3(blocks), dim3(256), 0, s, table->d_keys, table->d_owner,
-                       table->d_vals, table->n_slots, d_hash, d_val, n, rank0);
+                       table->d_vals, table->n_slots, d_hash, d_val, n, d_n, rank0);
     table->offered += n;
     return irm_launch_status();
+}
+
+extern "C" irm_status irm_table_insert(irm_table *table, const uint64_t *d_hash,
+                                       const irm_entry *d_val, uint32_t n, void *stream)
+{
+    return table_insert(table, d_hash, d_val, n, nullptr, stream);
+}
+
+extern "C" irm_status irm_table_insert_counted(irm_table *table, const uint64_t *d_hash,
+                                               const irm_entry *d_val, const uint32_t *d_n,
+                                               uint32_t capacity, void *stream)
+{
+    if (!d_n) return IRM_ERR_INVALID_ARG;
+    return table_insert(table, d_hash, d_val, capacity, d_n, stream);
 }

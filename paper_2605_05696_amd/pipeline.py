@@ -154,3 +154,49 @@ class Session:
                     buf["req_chunk_offsets"], d_req_offsets, d_pos_base, buf["n_chunks"], buf["chunk_entry"],
                     req_ptrs, req_stride, req_rows, d_slots, pool_ptrs, pool_stride, pool_rows, d_cursor,
                     d_admitted_row, stream)
+
+    # -- S1 fallback: fixed windows inside the chunks that missed -------------------------
+    def alloc_windows(self, n_tokens: int, n_req: int, window: int = 128):
+        """Buffers of a window list: laid out like ``alloc_front`` so that the same calls take it."""
+        cap = max(int(n_tokens // window), 1)
+        d = self.device
+        i32, i64 = torch.int32, torch.int64
+        return dict(cap=cap, window=window,
+                    chunk_start=torch.zeros(cap, dtype=i32, device=d),
+                    chunk_len=torch.zeros(cap, dtype=i32, device=d),
+                    parent=torch.zeros(cap, dtype=i32, device=d),
+                    req_chunk_offsets=torch.zeros(n_req + 1, dtype=i32, device=d),
+                    n_chunks=torch.zeros(1, dtype=i32, device=d),
+                    chunk_hash=torch.zeros(cap, dtype=i64, device=d),
+                    chunk_entry=torch.full((cap,), -1, dtype=i32, device=d),
+                    entries=torch.zeros((cap, 4), dtype=i32, device=d),
+                    hits=torch.zeros((cap, 4), dtype=i32, device=d),
+                    n_hits=torch.zeros(1, dtype=i32, device=d),
+                    hit_tokens=torch.zeros(1, dtype=i64, device=d))
+
+    def s1_serve(self, d_tokens, d_req_offsets, d_pos_base, d_dst_slots, src_ptrs, src_stride, src_rows,
+                 dst_ptrs, dst_stride, dst_rows, buf, wbuf, anchor=B.S1_ANCHOR_END, stream=None):
+        """After ``serve`` on the same batch: sub-divide the chunks it missed, fingerprint and look
+        up the windows, re-attach the window hits."""
+        B.irm_s1_windows(self.ctx, buf["chunk_start"], buf["chunk_len"], buf["req_chunk_offsets"], buf["n_chunks"],
+                         buf["chunk_entry"], B.S1_SELECT_NEGATIVE, wbuf["window"], anchor, wbuf["chunk_start"],
+                         wbuf["chunk_len"], wbuf["parent"], wbuf["req_chunk_offsets"], wbuf["n_chunks"],
+                         stream=stream)
+        B.irm_chunk_hash(self.ctx, d_tokens, wbuf["chunk_start"], wbuf["chunk_len"], wbuf["n_chunks"],
+                         wbuf["chunk_hash"], stream)
+        B.irm_lookup(self.ctx, self.table, wbuf["chunk_hash"], wbuf["chunk_start"], wbuf["chunk_len"],
+                     wbuf["req_chunk_offsets"], d_req_offsets, d_pos_base, wbuf["n_chunks"],
+                     wbuf["chunk_entry"], wbuf["hits"], wbuf["n_hits"], wbuf["hit_tokens"], stream)
+        B.irm_reattach(self.ctx, src_ptrs, src_stride, src_rows, dst_ptrs, dst_stride, dst_rows,
+                       d_dst_slots, wbuf["hits"], wbuf["n_hits"], stream)
+
+    def s1_register(self, d_tokens, d_req_offsets, d_pos_base, d_admitted_row, buf, wbuf,
+                    anchor=B.S1_ANCHOR_END, stream=None):
+        """After ``admit``: register the windows of the chunks it placed (rows inside their pool rows)."""
+        B.irm_s1_windows(self.ctx, buf["chunk_start"], buf["chunk_len"], buf["req_chunk_offsets"], buf["n_chunks"],
+                         d_admitted_row, B.S1_SELECT_NONNEGATIVE, wbuf["window"], anchor, wbuf["chunk_start"],
+                         wbuf["chunk_len"], wbuf["parent"], wbuf["req_chunk_offsets"], wbuf["n_chunks"],
+                         d_req_offsets, d_pos_base, wbuf["entries"], stream)
+        B.irm_chunk_hash(self.ctx, d_tokens, wbuf["chunk_start"], wbuf["chunk_len"], wbuf["n_chunks"],
+                         wbuf["chunk_hash"], stream)
+        B.irm_table_insert_counted(self.table, wbuf["chunk_hash"], wbuf["entries"], wbuf["n_chunks"], stream)

@@ -153,6 +153,19 @@ class Workload:
         return dict(hash=h, src_row=src_row, p_src=p_src, len=ln,
                     entry_id=np.arange(n, dtype=np.uint32))
 
+    def window_registry(self, win_start, win_len, win_parent, win_hash, first_id: int):
+        """Registry entries of fixed windows cut from the pool's chunks (the caller made the
+        window list and its fingerprints with the implementation it is exercising): a window
+        keeps the rows of its tokens and the position its parent chunk gives it."""
+        win_start = np.asarray(win_start, np.int64)
+        parent = np.asarray(win_parent, np.int64)
+        off = win_start - self.pool_chunk_start[parent].astype(np.int64)
+        n = len(win_start)
+        return dict(hash=np.asarray(win_hash, np.uint64), src_row=win_start.astype(np.uint32),
+                    p_src=(self.pool_p_src[parent].astype(np.int64) + off).astype(np.int32),
+                    len=np.asarray(win_len, np.uint32),
+                    entry_id=(first_id + np.arange(n)).astype(np.uint32))
+
     def expected_hits(self):
         """Pieces that were planted from the pool and lie past the carve-out:
         (dst_tok, len, pool_chunk, delta) -- what a correct pipeline must find,
@@ -218,8 +231,14 @@ def kv_seed(name: str) -> int:
 
 
 def make_workload(name: str, chunker: Chunker, size: str = "full", variant: int = 0,
-                  slots: str = "contiguous") -> Workload:
+                  slots: str = "contiguous", assembly: str = "aligned", s1_window: int = 0) -> Workload:
     """Build configuration ``name`` ("c0".."c4").
+
+    ``assembly`` "aligned" (default): every piece of a request ends on a cut, so the request
+    re-chunks into its pieces.  "unaligned": every fresh piece but the last loses 1..63 of its
+    trailing tokens, so the pool chunk that follows it starts off a cut and its first chunk
+    drifts (traffic whose assembly the operator does not control).  ``s1_window`` > 0 sizes the
+    table for the pool's fixed windows as well (``window_registry``).
 
     ``variant`` re-draws the request batch against the same pool (used to cycle
     through several batches while timing).  ``slots`` is "contiguous" (request
@@ -256,6 +275,10 @@ def make_workload(name: str, chunker: Chunker, size: str = "full", variant: int 
     f_start, f_len = chunk_stream(fresh_tokens)
     fresh_next = 0
     n_fresh_usable = len(f_start) - 1
+    if assembly == "unaligned":
+        f_len = f_len - rng.integers(1, min_chunk, size=len(f_len))
+    elif assembly != "aligned":
+        raise ValueError(assembly)
 
     toks, piece_start, piece_len, piece_pc = [], [], [], []
     req_offsets = [0]
@@ -317,7 +340,7 @@ def make_workload(name: str, chunker: Chunker, size: str = "full", variant: int 
 
     entries = dims.get("entries")
     n_filler = max(0, entries - len(p_start)) if entries else 0
-    n_entries = len(p_start) + n_filler
+    n_entries = len(p_start) + n_filler + (len(pool_tokens) // s1_window if s1_window else 0)
     table_slots = int(np.ceil(max(n_entries, 1) / LOAD_FACTOR))
 
     return Workload(
