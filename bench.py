@@ -45,10 +45,12 @@ def main() -> int:
                     help="full = c_KV copied + k_r rotated (the headline); kr = split-pool variant, "
                          "only the k_r slice is materialised (256 B per token and layer), read from "
                          "the packed 576-wide source rows; kr-dense = the same from a dense k_r_base pool")
-    ap.add_argument("--stage", default="hit", choices=["hit", "admit"],
+    ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1"],
                     help="hit = the cache-hit path (the headline); admit = the miss path on a cold registry: "
                          "every chunk of the batch is copied from the request pool into the shared pool and "
-                         "registered (irm_admit alone is timed, with events on its stream)")
+                         "registered (irm_admit alone is timed, with events on its stream); s1 = the hit path "
+                         "on UNALIGNED batches followed by the S1 fallback (128-token windows inside the chunks "
+                         "that missed, end-anchored): eight calls per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
@@ -85,10 +87,16 @@ def main() -> int:
         return st, ln, rco
 
     n_var = 1 if name == "c0" else max(1, args.variants)
-    works = [wl.make_workload(name, gpu_chunker, size=args.size, variant=v, slots=args.slots)
+    s1 = args.stage == "s1"
+    works = [wl.make_workload(name, gpu_chunker, size=args.size, variant=v, slots=args.slots,
+                              assembly="unaligned" if s1 else "aligned", s1_window=128 if s1 else 0)
              for v in range(n_var)]
     w0 = works[0]
     _, _, _, pool_hash = front.chunk_host(w0.pool_tokens, np.array([0, len(w0.pool_tokens)], np.uint32))
+    pool_windows = None
+    if s1:
+        pool_windows = front.windows_host(w0.pool_tokens, w0.pool_chunk_start, w0.pool_chunk_len,
+                                          np.array([0, len(w0.pool_chunk_start)], np.uint32), 128, B.S1_ANCHOR_END)
     front.close()
 
     L = w0.n_layers
@@ -114,12 +122,17 @@ def main() -> int:
     sessions, dev_in = [], []
     for w in works:
         s = Session.for_workload(w, dev)
-        s.build_table(w.table_slots, w.registry(pool_hash))
+        reg = w.registry(pool_hash)
+        if s1:
+            wreg = w.window_registry(pool_windows[0], pool_windows[1], pool_windows[2], pool_windows[3], len(reg["hash"]))
+            reg = {k: np.concatenate([reg[k], wreg[k]]) for k in reg}
+        s.build_table(w.table_slots, reg)
         sessions.append(s)
         dev_in.append(dict(tokens=torch.from_numpy(w.tokens).to(dev), req_offsets=s.to_dev_u32(w.req_offsets),
                            pos_base=torch.from_numpy(w.pos_base).to(dev),
                            dst_slots=torch.from_numpy(w.dst_slots).to(dev),
-                           buf=s.alloc_front(len(w.tokens), w.n_req)))
+                           buf=s.alloc_front(len(w.tokens), w.n_req),
+                           wbuf=s.alloc_windows(len(w.tokens), w.n_req, 128) if s1 else None))
         if args.grid:
             B.irm_ctx_tune(s.ctx, 0, args.grid)
 
@@ -139,17 +152,24 @@ def main() -> int:
         if args.reattach == "full":
             s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
                     w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], stream)
+            if s1:
+                s.s1_serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
+                           w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], d["wbuf"], B.S1_ANCHOR_END,
+                           stream)
         else:
             s.serve_kr(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], kr_src_ptrs,
                        kr_src_stride, w0.src_rows, dst_ptrs, 128, w0.dst_rows, ckv_index, d["buf"], stream)
 
     with torch.cuda.stream(stream):
         # one pass per variant: learn the hit counts, check the error words
-        hit_tokens = []
+        hit_tokens, window_tokens = [], []
         for v in range(n_var):
             step(v)
             stream.synchronize()
-            hit_tokens.append(int(dev_in[v]["buf"]["hit_tokens"].item()))
+            hit_tokens.append(int(dev_in[v]["buf"]["hit_tokens"].item())
+                              + (int(dev_in[v]["wbuf"]["hit_tokens"].item()) if s1 else 0))
+            if s1:
+                window_tokens.append(int(dev_in[v]["wbuf"]["hit_tokens"].item()))
             flags = sessions[v].error_flags()
             assert flags == 0, f"device error flags {flags:#x}"
         for k in range(args.warmup):
@@ -157,7 +177,8 @@ def main() -> int:
         calibrate(args.calibrate, dev, stream)
         for s in sessions:
             if args.kernel_timing:
-                B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1, args.kernel_timing)
+                # with S1 every step calls irm_reattach twice: sample the chunk-level launches only
+                B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1, args.kernel_timing * (2 if s1 else 1))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(args.steps):
@@ -169,14 +190,15 @@ def main() -> int:
             ms, n = B.irm_ctx_profile_end(s.ctx, stream)
             kernel_ms += ms
             kernel_n += n
-            kernel_tokens += n * hit_tokens[v]
+            kernel_tokens += n * (hit_tokens[v] - (window_tokens[v] if s1 else 0))
 
     total_tokens = sum(hit_tokens[k % n_var] for k in range(args.steps))
     value = total_tokens / elapsed
     alg_bytes = kernel_tokens * L * bytes_per_token_layer
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
     traffic = None
-    if name == "c1" and args.size == "full" and args.reattach == "full" and os.path.exists(PROFILE_TRAFFIC):
+    if (name == "c1" and args.size == "full" and args.reattach == "full" and args.stage == "hit"
+            and os.path.exists(PROFILE_TRAFFIC)):
         traffic = json.load(open(PROFILE_TRAFFIC)).get("hbm_bytes_per_launch")
 
     out = {
@@ -188,7 +210,9 @@ def main() -> int:
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
                    "variants": n_var, "hit_tokens_per_step": float(np.mean(hit_tokens)),
                    "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s on one stream"
-                             % ("" if args.reattach == "full" else "_kr")},
+                             % ("" if args.reattach == "full" else "_kr")
+                             + ("; then S1: irm_s1_windows+irm_chunk_hash+irm_lookup+irm_reattach on the windows of "
+                                "the missed chunks" if s1 else "")},
         "roofline": {"bound": "hbm", "kernel": "reattach_rows" if args.reattach == "full" else "reattach_kr_rows", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_token_layer": bytes_per_token_layer, "launches": kernel_n,
@@ -196,7 +220,11 @@ def main() -> int:
                      "kernel_tokens_per_s": kernel_tokens / (kernel_ms * 1e-3) if kernel_ms > 0 else 0.0},
     }
 
-    if not args.no_cpu_baseline:
+    if s1:
+        out["metric"] = "re-attached KV tokens/s (all layers), hit path + S1 window fallback on unaligned batches, 1 MI355X"
+        out["config"]["window_hit_tokens_per_step"] = float(np.mean(window_tokens))
+        out["config"]["assembly"] = "unaligned"
+    if not args.no_cpu_baseline and not s1:
         out["cpu_baseline"] = cpu_baseline(works, src, args.cpu_seconds)
 
     for s in sessions:

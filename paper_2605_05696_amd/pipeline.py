@@ -174,6 +174,24 @@ class Session:
                     n_hits=torch.zeros(1, dtype=i32, device=d),
                     hit_tokens=torch.zeros(1, dtype=i64, device=d))
 
+    def windows_host(self, tokens, chunk_start, chunk_len, req_chunk_offsets, window=128, anchor=B.S1_ANCHOR_END):
+        """All fixed windows of a host chunk list, cut and fingerprinted on the GPU.
+        -> (win_start u32, win_len u32, win_parent u32, win_hash u64)"""
+        n_tok, n_req = len(tokens), len(req_chunk_offsets) - 1
+        wbuf = self.alloc_windows(n_tok, n_req, window)
+        d_tok = torch.from_numpy(np.ascontiguousarray(tokens, np.int32)).to(self.device)
+        B.irm_s1_windows(self.ctx, self.to_dev_u32(chunk_start), self.to_dev_u32(chunk_len),
+                         self.to_dev_u32(req_chunk_offsets),
+                         torch.tensor([len(chunk_start)], dtype=torch.int32, device=self.device), None,
+                         B.S1_SELECT_ALL, window, anchor, wbuf["chunk_start"], wbuf["chunk_len"], wbuf["parent"],
+                         wbuf["req_chunk_offsets"], wbuf["n_chunks"])
+        B.irm_chunk_hash(self.ctx, d_tok, wbuf["chunk_start"], wbuf["chunk_len"], wbuf["n_chunks"],
+                         wbuf["chunk_hash"])
+        n = int(wbuf["n_chunks"].item())
+        view = lambda t, dt: t.cpu().numpy().view(dt)[:n].copy()
+        return (view(wbuf["chunk_start"], np.uint32), view(wbuf["chunk_len"], np.uint32),
+                view(wbuf["parent"], np.uint32), view(wbuf["chunk_hash"], np.uint64))
+
     def s1_serve(self, d_tokens, d_req_offsets, d_pos_base, d_dst_slots, src_ptrs, src_stride, src_rows,
                  dst_ptrs, dst_stride, dst_rows, buf, wbuf, anchor=B.S1_ANCHOR_END, stream=None):
         """After ``serve`` on the same batch: sub-divide the chunks it missed, fingerprint and look

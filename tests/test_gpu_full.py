@@ -213,3 +213,51 @@ def test_full_size_admit(name):
             assert torch.equal(a, b), f"layer {l}"
     finally:
         rig.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_full_size_s1_fallback(name):
+    """Unaligned assembly at full size: the window list, its fingerprints and lookup bit for
+    bit against the oracle; window rows recomputed by the oracle (all for c1, 256 hits for c2)."""
+    from tests.gpu_util import ROW
+    from tests.test_gpu_s1 import full_registry, u32
+    W, anchor = 128, 1
+    w = wl.make_workload(name, orc.cdc_chunk, size="full", assembly="unaligned", s1_window=W)
+    reg = full_registry(w, anchor, W)
+    st, ln, rco = orc.cdc_chunk(w.tokens, w.req_offsets, w.gear, w.mask, w.min_chunk, w.max_chunk)
+    ch = orc.chunk_hash(w.tokens, st, ln)
+    look = lambda h, s_, l_, r_: orc.lookup(reg["hash"], reg["src_row"], reg["p_src"], reg["len"], reg["entry_id"],
+                                            h, s_, l_, r_, w.req_offsets, w.pos_base, w.carve_out)
+    entry, hits, hit_tokens = look(ch, st, ln, rco)
+    rig = Rig(w, o=dict(start=st, len=ln, rco=rco, hash=ch, reg=reg, entry=entry, hits=hits, hit_tokens=hit_tokens))
+    try:
+        wbuf = rig.s.alloc_windows(len(w.tokens), w.n_req, W)
+        rig.serve()
+        rig.s.s1_serve(rig.d_tokens, rig.d_req_offsets, rig.d_pos_base, rig.d_dst_slots, rig.src_ptrs, ROW * 2,
+                       w.src_rows, rig.dst_ptrs, ROW * 2, w.dst_rows, rig.buf, wbuf, anchor)
+        torch.cuda.synchronize()
+        assert rig.s.error_flags() == 0
+        check_front(rig)
+        ws, wln, wp, rwo = orc.s1_windows(st, ln, rco, entry < 0, W, anchor)
+        n = int(wbuf["n_chunks"].item())
+        assert n == len(ws)
+        assert np.array_equal(u32(wbuf["chunk_start"])[:n], ws) and np.array_equal(u32(wbuf["parent"])[:n], wp)
+        assert np.array_equal(u32(wbuf["req_chunk_offsets"]), rwo)
+        wh = orc.chunk_hash(w.tokens, ws, wln)
+        assert np.array_equal(wbuf["chunk_hash"].cpu().numpy().view(np.uint64)[:n], wh)
+        wentry, whits, wtok = look(wh, ws, wln, rwo)
+        assert np.array_equal(wbuf["chunk_entry"].cpu().numpy()[:n], wentry)
+        got = hits_from_dev(wbuf["hits"], int(wbuf["n_hits"].item()))
+        for f in ("src_row", "dst_tok", "len", "delta"):
+            assert np.array_equal(getattr(got, f), getattr(whits, f)), f
+        assert wtok > 0.02 * len(w.tokens)                               # the fallback recovers a real share
+        sel = None if name == "c1" else np.sort(np.random.default_rng(77).choice(len(whits), 256, replace=False))
+        stats = verify_reattach(w, whits, rig.src, rig.dst, hit_sel=sel, what=f"{w.name} windows")
+        assert stats["rows"] == (wtok if sel is None else 256 * W) * w.n_layers
+        both = orc.Hits(np.concatenate([hits.src_row, whits.src_row]), np.concatenate([hits.dst_tok, whits.dst_tok]),
+                        np.concatenate([hits.len, whits.len]), np.concatenate([hits.delta, whits.delta]))
+        untouched = torch.from_numpy(np.nonzero(~covered_rows(w, both))[0]).to(DEV)
+        for l in (0, w.n_layers - 1):
+            assert torch.all(rig.dst[l].index_select(0, untouched).view(torch.int16) == wl.SENTINEL_BF16)
+    finally:
+        rig.close()
