@@ -51,6 +51,10 @@ def main() -> int:
                          "registered (irm_admit alone is timed, with events on its stream); s1 = the hit path "
                          "on UNALIGNED batches followed by the S1 fallback (128-token windows inside the chunks "
                          "that missed, end-anchored): eight calls per step")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="batches in flight: step k runs on stream k mod S with its own context and destination "
+                         "pool, so the front end of one batch overlaps the row kernel of another (hit and s1 "
+                         "stages with --reattach full; --variants must be a multiple of S)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
@@ -102,9 +106,14 @@ def main() -> int:
     L = w0.n_layers
     src = wl.kv_pool_torch(L, w0.src_rows, wl.kv_seed(name), dev)
     src_ptrs = B.layer_pointers(src)
+    n_streams = max(1, args.streams)
+    if n_streams > 1:
+        assert args.reattach == "full" and args.stage != "admit" and n_var % n_streams == 0, \
+            "--streams needs --reattach full, the hit or s1 stage, and --variants divisible by it"
     if args.reattach == "full":
-        dst = wl.sentinel_pool_torch(L, w0.dst_rows, dev)
-        dst_ptrs = B.layer_pointers(dst)
+        dsts = [wl.sentinel_pool_torch(L, w0.dst_rows, dev) for _ in range(n_streams)]
+        dst_ptrs_of = [B.layer_pointers(d) for d in dsts]
+        dst, dst_ptrs = dsts[0], dst_ptrs_of[0]
         bytes_per_token_layer = 2 * ROW_BYTES                        # one row read, one written
     else:
         dst = torch.zeros((L, w0.dst_rows, 64), dtype=torch.bfloat16, device=dev)
@@ -136,7 +145,8 @@ def main() -> int:
         if args.grid:
             B.irm_ctx_tune(s.ctx, 0, args.grid)
 
-    stream = torch.cuda.Stream(device=dev)
+    streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
+    stream = streams[0]
     torch.cuda.synchronize()
     if args.stage == "admit":
         with torch.cuda.stream(stream):
@@ -150,6 +160,7 @@ def main() -> int:
     def step(v):
         s, d = sessions[v], dev_in[v]
         if args.reattach == "full":
+            stream, dst_ptrs = streams[v % n_streams], dst_ptrs_of[v % n_streams]   # a context stays on one stream
             s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
                     w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], stream)
             if s1:
@@ -165,7 +176,7 @@ def main() -> int:
         hit_tokens, window_tokens = [], []
         for v in range(n_var):
             step(v)
-            stream.synchronize()
+            torch.cuda.synchronize()
             hit_tokens.append(int(dev_in[v]["buf"]["hit_tokens"].item())
                               + (int(dev_in[v]["wbuf"]["hit_tokens"].item()) if s1 else 0))
             if s1:
@@ -174,6 +185,7 @@ def main() -> int:
             assert flags == 0, f"device error flags {flags:#x}"
         for k in range(args.warmup):
             step(k % n_var)
+        torch.cuda.synchronize()
         calibrate(args.calibrate, dev, stream)
         for s in sessions:
             if args.kernel_timing:
@@ -187,7 +199,7 @@ def main() -> int:
         elapsed = time.perf_counter() - t0
         kernel_ms, kernel_n, kernel_tokens = 0.0, 0, 0
         for v, s in enumerate(sessions):
-            ms, n = B.irm_ctx_profile_end(s.ctx, stream)
+            ms, n = B.irm_ctx_profile_end(s.ctx, streams[v % n_streams])
             kernel_ms += ms
             kernel_n += n
             kernel_tokens += n * (hit_tokens[v] - (window_tokens[v] if s1 else 0))
@@ -208,9 +220,11 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
-                   "variants": n_var, "hit_tokens_per_step": float(np.mean(hit_tokens)),
-                   "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s on one stream"
-                             % ("" if args.reattach == "full" else "_kr")
+                   "variants": n_var, "streams": n_streams, "hit_tokens_per_step": float(np.mean(hit_tokens)),
+                   "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s %s"
+                             % ("" if args.reattach == "full" else "_kr",
+                                "on one stream" if n_streams == 1 else
+                                f"per batch on one stream, {n_streams} batches in flight on {n_streams} streams")
                              + ("; then S1: irm_s1_windows+irm_chunk_hash+irm_lookup+irm_reattach on the windows of "
                                 "the missed chunks" if s1 else "")},
         "roofline": {"bound": "hbm", "kernel": "reattach_rows" if args.reattach == "full" else "reattach_kr_rows", "achieved": achieved, "peak": HBM_PEAK_GBS,
