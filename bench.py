@@ -55,6 +55,7 @@ def main() -> int:
                     help="batches in flight: step k runs on stream k mod S with its own context and destination "
                          "pool, so the front end of one batch overlaps the row kernel of another (hit and s1 "
                          "stages with --reattach full; --variants must be a multiple of S)")
+    ap.add_argument("--tune", default="", help="comma-separated knob=value pairs for irm_ctx_tune (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
@@ -144,6 +145,8 @@ def main() -> int:
                            wbuf=s.alloc_windows(len(w.tokens), w.n_req, 128) if s1 else None))
         if args.grid:
             B.irm_ctx_tune(s.ctx, 0, args.grid)
+        for kv in filter(None, args.tune.split(",")):
+            B.irm_ctx_tune(s.ctx, int(kv.split("=")[0]), int(kv.split("=")[1]))
 
     streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
     stream = streams[0]
@@ -160,13 +163,12 @@ def main() -> int:
     def step(v):
         s, d = sessions[v], dev_in[v]
         if args.reattach == "full":
-            stream, dst_ptrs = streams[v % n_streams], dst_ptrs_of[v % n_streams]   # a context stays on one stream
+            st, dp = streams[v % n_streams], dst_ptrs_of[v % n_streams]   # a context stays on one stream
             s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
-                    w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], stream)
+                    w0.src_rows, dp, ROW_BYTES, w0.dst_rows, d["buf"], st)
             if s1:
                 s.s1_serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
-                           w0.src_rows, dst_ptrs, ROW_BYTES, w0.dst_rows, d["buf"], d["wbuf"], B.S1_ANCHOR_END,
-                           stream)
+                           w0.src_rows, dp, ROW_BYTES, w0.dst_rows, d["buf"], d["wbuf"], B.S1_ANCHOR_END, st)
         else:
             s.serve_kr(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], kr_src_ptrs,
                        kr_src_stride, w0.src_rows, dst_ptrs, 128, w0.dst_rows, ckv_index, d["buf"], stream)

@@ -133,7 +133,8 @@ irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
  * knob 4: waves per workgroup (1, 2, 4, 8 or 16); a tile is waves x rows-per-wave rows,
  *         at least 4
  * knob 5: 1 = irm_cdc_chunk always selects cuts with the serial walk (else only for
- *         requests with more than 4096 candidate positions) */
+ *         requests with more than 4096 candidate positions)
+ * knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; its tile is 32 times that) */
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
 /* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples

@@ -38,6 +38,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     c->block_waves = 8;
     c->mem_mode = 3;
     c->xcd_ranges = 1;
+    c->kr_rows_per_lane = 2;
 
     hipDeviceProp_t prop;
     if (hipGetDevice(&c->device) != hipSuccess || hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
@@ -143,6 +144,11 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
     if (knob == 5) {
         if (value > 1) return IRM_ERR_INVALID_ARG;
         ctx->cdc_serial = value;
+        return IRM_OK;
+    }
+    if (knob == 6) {
+        if (value != 2 && value != 4 && value != 8) return IRM_ERR_INVALID_ARG;
+        ctx->kr_rows_per_lane = value;
         return IRM_OK;
     }
     if (knob == 3) {

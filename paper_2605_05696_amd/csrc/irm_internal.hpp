@@ -34,6 +34,7 @@ struct irm_ctx {
     uint32_t block_waves;   // knob 4: 4, 8 or 16 waves per workgroup (tile = waves * rows_per_wave rows)
     uint32_t mem_mode;      // knob 2: bit 0 non-temporal loads, bit 1 non-temporal stores
     uint32_t cdc_serial;    // knob 5: 1 = always use the serial cut selection
+    uint32_t kr_rows_per_lane; // knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; tile = 32x that)
     uint32_t xcd_ranges;    // knob 3: 1 = each XCD serves a contiguous range of a layer's tiles
     uint32_t n_cu;
     // one device slab, carved up below

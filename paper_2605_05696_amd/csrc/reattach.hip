@@ -364,13 +364,13 @@ static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode)
 }
 
 // ---- split-pool variant: only k_r is materialised (App. C "Split TokenToKVPool") ----
-// Tile = up to 64 rows of one hit, four lanes per row; lane (r, j) rotates pairs
-// 8j .. 8j+7 of row r.  The source is addressed by the k_r slice of its row 0 and a
+// Tile = up to 32 * Q rows of one hit, eight lanes per row, one 16-byte vector each.  The source is addressed by the k_r slice of its row 0 and a
 // row stride, so it may be the k_r line of packed 1152-byte rows or a dense k_r_base
 // pool of 128-byte rows.  c_KV is never read: the kernel only records which shared
 // pool row each destination row refers to (once, by the layer-0 workgroups).
-#define IRM_KR_TILE_ROWS 64u
-
+// A lane keeps its (cos, sin) values for Q rows: the table read is as large as two rows'
+// worth of data, so a tile is 32 * Q rows.
+template <int Q>
 __global__ __launch_bounds__(256) void reattach_kr_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
     uint64_t kr_stride, uint64_t kr_rows, const int32_t *__restrict__ dst_slots,
@@ -394,11 +394,11 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
         const uint32_t hit = __builtin_amdgcn_readfirstlane(tp->hit);
         const f32x4 *tq = (const f32x4 *)(trig + (uint64_t)hit * IRM_KR_PAIRS + 8 * jq);
         const f32x4 t0 = tq[0], t1 = tq[1], t2 = tq[2], t3 = tq[3];
-        u32x4 mine[2];
-        int32_t slot[2];
+        u32x4 mine[Q];
+        int32_t slot[Q];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const uint32_t r = wave * 16 + q * 8 + (lane >> 3);
+        for (int q = 0; q < Q; ++q) {
+            const uint32_t r = (wave * Q + q) * 8 + (lane >> 3);
             slot[q] = -1;
             mine[q] = u32x4{0, 0, 0, 0};
             if (r < n_rows) {
@@ -413,8 +413,8 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
             }
         }
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const uint32_t r = wave * 16 + q * 8 + (lane >> 3);
+        for (int q = 0; q < Q; ++q) {
+            const uint32_t r = (wave * Q + q) * 8 + (lane >> 3);
             const u32x4 other = partner_vector(mine[q]);          // every lane takes part
             if (slot[q] < 0) continue;
             const u32x4 out = pair_mode ? rotate_vector_pairs(mine[q], t0, t1, t2, t3, v >= 4)
@@ -444,15 +444,20 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     if (hit_capacity < 1) return IRM_ERR_INVALID_ARG;
     if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
+    const uint32_t kr_tile_rows = 32u * ctx->kr_rows_per_lane;
     hipLaunchKernelGGL(reattach_plan, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,
                        hit_capacity, ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles,
-                       ctx->tile_cap, IRM_KR_TILE_ROWS, ctx->cfg.pair_mode, ctx->d_plan, ctx->d_err);
-    uint64_t tile_slots = n_slot_tokens / IRM_KR_TILE_ROWS + hit_capacity;
+                       ctx->tile_cap, kr_tile_rows, ctx->cfg.pair_mode, ctx->d_plan, ctx->d_err);
+    uint64_t tile_slots = n_slot_tokens / kr_tile_rows + hit_capacity;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(reattach_kr_rows, dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
+    void (*kr_kernel)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t, const int32_t *,
+                      const irm_tile *, const uint32_t *, const float2 *, int32_t *, uint32_t, uint32_t *) =
+        ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2>
+        : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4> : reattach_kr_rows<8>;
+    hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
                        d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
                        kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index,
                        ctx->cfg.pair_mode, ctx->d_err);
