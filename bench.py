@@ -55,6 +55,10 @@ def main() -> int:
                     help="batches in flight: step k runs on stream k mod S with its own context and destination "
                          "pool, so the front end of one batch overlaps the row kernel of another (hit and s1 "
                          "stages with --reattach full; --variants must be a multiple of S)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each batch variant's step in a HIP graph once and replay it in the timed loop "
+                         "(no per-kernel events then, so no roofline figure); pays off where the step is "
+                         "launch-bound (c0)")
     ap.add_argument("--tune", default="", help="comma-separated knob=value pairs for irm_ctx_tune (sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
@@ -189,14 +193,28 @@ def main() -> int:
             step(k % n_var)
         torch.cuda.synchronize()
         calibrate(args.calibrate, dev, stream)
+        graphs = None
+        if args.graph:
+            assert n_streams == 1, "--graph replays on one stream"
+            graphs = []
+            for v in range(n_var):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    step(v)
+                graphs.append(g)
+            torch.cuda.synchronize()
         for s in sessions:
-            if args.kernel_timing:
+            if args.kernel_timing and not args.graph:
                 # with S1 every step calls irm_reattach twice: sample the chunk-level launches only
                 B.irm_ctx_profile_begin(s.ctx, args.steps // n_var + 1, args.kernel_timing * (2 if s1 else 1))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for k in range(args.steps):
-            step(k % n_var)
+        if graphs:
+            for k in range(args.steps):
+                graphs[k % n_var].replay()
+        else:
+            for k in range(args.steps):
+                step(k % n_var)
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         kernel_ms, kernel_n, kernel_tokens = 0.0, 0, 0
@@ -222,7 +240,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
-                   "variants": n_var, "streams": n_streams, "hit_tokens_per_step": float(np.mean(hit_tokens)),
+                   "variants": n_var, "streams": n_streams, "hip_graph": bool(args.graph), "hit_tokens_per_step": float(np.mean(hit_tokens)),
                    "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s %s"
                              % ("" if args.reattach == "full" else "_kr",
                                 "on one stream" if n_streams == 1 else

@@ -400,3 +400,49 @@ def test_interleaved_pairs_special_deltas():
                 assert np.array_equal(bits(src[:, int(src_row[h]) + j]), bits(dst[:, int(slots[int(dst_tok[h]) + j])]))
     finally:
         s.close()
+
+
+# ------------------------------------------------------------ graph capture --
+
+def test_hot_path_captured_in_a_graph_replays_like_eager():
+    """The four calls allocate nothing, never synchronise and record no memset nodes: they can be
+    captured once and replayed.  Several replays, with eager work and synchronisation between
+    them, against the eager result."""
+    w = small("c2")
+    rig = Rig(w)
+    try:
+        rig.serve()
+        torch.cuda.synchronize()
+        assert rig.s.error_flags() == 0
+        want_dst = rig.dst.clone()
+        keys = ("chunk_start", "chunk_len", "req_chunk_offsets", "n_chunks", "chunk_hash", "chunk_entry", "hits",
+                "n_hits", "hit_tokens")
+        want = {k: rig.buf[k].clone() for k in keys}
+        n_hits = int(want["n_hits"].item())
+        stream = torch.cuda.Stream(device=DEV)
+        graph = torch.cuda.CUDAGraph()
+        serve = lambda: rig.s.serve(rig.d_tokens, rig.d_req_offsets, rig.d_pos_base, rig.d_dst_slots, rig.src_ptrs,
+                                    ROW * 2, w.src_rows, rig.dst_ptrs, ROW * 2, w.dst_rows, rig.buf, stream)
+        with torch.cuda.stream(stream):
+            serve()
+            stream.synchronize()
+            with torch.cuda.graph(graph, stream=stream):
+                serve()
+        torch.cuda.synchronize()
+        for rep in range(4):
+            rig.dst.view(torch.int16).fill_(wl.SENTINEL_BF16)          # eager work between the replays
+            for k in keys:
+                rig.buf[k].fill_(-1 if k != "hit_tokens" else 7)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert rig.s.error_flags() == 0
+            assert torch.equal(rig.dst.view(torch.int16), want_dst.view(torch.int16)), rep
+            n = int(want["n_chunks"].item())
+            for k in ("chunk_start", "chunk_len", "chunk_hash", "chunk_entry"):
+                assert torch.equal(rig.buf[k][:n], want[k][:n]), (rep, k)
+            assert torch.equal(rig.buf["hits"][:n_hits], want["hits"][:n_hits])
+            for k in ("req_chunk_offsets", "n_chunks", "n_hits", "hit_tokens"):
+                assert torch.equal(rig.buf[k], want[k]), (rep, k)
+    finally:
+        rig.close()
