@@ -308,9 +308,8 @@ irm_status irm_s1_windows(irm_ctx *ctx, const uint32_t *d_chunk_start, const uin
  *   d_cursor             uint32[1] in/out: first free pool row
  *   d_admitted_row       int32[chunk_capacity] out: first pool row of chunk c, or -1
  * Deterministic.  Needs table n_slots < 2^32 - 16.  Not to be overlapped with lookups of
- * the same table.  Like irm_table_insert it advances a host-side offer counter of the
- * table (the rank that makes "first offer wins" hold across batches), so a captured graph
- * that contains it must not be replayed. */
+ * the same table.  The rank that makes "first offer wins" hold across batches lives in
+ * device memory, so this call (like irm_table_insert) may be captured and replayed. */
 irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *d_chunk_hash,
                      const uint32_t *d_chunk_start, const uint32_t *d_chunk_len,
                      const uint32_t *d_req_chunk_offsets, const uint32_t *d_req_offsets,

@@ -18,7 +18,7 @@
 #define ADMIT_NONE 0xFFFFFFFFu
 
 __global__ __launch_bounds__(256) void admit_claim(
-    uint64_t *keys, uint32_t *owner, irm_entry *vals, uint64_t n_slots, uint32_t rank0,
+    uint64_t *keys, uint32_t *owner, irm_entry *vals, uint64_t n_slots, uint32_t *state,
     const uint64_t *__restrict__ chunk_hash, const uint32_t *__restrict__ chunk_start,
     const uint32_t *__restrict__ chunk_len, const uint32_t *__restrict__ req_chunk_offsets,
     const uint32_t *__restrict__ req_offsets, const int32_t *__restrict__ pos_base, uint32_t n_req,
@@ -33,11 +33,15 @@ __global__ __launch_bounds__(256) void admit_claim(
     const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t n_chunks = *n_chunks_p;
     if (n_chunks > chunk_capacity) n_chunks = chunk_capacity;
+    // rank base of this batch's bids (see table_claim); the last workgroup advances it
+    const uint32_t rank0 = state[0];
+    const bool room = rank0 <= 0xFFFFFFFEu - chunk_capacity;
+    if (!room && c == 0) atomicOr(err, IRM_FLAG_TABLE_FULL);
     if (c < n_chunks) {
         uint32_t mine = ADMIT_NONE;
         const uint32_t start = chunk_start[c], len = chunk_len[c];
         const int64_t pos = irm_chunk_pos(req_chunk_offsets, req_offsets, pos_base, n_req, c, start);
-        if (chunk_entry[c] < 0 && pos >= (int64_t)carve_out && len != 0) {
+        if (room && chunk_entry[c] < 0 && pos >= (int64_t)carve_out && len != 0) {
             if ((uint64_t)start + len > n_slot_tokens) {
                 atomicOr(err, IRM_FLAG_BAD_CHUNK);
             } else {
@@ -119,6 +123,7 @@ __global__ __launch_bounds__(256) void admit_claim(
     }
     if (threadIdx.x == 0) {
         *cursor = *cursor + admitted_rows_sh;
+        if (room) state[0] = rank0 + chunk_capacity;
         plan[0] = tile_carry_sh < tile_cap ? tile_carry_sh : tile_cap;
         *tickets = 0;
     }
@@ -183,13 +188,11 @@ extern "C" irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *
     if (req_rows < 1 || pool_rows < 1 || req_rows > 0x7FFFFFFFull || pool_rows > 0x7FFFFFFFull)
         return IRM_ERR_INVALID_ARG;
     if (n_req > ctx->cfg.max_requests || chunk_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens ||
-        table->n_slots > 0xFFFFFFF0ull || table->offered + chunk_capacity >= 0xFFFFFFFFull)
+        table->n_slots > 0xFFFFFFF0ull)
         return IRM_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
-    const uint32_t rank0 = (uint32_t)table->offered;
-    table->offered += chunk_capacity;
     hipLaunchKernelGGL(admit_claim, dim3((chunk_capacity + 255) / 256), dim3(256), 0, s, table->d_keys,
-                       table->d_owner, table->d_vals, table->n_slots, rank0, d_chunk_hash, d_chunk_start,
+                       table->d_owner, table->d_vals, table->n_slots, table->d_state, d_chunk_hash, d_chunk_start,
                        d_chunk_len, d_req_chunk_offsets, d_req_offsets, d_pos_base, n_req, d_n_chunks,
                        chunk_capacity, ctx->cfg.carve_out, d_chunk_entry, n_slot_tokens, pool_rows, d_cursor,
                        d_admitted_row, ctx->d_slot_of, ctx->d_tiles, ctx->tile_cap, ctx->d_plan, ctx->d_plan + 3,

@@ -229,6 +229,8 @@ extern "C" irm_status irm_table_create(irm_ctx *ctx, uint64_t n_slots, irm_table
     if (hipMalloc((void **)&t->d_keys, n * 8) != hipSuccess ||
         hipMalloc((void **)&t->d_owner, n * 4) != hipSuccess ||
         hipMalloc((void **)&t->d_vals, n * sizeof(irm_entry)) != hipSuccess ||
+        hipMalloc((void **)&t->d_state, 2 * sizeof(uint32_t)) != hipSuccess ||
+        hipMemset(t->d_state, 0, 2 * sizeof(uint32_t)) != hipSuccess ||
         hipMemset(t->d_keys, 0, n * 8) != hipSuccess ||
         hipMemset(t->d_owner, 0xFF, n * 4) != hipSuccess ||
         hipMemset(t->d_vals, 0, n * sizeof(irm_entry)) != hipSuccess ||
@@ -237,6 +239,7 @@ extern "C" irm_status irm_table_create(irm_ctx *ctx, uint64_t n_slots, irm_table
         if (t->d_keys) (void)hipFree(t->d_keys);
         if (t->d_owner) (void)hipFree(t->d_owner);
         if (t->d_vals) (void)hipFree(t->d_vals);
+        if (t->d_state) (void)hipFree(t->d_state);
         delete t;
         return IRM_ERR_DEVICE;
     }
@@ -251,17 +254,28 @@ extern "C" irm_status irm_table_destroy(irm_table *table)
     if (hipFree(table->d_keys) != hipSuccess) st = IRM_ERR_DEVICE;
     if (hipFree(table->d_owner) != hipSuccess) st = IRM_ERR_DEVICE;
     if (hipFree(table->d_vals) != hipSuccess) st = IRM_ERR_DEVICE;
+    if (hipFree(table->d_state) != hipSuccess) st = IRM_ERR_DEVICE;
     if (st != IRM_OK) (void)hipGetLastError();
     delete table;
     return st;
 }
 
+// Offer ranks: offer i of a batch bids with rank state[0] + i, and state[0] grows by the
+// batch size afterwards, so an earlier batch always outbids a later one.  A batch that
+// would run past 2^32 - 2 offers is refused (IRM_FLAG_TABLE_FULL).
+__device__ __forceinline__ bool irm_rank_room(uint32_t rank0, uint32_t n) { return rank0 <= 0xFFFFFFFEu - n; }
+
 // pass 1: claim a slot per key and record the lowest offer rank that wants it
 __global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *owner, uint64_t n_slots,
                                                    const uint64_t *hash, uint32_t n, const uint32_t *n_p,
-                                                   uint32_t rank0, uint32_t *err)
+                                                   const uint32_t *state, uint32_t *err)
 {
     uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t rank0 = state[0];
+    if (!irm_rank_room(rank0, n)) {
+        if (i == 0) atomicOr(err, IRM_FLAG_TABLE_FULL);
+        return;
+    }
     if (n_p && *n_p < n) n = *n_p;                      // count kept on the device
     if (i >= n) return;
     uint64_t s = irm_claim_slot(keys, n_slots, hash[i]);
@@ -272,26 +286,43 @@ __global__ __launch_bounds__(256) void table_claim(uint64_t *keys, uint32_t *own
     atomicMin(&owner[s], rank0 + i);
 }
 
-// pass 2: the winning offer of a slot that was empty before this batch writes the value
+// pass 2: the winning offer of a slot that was empty before this batch writes the value;
+// the workgroup that finishes last advances the rank base (all have read it by then)
 __global__ __launch_bounds__(256) void table_fill(const uint64_t *keys, const uint32_t *owner,
                                                   irm_entry *vals, uint64_t n_slots,
                                                   const uint64_t *hash, const irm_entry *val,
-                                                  uint32_t n, const uint32_t *n_p, uint32_t rank0)
+                                                  uint32_t n_launch, const uint32_t *n_p, uint32_t *state)
 {
-    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t rank0 = state[0];
+    const bool room = irm_rank_room(rank0, n_launch);
+    uint32_t n = n_launch;
     if (n_p && *n_p < n) n = *n_p;
-    if (i >= n) return;
-    const uint64_t key = hash[i];
-    uint64_t s = n_slots;
-    if (key != 0) {
-        s = irm_slot_of(key, n_slots);
-        uint64_t tries = 0;
-        while (keys[s] != key) {                        // present unless the table was full
-            if (keys[s] == 0 || ++tries >= n_slots) return;
-            s = (s + 1 == n_slots) ? 0 : s + 1;
+    if (room && i < n) {
+        const uint64_t key = hash[i];
+        uint64_t s = n_slots;
+        bool found = true;
+        if (key != 0) {
+            s = irm_slot_of(key, n_slots);
+            uint64_t tries = 0;
+            while (keys[s] != key) {                    // present unless the table was full
+                if (keys[s] == 0 || ++tries >= n_slots) {
+                    found = false;
+                    break;
+                }
+                s = (s + 1 == n_slots) ? 0 : s + 1;
+            }
+        }
+        if (found && owner[s] == rank0 + i) vals[s] = val[i];
+    }
+    __syncthreads();                                    // every lane of this workgroup has read state[0]
+    if (threadIdx.x == 0) {
+        __threadfence();
+        if (atomicAdd(&state[1], 1u) == gridDim.x - 1) {
+            if (room) state[0] = rank0 + n_launch;
+            state[1] = 0;
         }
     }
-    if (owner[s] == rank0 + i) vals[s] = val[i];
 }
 
 static irm_status table_insert(irm_table *table, const uint64_t *d_hash, const irm_entry *d_val, uint32_t n,
@@ -299,15 +330,12 @@ static irm_status table_insert(irm_table *table, const uint64_t *d_hash, const i
 {
     if (!table || (!d_hash && n) || (!d_val && n)) return IRM_ERR_INVALID_ARG;
     if (n == 0) return IRM_OK;
-    if (table->offered + n >= 0xFFFFFFFFull) return IRM_ERR_CAPACITY;
     hipStream_t s = (hipStream_t)stream;
-    const uint32_t rank0 = (uint32_t)table->offered;
     const uint32_t blocks = (n + 255) / 256;
     hipLaunchKernelGGL(table_claim, dim3(blocks), dim3(256), 0, s, table->d_keys, table->d_owner,
-                       table->n_slots, d_hash, n, d_n, rank0, table->ctx->d_err);
+                       table->n_slots, d_hash, n, d_n, table->d_state, table->ctx->d_err);
     hipLaunchKernelGGL(table_fill, dim3(blocks), dim3(256), 0, s, table->d_keys, table->d_owner,
-                       table->d_vals, table->n_slots, d_hash, d_val, n, d_n, rank0);
-    table->offered += n;
+                       table->d_vals, table->n_slots, d_hash, d_val, n, d_n, table->d_state);
     return irm_launch_status();
 }
 

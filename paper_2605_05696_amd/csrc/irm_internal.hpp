@@ -58,7 +58,9 @@ struct irm_ctx {
 struct irm_table {
     irm_ctx *ctx;
     uint64_t n_slots;       // slot n_slots is reserved for the key 0
-    uint64_t offered;       // entries offered so far (ranks first-wins across batches)
+    uint32_t *d_state;      // [0] offers made so far: the rank base that makes "first offer wins" hold
+                            // across batches; [1] ticket counter of table_fill.  Kept on the device so
+                            // that captured launches stay correct when replayed.
     uint64_t *d_keys;       // [n_slots + 1], 0 = empty
     uint32_t *d_owner;      // [n_slots + 1], rank of the winning offer, 0xFFFFFFFF = none
     irm_entry *d_vals;      // [n_slots + 1]

@@ -183,3 +183,67 @@ def test_admit_rejects_bad_arguments_and_flags_bad_slots():
         assert np.array_equal(got[ok], src[ok]) and np.all(got[~ok] == wl.SENTINEL_BF16)   # bad slots are skipped
     finally:
         s.close()
+
+
+def test_serve_and_admit_captured_in_a_graph_replay_over_changing_batches():
+    """serve + admit recorded once; the graph is replayed on batch A, batch B, batch A again
+    (tokens swapped in place between replays).  The registry must accumulate exactly as the
+    oracle's does: the offer ranks that decide "first wins" live on the device."""
+    wa = wl.make_workload("c2", orc.cdc_chunk, size="small", variant=0)
+    wb = wl.make_workload("c2", orc.cdc_chunk, size="small", variant=1)
+    assert np.array_equal(wa.req_offsets, wb.req_offsets) and np.array_equal(wa.pool_tokens, wb.pool_tokens)
+    rig = Rig(wa)
+    w, L = wa, wa.n_layers
+    try:
+        extra = len(w.tokens)
+        pool_rows = w.src_rows + extra
+        pool = torch.cat([rig.src, wl.sentinel_pool_torch(L, extra, DEV)], dim=1).contiguous()
+        pool_ptrs = B.layer_pointers(pool)
+        d_cursor = torch.tensor([w.src_rows], dtype=torch.int32, device=DEV)
+        d_adm = torch.full((rig.buf["cap"],), -7, dtype=torch.int32, device=DEV)
+        stream = torch.cuda.Stream(device=DEV)
+
+        def both():
+            rig.s.serve(rig.d_tokens, rig.d_req_offsets, rig.d_pos_base, rig.d_dst_slots, pool_ptrs, ROW * 2,
+                        pool_rows, rig.dst_ptrs, ROW * 2, w.dst_rows, rig.buf, stream)
+            rig.s.admit(rig.d_req_offsets, rig.d_pos_base, rig.d_dst_slots, rig.dst_ptrs, ROW * 2, w.dst_rows,
+                        pool_ptrs, ROW * 2, pool_rows, d_cursor, d_adm, rig.buf, stream)
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(stream):                                   # recording runs nothing
+            with torch.cuda.graph(graph, stream=stream):
+                both()
+        torch.cuda.synchronize()
+        reg = dict(rig.o["reg"])
+        pool_h, cursor = bits(pool), w.src_rows
+        for rep, wk in enumerate((wa, wb, wa)):
+            rig.d_tokens.copy_(torch.from_numpy(wk.tokens).to(DEV))
+            rig.dst.copy_(wl.kv_pool_torch(L, w.dst_rows, 600 + rep, DEV))     # rows "prefilled" for the misses
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert rig.s.error_flags() == 0
+            st, ln, rco = orc.cdc_chunk(wk.tokens, wk.req_offsets, wk.gear, wk.mask, wk.min_chunk, wk.max_chunk)
+            ch = orc.chunk_hash(wk.tokens, st, ln)
+            entry, hits, hit_tokens = orc.lookup(reg["hash"], reg["src_row"], reg["p_src"], reg["len"], reg["entry_id"],
+                                                 ch, st, ln, rco, wk.req_offsets, wk.pos_base, wk.carve_out)
+            n = len(st)
+            assert int(rig.buf["n_chunks"].item()) == n
+            assert np.array_equal(rig.buf["chunk_entry"].cpu().numpy()[:n], entry), rep
+            assert int(rig.buf["hit_tokens"].item()) == hit_tokens
+            req_h = bits(rig.dst)
+            adm, new, cursor = orc.admit(reg["hash"], ch, st, ln, rco, wk.req_offsets, wk.pos_base, wk.carve_out,
+                                         entry, req_h, wk.dst_slots, pool_h, cursor)
+            assert np.array_equal(d_adm.cpu().numpy()[:n], adm), rep
+            assert int(d_cursor.item()) == cursor
+            assert np.array_equal(bits(pool), pool_h)
+            reg = concat_reg(reg, new)
+            if rep == 2:                                                        # batch A again: nothing left to admit
+                assert np.all(adm < 0)
+                pos_ok = np.concatenate([wk.pos_base[r] + st[rco[r]:rco[r + 1]].astype(np.int64)
+                                         - int(wk.req_offsets[r]) for r in range(wk.n_req)]) >= wk.carve_out
+                assert np.array_equal(entry >= 0, pos_ok)
+            else:
+                assert (adm >= 0).sum() > 0
+    finally:
+        rig.close()
