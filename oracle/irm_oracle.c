@@ -450,3 +450,39 @@ int64_t oracle_s1_windows(const uint32_t *chunk_start, const uint32_t *chunk_len
     req_win_offsets[n_req] = (uint32_t)n_win;
     return n_win;
 }
+
+/* ------------------------------------------------------------------------- */
+/* No-materialise variant (Sec. 7.2 "fuseable into the attention kernel's load */
+/* path"; App. C "keep k_r_base in HBM and fuse the rotation into the load     */
+/* path so the rotated tensor never materialises"): re-attachment writes no KV */
+/* at all, only what the load path needs to rotate on the fly.                 */
+/* For every hit h, j < len[h], slot = dst_slots[dst_tok[h] + j]:              */
+/*   row_index[slot] <- src_row[h] + j     pool row holding (c_KV, k_r_base)   */
+/*   hit_index[slot] <- h                  which rotation the row needs        */
+/* and per hit the rotation itself, trig[h][i] = (cos, sin)(delta[h] *         */
+/* inv_freq[i]) for the 32 pairs, angle as the fp64 product, exactly (1, 0)    */
+/* when delta = 0.  Slots no hit covers are left as they were.                 */
+/* Returns 0, or -1 when an index falls outside its pool.                      */
+/* ------------------------------------------------------------------------- */
+int oracle_reattach_ref(uint64_t src_rows, int32_t *row_index, int32_t *hit_index, uint64_t dst_rows,
+                        double *trig /* [n_hits][32][2] */, const int32_t *dst_slots,
+                        const uint32_t *hit_src_row, const uint32_t *hit_dst_tok,
+                        const uint32_t *hit_len, const int32_t *hit_delta, uint32_t n_hits,
+                        const float *inv_freq)
+{
+    for (uint32_t h = 0; h < n_hits; ++h) {
+        for (int i = 0; i < ORACLE_KR_PAIRS; ++i) {
+            double phi = (double)hit_delta[h] * (double)inv_freq[i];
+            trig[((uint64_t)h * ORACLE_KR_PAIRS + i) * 2 + 0] = hit_delta[h] ? cos(phi) : 1.0;
+            trig[((uint64_t)h * ORACLE_KR_PAIRS + i) * 2 + 1] = hit_delta[h] ? sin(phi) : 0.0;
+        }
+        for (uint32_t j = 0; j < hit_len[h]; ++j) {
+            uint64_t srow = (uint64_t)hit_src_row[h] + j;
+            int64_t slot = dst_slots[(uint64_t)hit_dst_tok[h] + j];
+            if (srow >= src_rows || slot < 0 || (uint64_t)slot >= dst_rows) return -1;
+            row_index[slot] = (int32_t)srow;
+            hit_index[slot] = (int32_t)h;
+        }
+    }
+    return 0;
+}

@@ -51,6 +51,7 @@ def lib():
         L.oracle_reattach_kr.restype = ctypes.c_int
         L.oracle_admit.restype = ctypes.c_int64
         L.oracle_s1_windows.restype = ctypes.c_int64
+        L.oracle_reattach_ref.restype = ctypes.c_int
         L.oracle_bf16_to_f64.restype = ctypes.c_double
         L.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
         L.oracle_f64_to_bf16.restype = ctypes.c_uint16
@@ -295,3 +296,25 @@ def s1_windows(chunk_start, chunk_len, req_chunk_offsets, expand, window=128, an
                                 _p(ws, ctypes.c_uint32), _p(wp, ctypes.c_uint32), _p(rwo, ctypes.c_uint32))
     assert 0 <= n < cap + 1
     return ws[:n].copy(), np.full(n, window, np.uint32), wp[:n].copy(), rwo
+
+
+def reattach_ref(src_rows, row_index, hit_index, dst_slots, hits: Hits, inv_freq) -> np.ndarray:
+    """No-materialise variant, in place on ``row_index`` / ``hit_index`` (i32[dst_rows]).
+    -> trig f64[n_hits][32][2], the (cos, sin) of every hit's 32 pair angles."""
+    assert row_index.dtype == np.int32 and hit_index.dtype == np.int32 and len(row_index) == len(hit_index)
+    assert row_index.flags.c_contiguous and hit_index.flags.c_contiguous
+    dst_slots = _arr(dst_slots, np.int32)
+    inv_freq = _arr(inv_freq, np.float32)
+    hs, hd = _arr(hits.src_row, np.uint32), _arr(hits.dst_tok, np.uint32)
+    hl, hx = _arr(hits.len, np.uint32), _arr(hits.delta, np.int32)
+    if len(hs):
+        assert int((hd.astype(np.int64) + hl).max()) <= len(dst_slots)
+    trig = np.zeros((len(hs), KR_DIM // 2, 2), np.float64)
+    rc = lib().oracle_reattach_ref(
+        ctypes.c_uint64(int(src_rows)), _p(row_index, ctypes.c_int32), _p(hit_index, ctypes.c_int32),
+        ctypes.c_uint64(len(row_index)), _p(trig, ctypes.c_double), _p(dst_slots, ctypes.c_int32),
+        _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32), _p(hx, ctypes.c_int32),
+        ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float))
+    if rc != 0:
+        raise IndexError("oracle_reattach_ref: a hit or slot points outside its pool")
+    return trig

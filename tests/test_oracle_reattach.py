@@ -334,3 +334,43 @@ def test_interleaved_rows_through_the_gather_rotate_scatter():
     idx = np.full(dst_rows, -1, np.int32)
     orc.reattach_kr(src, kr, idx, slots, hits, INV, pair_mode=1)
     assert np.array_equal(kr[:, touched], got[:, touched, 512:]) and np.all(kr[:, ~touched] == 0x7FC1)
+
+
+# ------------------------------------------------- no-materialise variant --
+
+@pytest.mark.parametrize("pair_mode", [0, 1])
+def test_reference_variant_rotated_at_load_time_equals_the_materialised_rows(pair_mode):
+    """What a load path would do with the references and the per-hit (cos, sin) table, done
+    here by numpy in complex arithmetic, must give the rows the materialising oracle writes."""
+    rng = np.random.default_rng(31)
+    L, src_rows, dst_rows = 2, 300, 260
+    src = bf16_bits(rng.standard_normal((L, src_rows, 576)))
+    slots = rng.permutation(dst_rows).astype(np.int32)[:200]
+    hits = orc.Hits(np.array([5, 100, 210], np.uint32), np.array([0, 60, 130], np.uint32),
+                    np.array([60, 70, 50], np.uint32), np.array([-99999, 0, 4097], np.int32))
+    inv = wl.inv_freq_yarn()
+    want = np.full((L, dst_rows, 576), 0x7FC1, np.uint16)
+    orc.reattach(src, want, slots, hits, inv, pair_mode)
+    row_index = np.full(dst_rows, -1, np.int32)
+    hit_index = np.full(dst_rows, -1, np.int32)
+    trig = orc.reattach_ref(src_rows, row_index, hit_index, slots, hits, inv)
+    touched = row_index >= 0
+    assert touched.sum() == 180 and np.array_equal(touched, hit_index >= 0)
+    assert np.all(want[:, ~touched] == 0x7FC1)
+    assert np.array_equal(trig[1], np.tile([1.0, 0.0], (32, 1)))          # delta = 0: the exact identity
+    assert np.max(np.abs(trig[..., 0] ** 2 + trig[..., 1] ** 2 - 1.0)) < 1e-15
+    for slot in np.nonzero(touched)[0]:
+        rows = src[:, row_index[slot]]                                     # [L][576], read "at load time"
+        assert np.array_equal(rows[:, :512], want[:, slot, :512])          # c_KV by reference: the same bits
+        k = orc.bf16_to_f64(rows[:, 512:])
+        a, b = (k[:, 0::2], k[:, 1::2]) if pair_mode else (k[:, :32], k[:, 32:])
+        z = (a + 1j * b) * (trig[hit_index[slot], :, 0] + 1j * trig[hit_index[slot], :, 1])
+        out = np.empty_like(k)
+        if pair_mode:
+            out[:, 0::2], out[:, 1::2] = z.real, z.imag
+        else:
+            out[:, :32], out[:, 32:] = z.real, z.imag
+        got = orc.f64_to_bf16(out)
+        step = np.abs(got.astype(np.int32) - want[:, slot, 512:].astype(np.int32))
+        assert step.max() <= 1                                             # complex product vs the oracle's a c - b s
+        assert (step == 0).mean() > 0.99
