@@ -41,10 +41,12 @@ def main() -> int:
     ap.add_argument("--variants", type=int, default=8, help="request batches cycled through")
     ap.add_argument("--slots", default="contiguous", choices=["contiguous", "permuted"])
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the row kernel (0 = library default)")
-    ap.add_argument("--reattach", default="full", choices=["full", "kr", "kr-dense"],
+    ap.add_argument("--reattach", default="full", choices=["full", "kr", "kr-dense", "ref"],
                     help="full = c_KV copied + k_r rotated (the headline); kr = split-pool variant, "
                          "only the k_r slice is materialised (256 B per token and layer), read from "
-                         "the packed 576-wide source rows; kr-dense = the same from a dense k_r_base pool")
+                         "the packed 576-wide source rows; kr-dense = the same from a dense k_r_base pool; ref = "
+                         "no-materialise variant, only row references and the per-hit rotation table are written "
+                         "(8 B per token, once, not per layer)")
     ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1"],
                     help="hit = the cache-hit path (the headline); admit = the miss path on a cold registry: "
                          "every chunk of the batch is copied from the request pool into the shared pool and "
@@ -120,6 +122,10 @@ def main() -> int:
         dst_ptrs_of = [B.layer_pointers(d) for d in dsts]
         dst, dst_ptrs = dsts[0], dst_ptrs_of[0]
         bytes_per_token_layer = 2 * ROW_BYTES                        # one row read, one written
+    elif args.reattach == "ref":
+        row_index = torch.full((w0.dst_rows,), -1, dtype=torch.int32, device=dev)
+        hit_index = torch.full((w0.dst_rows,), -1, dtype=torch.int32, device=dev)
+        bytes_per_token_layer = 12.0 / L                            # 4 B slot read, 8 B written, per token
     else:
         dst = torch.zeros((L, w0.dst_rows, 64), dtype=torch.bfloat16, device=dev)
         dst_ptrs = B.kr_layer_pointers(dst)
@@ -147,6 +153,8 @@ def main() -> int:
                            dst_slots=torch.from_numpy(w.dst_slots).to(dev),
                            buf=s.alloc_front(len(w.tokens), w.n_req),
                            wbuf=s.alloc_windows(len(w.tokens), w.n_req, 128) if s1 else None))
+        if args.reattach == "ref":
+            dev_in[-1]["trig"] = torch.zeros((dev_in[-1]["buf"]["cap"], 32, 2), dtype=torch.float32, device=dev)
         if args.grid:
             B.irm_ctx_tune(s.ctx, 0, args.grid)
         for kv in filter(None, args.tune.split(",")):
@@ -173,6 +181,9 @@ def main() -> int:
             if s1:
                 s.s1_serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
                            w0.src_rows, dp, ROW_BYTES, w0.dst_rows, d["buf"], d["wbuf"], B.S1_ANCHOR_END, st)
+        elif args.reattach == "ref":
+            s.serve_ref(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], w0.src_rows, row_index,
+                        hit_index, d["trig"], d["buf"], stream)
         else:
             s.serve_kr(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], kr_src_ptrs,
                        kr_src_stride, w0.src_rows, dst_ptrs, 128, w0.dst_rows, ckv_index, d["buf"], stream)
@@ -242,12 +253,12 @@ def main() -> int:
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
                    "variants": n_var, "streams": n_streams, "hip_graph": bool(args.graph), "hit_tokens_per_step": float(np.mean(hit_tokens)),
                    "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s %s"
-                             % ("" if args.reattach == "full" else "_kr",
+                             % ({"full": "", "ref": "_ref"}.get(args.reattach, "_kr"),
                                 "on one stream" if n_streams == 1 else
                                 f"per batch on one stream, {n_streams} batches in flight on {n_streams} streams")
                              + ("; then S1: irm_s1_windows+irm_chunk_hash+irm_lookup+irm_reattach on the windows of "
                                 "the missed chunks" if s1 else "")},
-        "roofline": {"bound": "hbm", "kernel": "reattach_rows" if args.reattach == "full" else "reattach_kr_rows", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": {"full": "reattach_rows", "ref": "reattach_ref_rows"}.get(args.reattach, "reattach_kr_rows"), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_token_layer": bytes_per_token_layer, "launches": kernel_n,
                      "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3,

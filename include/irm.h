@@ -252,6 +252,23 @@ irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
                            const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
                            void *stream);
 
+/* No-materialise variant of the re-attachment (Sec. 7.2: the rotation is "fuseable into
+ * the attention kernel's load path"; App. C: keep k_r_base in HBM so that the rotated
+ * tensor never materialises).  No KV is moved.  For every hit h, j < len and
+ * slot = d_dst_slots[dst_tok + j]:
+ *   d_row_index[slot] = src_row + j   pool row that holds the slot's (c_KV, k_r_base)
+ *   d_hit_index[slot] = h             which rotation the load path applies to that row
+ * and d_trig[h][i] = (cos, sin)(delta_h * inv_freq[i]), i < 32, fp32 pairs in pair order
+ * (exactly (1, 0) when delta = 0; angle reduced in fp64).  The consumer, an attention
+ * kernel that rotates k_r on load, is not part of this library.
+ *   d_row_index, d_hit_index  int32[dst_rows], slots no hit covers are left as they were
+ *   d_trig                    float[hit_capacity][32][2], 8-byte aligned
+ * Bad indices are skipped and flagged like in irm_reattach. */
+irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_index, int32_t *d_hit_index,
+                            uint64_t dst_rows, float *d_trig, const int32_t *d_dst_slots,
+                            uint64_t n_slot_tokens, const irm_hit *d_hits, const uint32_t *d_n_hits,
+                            uint32_t hit_capacity, void *stream);
+
 /* irm_table_insert with the count kept on the device: the first min(*d_n, capacity)
  * pairs are offered (for lists another call of this library produced). */
 irm_status irm_table_insert_counted(irm_table *table, const uint64_t *d_hash, const irm_entry *d_val,

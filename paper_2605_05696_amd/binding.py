@@ -23,7 +23,7 @@ IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_C
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
-           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows")
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows", "irm_reattach_ref")
 
 
 class IrmError(RuntimeError):
@@ -75,6 +75,7 @@ def lib():
         L.irm_table_insert_counted.argtypes = [vp, vp, vp, vp, u32, vp]
         L.irm_s1_windows.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, u32,
                                      vp, vp]
+        L.irm_reattach_ref.argtypes = [vp, u64, vp, vp, u64, vp, vp, u64, vp, vp, u32, vp]
         L.irm_admit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, u64, u64, vp, u64, vp,
                                 u64, u64, vp, vp, vp]
         L.irm_reattach_kr.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, vp, u64, vp, vp, u32, vp]
@@ -345,3 +346,17 @@ def irm_admit(ctx, table, d_chunk_hash, d_chunk_start, d_chunk_len, d_req_chunk_
         _dev(d_slots, i32, "d_slots"), d_slots.numel(), _dev(d_pool_layer_ptrs, i64, "d_pool_layer_ptrs"),
         pool_row_stride_bytes, pool_rows, _dev(d_cursor, i32, "d_cursor"),
         _dev(d_admitted_row, i32, "d_admitted_row"), _stream(stream)))
+
+
+def irm_reattach_ref(ctx, src_rows, d_row_index, d_hit_index, d_trig, d_dst_slots, d_hits, d_n_hits,
+                     stream=None) -> None:
+    """d_trig: float32 device tensor [hit_capacity, 32, 2]."""
+    import torch
+    i32 = torch.int32
+    cap = d_hits.shape[0]
+    if (d_hits.shape != (cap, 4) or d_trig.shape != (cap, 32, 2) or d_row_index.numel() != d_hit_index.numel()):
+        raise TypeError("irm_reattach_ref: array sizes do not match")
+    _check("irm_reattach_ref", lib().irm_reattach_ref(
+        ctx, src_rows, _dev(d_row_index, i32, "d_row_index"), _dev(d_hit_index, i32, "d_hit_index"),
+        d_row_index.numel(), _dev(d_trig, torch.float32, "d_trig"), _dev(d_dst_slots, i32, "d_dst_slots"),
+        d_dst_slots.numel(), _dev(d_hits, i32, "d_hits"), _dev(d_n_hits, i32, "d_n_hits"), cap, _stream(stream)))

@@ -468,6 +468,62 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     return irm_launch_status();
 }
 
+// ---- no-materialise variant (Sec. 7.2, App. C: rotation fused into the attention load path) ----
+// Nothing of the KV is moved: every destination slot learns which pool row holds its
+// (c_KV, k_r_base) and which hit's rotation applies; the per-hit (cos, sin) table goes to
+// the caller's memory in pair order.  Tiles of up to 256 rows, one lane per row.
+#define IRM_REF_TILE_ROWS 256u
+
+__global__ __launch_bounds__(256) void reattach_ref_rows(uint64_t dst_rows, const int32_t *__restrict__ dst_slots,
+                                                         const irm_tile *__restrict__ tiles,
+                                                         const uint32_t *__restrict__ plan,
+                                                         int32_t *__restrict__ row_index,
+                                                         int32_t *__restrict__ hit_index, uint32_t *err)
+{
+    const uint32_t n_tiles = plan[0];
+#pragma nounroll
+    for (uint32_t ti = blockIdx.x; ti < n_tiles; ti += gridDim.x) {
+        const irm_tile t = tiles[ti];
+        if (threadIdx.x >= t.n_rows) continue;
+        const int32_t sl = dst_slots[(uint64_t)t.dst_tok0 + threadIdx.x];
+        if (sl < 0 || (uint64_t)(uint32_t)sl >= dst_rows) {
+            atomicOr(err, IRM_FLAG_ROW_RANGE);
+            continue;
+        }
+        row_index[sl] = (int32_t)(t.src_row0 + threadIdx.x);
+        hit_index[sl] = (int32_t)t.hit;
+    }
+}
+
+extern "C" irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_index, int32_t *d_hit_index,
+                                       uint64_t dst_rows, float *d_trig, const int32_t *d_dst_slots,
+                                       uint64_t n_slot_tokens, const irm_hit *d_hits, const uint32_t *d_n_hits,
+                                       uint32_t hit_capacity, void *stream)
+{
+    if (!ctx || !d_row_index || !d_hit_index || !d_trig || !d_dst_slots || !d_hits || !d_n_hits)
+        return IRM_ERR_INVALID_ARG;
+    if (src_rows < 1 || dst_rows < 1 || src_rows > 0x7FFFFFFFull || dst_rows > 0x7FFFFFFFull || n_slot_tokens < 1 ||
+        hit_capacity < 1 || ((uintptr_t)d_trig & 7))
+        return IRM_ERR_INVALID_ARG;
+    if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(reattach_plan, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,
+                       hit_capacity, ctx->d_inv_freq, src_rows, n_slot_tokens, (float2 *)d_trig, ctx->d_tiles,
+                       ctx->tile_cap, IRM_REF_TILE_ROWS, IRM_PAIR_HALF_SPLIT, ctx->d_plan, ctx->d_err);
+    uint64_t tile_slots = n_slot_tokens / IRM_REF_TILE_ROWS + hit_capacity;
+    if (tile_slots > (1u << 20)) tile_slots = 1u << 20;
+    const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
+                        (ctx->prof_calls++ % ctx->prof_every) == 0;
+    if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
+    hipLaunchKernelGGL(reattach_ref_rows, dim3((uint32_t)tile_slots), dim3(256), 0, s, dst_rows, d_dst_slots,
+                       ctx->d_tiles, ctx->d_plan, d_row_index, d_hit_index, ctx->d_err);
+    if (sample) {
+        IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
+        ++ctx->prof_n;
+    }
+    return irm_launch_status();
+}
+
 extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
                                    uint64_t src_row_stride_bytes, uint64_t src_rows,
                                    void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,

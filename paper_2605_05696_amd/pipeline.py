@@ -145,6 +145,19 @@ class Session:
         B.irm_reattach_kr(self.ctx, src_ptrs, src_stride, src_rows, kr_ptrs, kr_stride, kr_rows,
                           d_ckv_index, d_dst_slots, buf["hits"], buf["n_hits"], stream)
 
+    def serve_ref(self, d_tokens, d_req_offsets, d_pos_base, d_dst_slots, src_rows, d_row_index, d_hit_index,
+                  d_trig, buf, stream=None):
+        """Same front end, no-materialise back end: references and the per-hit rotation table only."""
+        B.irm_cdc_chunk(self.ctx, d_tokens, d_req_offsets, buf["chunk_start"], buf["chunk_len"],
+                        buf["req_chunk_offsets"], buf["n_chunks"], stream)
+        B.irm_chunk_hash(self.ctx, d_tokens, buf["chunk_start"], buf["chunk_len"], buf["n_chunks"],
+                         buf["chunk_hash"], stream)
+        B.irm_lookup(self.ctx, self.table, buf["chunk_hash"], buf["chunk_start"], buf["chunk_len"],
+                     buf["req_chunk_offsets"], d_req_offsets, d_pos_base, buf["n_chunks"],
+                     buf["chunk_entry"], buf["hits"], buf["n_hits"], buf["hit_tokens"], stream)
+        B.irm_reattach_ref(self.ctx, src_rows, d_row_index, d_hit_index, d_trig, d_dst_slots, buf["hits"],
+                           buf["n_hits"], stream)
+
     def admit(self, d_req_offsets, d_pos_base, d_slots, req_ptrs, req_stride, req_rows, pool_ptrs, pool_stride,
               pool_rows, d_cursor, d_admitted_row, buf, stream=None):
         """Miss path after the engine prefilled the missed chunks into the request's slots:

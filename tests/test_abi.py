@@ -21,7 +21,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported():
     names = declared_functions()
-    assert len(names) >= 18
+    assert len(names) >= 19
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -78,6 +78,7 @@ def test_null_arguments_are_rejected():
     assert L.irm_admit(*([None] * 8), 0, None, 0, None, None, 0, 0, None, 0, None, 0, 0, None, None, None) == B.IRM_ERR_INVALID_ARG
     assert L.irm_s1_windows(*([None] * 4), 0, None, 0, None, 0, 0, 0, *([None] * 7), 0, None, None) == B.IRM_ERR_INVALID_ARG
     assert L.irm_table_insert_counted(None, None, None, None, 0, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_reattach_ref(None, 1, None, None, 1, None, None, 1, None, None, 1, None) == B.IRM_ERR_INVALID_ARG
     flags = ctypes.c_uint32()
     assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG

@@ -446,3 +446,74 @@ def test_hot_path_captured_in_a_graph_replays_like_eager():
                 assert torch.equal(rig.buf[k], want[k]), (rep, k)
     finally:
         rig.close()
+
+
+# ------------------------------------------------- no-materialise variant --
+
+@pytest.mark.parametrize("name", ["c0", "c1", "c2", "c3", "c4"])
+@pytest.mark.parametrize("slots", ["contiguous", "permuted"])
+def test_reattach_ref_small_configs(name, slots):
+    """References bit for bit; the rotation table within one fp32 step of the oracle's fp64 values,
+    and good enough that rotating at load time lands within the k_r tolerance."""
+    w = small(name, slots=slots)
+    o = oracle_front(w)
+    hits = o["hits"]
+    s = Session.for_workload(w, DEV)
+    try:
+        cap = max(len(hits), 1) + 5
+        d_hits, d_n = hits_to_dev(hits, cap)
+        row = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        hit = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.full((cap, 32, 2), 9.0, dtype=torch.float32, device=DEV)
+        B.irm_reattach_ref(s.ctx, w.src_rows, row, hit, trig, torch.from_numpy(w.dst_slots).to(DEV), d_hits, d_n)
+        torch.cuda.synchronize()
+        assert s.error_flags() == 0
+        want_row = np.full(w.dst_rows, -1, np.int32)
+        want_hit = np.full(w.dst_rows, -1, np.int32)
+        want_trig = orc.reattach_ref(w.src_rows, want_row, want_hit, w.dst_slots, hits, w.inv_freq)
+        assert np.array_equal(row.cpu().numpy(), want_row) and np.array_equal(hit.cpu().numpy(), want_hit)
+        got_trig = trig.cpu().numpy()
+        n = len(hits)
+        assert np.all(got_trig[n:] == 9.0)                                   # nothing past the hit count
+        err = np.abs(got_trig[:n].astype(np.float64) - want_trig)
+        assert err.max() <= 2.0 ** -23                                       # fp32 rounding of values in [-1, 1]
+        zero = hits.delta == 0
+        assert np.all(got_trig[:n][zero] == np.array([1.0, 0.0], np.float32))
+        # a load path using this table: rows of layer 0 of a few hits
+        src = wl.kv_pool_torch(1, w.src_rows, wl.kv_seed(name), DEV)
+        src_h = bits(src)
+        for h in range(0, n, max(1, n // 6)):
+            rows = src_h[0, hits.src_row[h]:hits.src_row[h] + hits.len[h]]
+            k = orc.bf16_to_f64(rows[:, 512:])
+            z = (k[:, :32] + 1j * k[:, 32:]) * (got_trig[h, :, 0].astype(np.float64) + 1j * got_trig[h, :, 1])
+            lazy = rows.copy()
+            lazy[:, 512:] = orc.f64_to_bf16(np.concatenate([z.real, z.imag], axis=1))
+            want = np.stack([orc.reattach_row(r, int(hits.delta[h]), w.inv_freq) for r in rows])
+            compare_rows(lazy[None], want[None], what=f"{w.name} hit {h} rotated at load")
+    finally:
+        s.close()
+
+
+def test_reattach_ref_bad_indices_are_skipped_and_flagged():
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, 1, wl.inv_freq_plain(), 4096, 1, DEV)
+    try:
+        hits = orc.Hits(np.array([0, 90, 10], np.uint32), np.array([0, 300, 600], np.uint32),
+                        np.array([300, 300, 100], np.uint32), np.array([5, -5, 0], np.int32))   # hit 1 leaves the pool
+        d_hits, d_n = hits_to_dev(hits, 4)
+        slots = np.arange(700, dtype=np.int32)
+        slots[7] = 900                                                       # outside the destination
+        row = torch.full((800,), -1, dtype=torch.int32, device=DEV)
+        hit = torch.full((800,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.zeros((4, 32, 2), dtype=torch.float32, device=DEV)
+        B.irm_reattach_ref(s.ctx, 350, row, hit, trig, torch.from_numpy(slots).to(DEV), d_hits, d_n)
+        torch.cuda.synchronize()
+        assert s.error_flags() == B.IRM_FLAG_ROW_RANGE
+        r = row.cpu().numpy()
+        want = np.full(800, -1, np.int32)
+        want[:300] = np.arange(300)
+        want[7] = -1
+        want[600:700] = 10 + np.arange(100)
+        assert np.array_equal(r, want)
+        assert np.array_equal(hit.cpu().numpy() >= 0, want >= 0)
+    finally:
+        s.close()
