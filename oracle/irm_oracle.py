@@ -318,3 +318,57 @@ def reattach_ref(src_rows, row_index, hit_index, dst_slots, hits: Hits, inv_freq
     if rc != 0:
         raise IndexError("oracle_reattach_ref: a hit or slot points outside its pool")
     return trig
+
+
+def attend_ref(q_bits, pool_bits, kv_slots, kv_offsets, row_index, hit_index, trig, scale, pair_mode=0):
+    """The consumer of the no-materialise variant: MLA decode attention in the latent ("absorbed")
+    form (Sec. 2 "MLA": per token a 512-dim c_KV and a 64-dim RoPE key k_r, V derived from c_KV),
+    reading (c_KV, k_r_base) through the references and rotating k_r by the hit's R(delta) as it
+    is loaded (Sec. 7.2; App. C).  One layer.  For request b, head h and the request's context
+    slots s_0 .. s_{n-1} = kv_slots[kv_offsets[b] : kv_offsets[b+1]]:
+
+        row_t   = row_index[s_t]                      k_t = [ c_KV(row_t) | R_t k_r_base(row_t) ]
+        R_t     = rotation of hit hit_index[s_t] from ``trig`` (identity when hit_index < 0)
+        score_t = scale * q[b][h] . k_t               p = softmax over t
+        out[b][h] = sum_t p_t c_KV(row_t)             lse[b][h] = log sum_t exp(score_t)
+
+    q_bits [B][H][576] and pool_bits [rows][576] are bf16 bit patterns, everything is computed in
+    fp64, nothing is rounded.  A request without context gives out = 0, lse = -inf.
+    -> (out f64 [B][H][512], lse f64 [B][H])"""
+    q = bf16_to_f64(np.asarray(q_bits, np.uint16))
+    pool_bits = np.asarray(pool_bits, np.uint16)
+    kv_slots = np.asarray(kv_slots, np.int64)
+    kv_offsets = np.asarray(kv_offsets, np.int64)
+    row_index = np.asarray(row_index, np.int64)
+    hit_index = np.asarray(hit_index, np.int64)
+    n_req, n_heads = q.shape[0], q.shape[1]
+    assert q.shape[2] == ROW_DIM and pool_bits.shape[1] == ROW_DIM and len(kv_offsets) == n_req + 1
+    out = np.zeros((n_req, n_heads, CKV_DIM), np.float64)
+    lse = np.full((n_req, n_heads), -np.inf, np.float64)
+    half = KR_DIM // 2
+    for b in range(n_req):
+        slots = kv_slots[kv_offsets[b]:kv_offsets[b + 1]]
+        if len(slots) == 0:
+            continue
+        rows = row_index[slots]
+        assert rows.min() >= 0 and rows.max() < pool_bits.shape[0]
+        k = bf16_to_f64(pool_bits[rows])                               # [n][576]
+        hit = hit_index[slots]
+        c = np.ones((len(slots), half))
+        s = np.zeros((len(slots), half))
+        on = hit >= 0
+        c[on], s[on] = trig[hit[on], :, 0], trig[hit[on], :, 1]
+        kr = k[:, CKV_DIM:]
+        ia, ib = (np.arange(0, KR_DIM, 2), np.arange(1, KR_DIM, 2)) if pair_mode else \
+            (np.arange(half), np.arange(half) + half)
+        rot = np.empty_like(kr)
+        rot[:, ia] = kr[:, ia] * c - kr[:, ib] * s
+        rot[:, ib] = kr[:, ib] * c + kr[:, ia] * s
+        keys = np.concatenate([k[:, :CKV_DIM], rot], axis=1)
+        score = scale * (q[b] @ keys.T)                                # [H][n]
+        top = score.max(axis=1, keepdims=True)
+        e = np.exp(score - top)
+        z = e.sum(axis=1, keepdims=True)
+        out[b] = (e / z) @ k[:, :CKV_DIM]
+        lse[b] = (top + np.log(z))[:, 0]
+    return out, lse
