@@ -269,6 +269,35 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
                             uint64_t n_slot_tokens, const irm_hit *d_hits, const uint32_t *d_n_hits,
                             uint32_t hit_capacity, void *stream);
 
+/* The consumer of irm_reattach_ref: MLA decode attention in the latent form, one layer
+ * (Sec. 2 "MLA": per token a 512-dim c_KV and a 64-dim RoPE key, V derived from c_KV;
+ * Sec. 7.2, App. C: the delta-rotation fused into the attention load path).  For request
+ * b, head h and the request's context slots s_t = d_kv_slots[d_kv_offsets[b] + t]:
+ *   row_t = d_row_index[s_t],  R_t = rotation d_trig[d_hit_index[s_t]] (identity if < 0)
+ *   score_t = scale * q[b][h] . [ c_KV(row_t) | R_t k_r_base(row_t) ],  p = softmax_t
+ *   d_out[b][h][0:512] = sum_t p_t c_KV(row_t),   d_lse[b][h] = log sum_t exp(score_t)
+ * k_r is rotated in fp32 and rounded once to bf16 while the rows are staged on chip (the
+ * values irm_reattach would have written); products in bf16 MFMA with fp32 accumulation.
+ *   d_q            bf16 [n_req][n_heads][576] (latent-space query | rotary query), 16-byte aligned;
+ *                  n_heads a multiple of 16, at most 128
+ *   d_pool_layer   one layer of the pool, rows of 576 bf16 at pool_row_stride_bytes
+ *   d_kv_slots     int32, d_kv_offsets uint32[n_req + 1]: CSR of every request's context slots
+ *   d_row_index, d_hit_index  int32[dst_rows] as written by irm_reattach_ref (plain rows of
+ *                  prefilled tokens: any pool row with hit index -1)
+ *   d_trig         float[trig_hits][32][2] as written by irm_reattach_ref
+ *   n_splits       workgroups per request and 16 heads (split of the context, merged afterwards)
+ *   d_workspace    irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) bytes, 16-byte aligned
+ *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]
+ * A request without context gives out = 0, lse = -inf.  A slot, row or hit index out of
+ * range leaves that token out and raises IRM_FLAG_ROW_RANGE. */
+uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
+irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
+                          const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,
+                          const int32_t *d_kv_slots, const uint32_t *d_kv_offsets, const int32_t *d_row_index,
+                          const int32_t *d_hit_index, uint64_t dst_rows, const float *d_trig, uint32_t trig_hits,
+                          float scale, uint32_t n_splits, void *d_workspace, uint64_t workspace_bytes,
+                          float *d_out, float *d_lse, void *stream);
+
 /* irm_table_insert with the count kept on the device: the first min(*d_n, capacity)
  * pairs are offered (for lists another call of this library produced). */
 irm_status irm_table_insert_counted(irm_table *table, const uint64_t *d_hash, const irm_entry *d_val,

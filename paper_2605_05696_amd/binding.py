@@ -23,7 +23,7 @@ IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_C
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
-           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows", "irm_reattach_ref")
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows", "irm_reattach_ref", "irm_attend_ref", "irm_attend_ref_workspace_bytes")
 
 
 class IrmError(RuntimeError):
@@ -76,6 +76,10 @@ def lib():
         L.irm_s1_windows.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, u32,
                                      vp, vp]
         L.irm_reattach_ref.argtypes = [vp, u64, vp, vp, u64, vp, vp, u64, vp, vp, u32, vp]
+        L.irm_attend_ref_workspace_bytes.argtypes = [u32, u32, u32]
+        L.irm_attend_ref_workspace_bytes.restype = u64
+        L.irm_attend_ref.argtypes = [vp, vp, u32, u32, vp, u64, u64, vp, vp, vp, vp, u64, vp, u32, ctypes.c_float, u32,
+                                     vp, u64, vp, vp, vp]
         L.irm_admit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, u64, u64, vp, u64, vp,
                                 u64, u64, vp, vp, vp]
         L.irm_reattach_kr.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, vp, u64, vp, vp, u32, vp]
@@ -360,3 +364,28 @@ def irm_reattach_ref(ctx, src_rows, d_row_index, d_hit_index, d_trig, d_dst_slot
         ctx, src_rows, _dev(d_row_index, i32, "d_row_index"), _dev(d_hit_index, i32, "d_hit_index"),
         d_row_index.numel(), _dev(d_trig, torch.float32, "d_trig"), _dev(d_dst_slots, i32, "d_dst_slots"),
         d_dst_slots.numel(), _dev(d_hits, i32, "d_hits"), _dev(d_n_hits, i32, "d_n_hits"), cap, _stream(stream)))
+
+
+def irm_attend_ref(ctx, d_q, d_pool_layer, pool_row_stride_bytes, d_kv_slots, d_kv_offsets, d_row_index,
+                   d_hit_index, d_trig, scale, n_splits, d_workspace, d_out, d_lse, stream=None) -> None:
+    """d_q: bf16 [n_req, n_heads, 576]; d_pool_layer: bf16 [rows, >= 576] (one layer);
+    d_out: float32 [n_req, n_heads, 512]; d_lse: float32 [n_req, n_heads]; d_workspace: uint8 tensor."""
+    import torch
+    i32 = torch.int32
+    n_req, n_heads = d_q.shape[0], d_q.shape[1]
+    if (d_q.dtype != torch.bfloat16 or d_q.shape[2] != 576 or not d_q.is_contiguous() or
+            d_pool_layer.dtype != torch.bfloat16 or d_out.shape != (n_req, n_heads, 512) or
+            d_lse.shape != (n_req, n_heads) or d_kv_offsets.numel() != n_req + 1 or
+            d_row_index.numel() != d_hit_index.numel() or d_trig.dim() != 3 or d_trig.shape[1:] != (32, 2)):
+        raise TypeError("irm_attend_ref: array shapes or types do not match")
+    _check("irm_attend_ref", lib().irm_attend_ref(
+        ctx, d_q.data_ptr(), n_req, n_heads, d_pool_layer.data_ptr(), pool_row_stride_bytes, d_pool_layer.shape[0],
+        _dev(d_kv_slots, i32, "d_kv_slots"), _dev(d_kv_offsets, i32, "d_kv_offsets"),
+        _dev(d_row_index, i32, "d_row_index"), _dev(d_hit_index, i32, "d_hit_index"), d_row_index.numel(),
+        _dev(d_trig, torch.float32, "d_trig"), d_trig.shape[0], float(scale), n_splits,
+        d_workspace.data_ptr(), d_workspace.numel() * d_workspace.element_size(),
+        _dev(d_out, torch.float32, "d_out"), _dev(d_lse, torch.float32, "d_lse"), _stream(stream)))
+
+
+def irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) -> int:
+    return int(lib().irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits))
