@@ -16,12 +16,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "irm.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\birm_status\s+(irm_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"^(?:irm_status|uint64_t)\s+(irm_\w+)\s*\(", text, flags=re.M)))
 
 
 def test_every_declared_symbol_is_exported():
     names = declared_functions()
-    assert len(names) >= 19
+    assert len(names) >= 21
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
@@ -79,6 +79,9 @@ def test_null_arguments_are_rejected():
     assert L.irm_s1_windows(*([None] * 4), 0, None, 0, None, 0, 0, 0, *([None] * 7), 0, None, None) == B.IRM_ERR_INVALID_ARG
     assert L.irm_table_insert_counted(None, None, None, None, 0, None) == B.IRM_ERR_INVALID_ARG
     assert L.irm_reattach_ref(None, 1, None, None, 1, None, None, 1, None, None, 1, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_attend_ref(*([None] * 2), 1, 16, None, 1152, 1, *([None] * 4), 1, None, 0, ctypes.c_float(1.0), 1, None, 0,
+                            None, None, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_attend_ref_workspace_bytes(2, 16, 3) == 2 * 16 * 3 * 514 * 4
     flags = ctypes.c_uint32()
     assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG
