@@ -47,12 +47,16 @@ def main() -> int:
                          "the packed 576-wide source rows; kr-dense = the same from a dense k_r_base pool; ref = "
                          "no-materialise variant, only row references and the per-hit rotation table are written "
                          "(8 B per token, once, not per layer)")
-    ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1"],
+    ap.add_argument("--heads", type=int, default=16, help="attend stage: query heads (multiple of 16)")
+    ap.add_argument("--splits", type=int, default=8, help="attend stage: workgroups per request and 16 heads")
+    ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1", "attend"],
                     help="hit = the cache-hit path (the headline); admit = the miss path on a cold registry: "
                          "every chunk of the batch is copied from the request pool into the shared pool and "
                          "registered (irm_admit alone is timed, with events on its stream); s1 = the hit path "
                          "on UNALIGNED batches followed by the S1 fallback (128-token windows inside the chunks "
-                         "that missed, end-anchored): eight calls per step")
+                         "that missed, end-anchored): eight calls per step; attend = the no-materialise scheme end to end: "
+                         "front end + irm_reattach_ref once, then irm_attend_ref (decode attention over the "
+                         "references, k_r rotated on load) on every layer")
     ap.add_argument("--streams", type=int, default=1,
                     help="batches in flight: step k runs on stream k mod S with its own context and destination "
                          "pool, so the front end of one batch overlaps the row kernel of another (hit and s1 "
@@ -163,6 +167,14 @@ def main() -> int:
     streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
     stream = streams[0]
     torch.cuda.synchronize()
+    if args.stage == "attend":
+        with torch.cuda.stream(stream):
+            calibrate(args.calibrate, dev, stream)
+        out = bench_attend(args, works, sessions, dev_in, src, stream)
+        for s in sessions:
+            s.close()
+        print(json.dumps(out), flush=True)
+        return 0
     if args.stage == "admit":
         with torch.cuda.stream(stream):
             calibrate(args.calibrate, dev, stream)
@@ -276,6 +288,80 @@ def main() -> int:
         s.close()
     print(json.dumps(out), flush=True)
     return 0
+
+
+def bench_attend(args, works, sessions, dev_in, pool, stream):
+    """The no-materialise scheme end to end for one decode step of a batch: chunk, fingerprint,
+    look up, write the references (irm_reattach_ref), then attend over them on every layer
+    (irm_attend_ref, one query token per request, k_r rotated as the rows are staged)."""
+    import torch
+    from paper_2605_05696_amd import binding as B
+
+    w0 = works[0]
+    L, dev, H = w0.n_layers, pool.device, args.heads
+    n_req = w0.n_req
+    scale = 1.0 / np.sqrt(192.0)
+    q = torch.randn((n_req, H, 576), device=dev, generator=torch.Generator(dev).manual_seed(1)).to(torch.bfloat16)
+    out = torch.zeros((n_req, H, 512), dtype=torch.float32, device=dev)
+    lse = torch.zeros((n_req, H), dtype=torch.float32, device=dev)
+    ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, H, args.splits), dtype=torch.uint8, device=dev)
+    for v, (s, d, w) in enumerate(zip(sessions, dev_in, works)):
+        d["row"] = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=dev)
+        d["hit"] = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=dev)
+        d["trig"] = torch.zeros((d["buf"]["cap"], 32, 2), dtype=torch.float32, device=dev)
+
+    def step(v):
+        s, d = sessions[v], dev_in[v]
+        s.serve_ref(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], w0.src_rows, d["row"], d["hit"],
+                    d["trig"], d["buf"], stream)
+        for l in range(L):
+            B.irm_attend_ref(s.ctx, q, pool[l], ROW_BYTES, d["dst_slots"], d["req_offsets"], d["row"], d["hit"],
+                             d["trig"], scale, args.splits, ws, out, lse, stream)
+
+    with torch.cuda.stream(stream):
+        for v in range(len(works)):                              # first pass: the tokens no hit covers get
+            step(v)                                              # plain pool rows ("prefilled and admitted")
+            stream.synchronize()
+            sessions[v].error_flags()                            # the first pass met unfilled slots: clear the word
+            d = dev_in[v]
+            miss = d["row"] < 0
+            d["row"][miss] = torch.randint(0, w0.src_rows, (int(miss.sum().item()),), device=dev, dtype=torch.int32)
+            step(v)
+            stream.synchronize()
+            assert sessions[v].error_flags() == 0
+        for k in range(args.warmup):
+            step(k % len(works))
+        for s in sessions:
+            if args.kernel_timing:
+                B.irm_ctx_profile_begin(s.ctx, (args.steps // len(works) + 1) * L, 1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(k % len(works))
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        kernel_ms, kernel_n = 0.0, 0
+        for s in sessions:
+            ms, n = B.irm_ctx_profile_end(s.ctx, stream)
+            kernel_ms += ms
+            kernel_n += n
+    ctx_tokens = len(w0.tokens)                                  # every request attends over all of its tokens
+    groups = H // 16
+    alg = ctx_tokens * ROW_BYTES * groups                        # per layer launch: each row once per 16 heads
+    achieved = alg * kernel_n / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
+    return {"metric": "attended context tokens/s (all layers), no-materialise scheme: front end + references + "
+                      "rotate-on-load decode attention, 1 MI355X",
+            "value": ctx_tokens * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"{w0.name}: {n_req} request(s), one decode query each over its whole context "
+                                   f"({ctx_tokens} tokens in all), {H} heads, {L} layers, splits {args.splits}",
+                       "variants": len(works),
+                       "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach_ref once, irm_attend_ref per layer"},
+            "roofline": {"bound": "hbm", "kernel": "attend_ref_split+attend_ref_merge", "achieved": achieved,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                         "bytes_per_token_layer": ROW_BYTES * groups, "launches": kernel_n,
+                         "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3}}
 
 
 def calibrate(n, dev, stream):

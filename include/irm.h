@@ -284,7 +284,7 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  *   d_kv_slots     int32, d_kv_offsets uint32[n_req + 1]: CSR of every request's context slots
  *   d_row_index, d_hit_index  int32[dst_rows] as written by irm_reattach_ref (plain rows of
  *                  prefilled tokens: any pool row with hit index -1)
- *   d_trig         float[trig_hits][32][2] as written by irm_reattach_ref
+ *   d_trig         float[trig_hits][32][2] as written by irm_reattach_ref, trig_hits >= 1
  *   n_splits       workgroups per request and 16 heads (split of the context, merged afterwards)
  *   d_workspace    irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) bytes, 16-byte aligned
  *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]

@@ -7,10 +7,11 @@
 //   score[b][h][t] = scale * q[b][h] . [ c_KV(row_t) | R_t k_r_base(row_t) ]
 //   out[b][h]      = sum_t softmax_t(score) c_KV(row_t)
 //
-//   attend_ref_split   grid (splits, head groups of 16, requests), 4 waves.  A workgroup walks
-//       its share of the request's tokens in tiles of 64: the 64 rows (1152 B each) are
-//       gathered into LDS with 16-byte loads, k_r is rotated in place there (fp32, one
-//       rounding to bf16: the same values the materialising kernel writes), then
+//   attend_ref_split   grid (splits, head groups of 16, requests), 8 waves.  A workgroup walks
+//       its share of the request's tokens in tiles of 64.  Four waves fetch: the tile's 64
+//       rows (1152 B each) come from HBM into registers with 16-byte loads, k_r is rotated
+//       there (fp32, one rounding to bf16: the same values the materialising kernel writes)
+//       and the tile lands in one of two LDS buffers.  Four waves compute on the other buffer:
 //         S = Q K^T     wave w: 16 heads x its 16 tokens, 18 MFMA 16x16x32 (bf16 in, fp32 acc)
 //         online softmax over the tile (running max per head shared through LDS)
 //         O += P V      wave w: 16 heads x its 128 of the 512 latent dims, 16 MFMA
@@ -41,15 +42,131 @@ __device__ __forceinline__ uint32_t att_to_bf16(float x)
 }
 
 struct att_smem {
-    uint16_t k[ATT_TILE * ATT_KROW];   // staged rows, k_r rotated
-    uint16_t p[ATT_HEADS * ATT_PROW];  // softmax numerators of the tile, bf16
-    float red[4 * ATT_HEADS];          // per wave and head: tile maximum
-    float mfin[ATT_HEADS];             // running maximum per head at the end
-    int32_t row[ATT_TILE];             // pool row of each tile token, -1 = no token
-    int32_t hit[ATT_TILE];             // rotation of each tile token, -1 = none
+    uint16_t k[2][ATT_TILE * ATT_KROW]; // staged rows, k_r rotated: the tile in work and the next one
+    uint16_t p[ATT_HEADS * ATT_PROW];   // softmax numerators of the tile, bf16
+    float red[4 * ATT_HEADS];           // per compute wave and head: tile maximum / final sums
+    float mfin[ATT_HEADS];              // running maximum per head at the end
+    int32_t row[4][ATT_TILE];           // pool row of each tile token, -1 = no token; slot = tile mod 4
+    int32_t hit[4][ATT_TILE];           // rotation of each tile token, -1 = none
 };
 
-__global__ __launch_bounds__(256) void attend_ref_split(
+// Barrier that orders LDS traffic only: global loads issued before it stay in flight.
+#define ATT_SYNC()                                                          \
+    do {                                                                    \
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");     \
+        __builtin_amdgcn_s_barrier();                                       \
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
+    } while (0)
+
+// ---- fetch half: waves 4..7 -------------------------------------------------------------------
+// A fetch lane holds, of a tile's 64 rows: c_KV vector `lane` of rows cw + 4j (a wave reads whole
+// 1024-byte c_KV spans), and the two k_r vectors that hold pair partners of row ct / 4.  Two
+// register sets: the rows of two tiles are in flight while a third is being worked on.  There is
+// no branch around a load and no load whose result is needed at once: a wave's memory counter is
+// in order, so waiting for anything younger would wait for every row in flight.
+struct att_args {
+    const char *pool;
+    uint64_t pool_stride;
+    const float2 *trig;
+    uint32_t pair_mode;
+};
+
+__device__ __forceinline__ void att_issue_rows(u32x4 (&vc)[ATT_KSTEPS], const att_smem *sm, uint32_t slot,
+                                               const att_args &a, uint32_t cw, uint32_t lane, uint32_t ct)
+{
+    // an absent token reads row 0 and is zeroed when the tile lands
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int32_t row = sm->row[slot][cw + 4u * (uint32_t)j];
+        const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
+        vc[j] = __builtin_nontemporal_load((const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride) + lane);
+    }
+    const uint32_t kr_row = ct >> 2, kj = ct & 3u;
+    const int32_t row = sm->row[slot][kr_row];
+    const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
+    const u32x4 *kr = (const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride + IRM_CKV_BYTES);
+    // half-split: elements 8 kj .. and their partners; interleaved: pairs 8 kj .. 8 kj + 7, whole
+    const uint32_t ia = a.pair_mode == IRM_PAIR_HALF_SPLIT ? kj : 2u * kj;
+    const uint32_t ib = a.pair_mode == IRM_PAIR_HALF_SPLIT ? 4u + kj : 2u * kj + 1u;
+    vc[16] = __builtin_nontemporal_load(kr + ia);
+    vc[17] = __builtin_nontemporal_load(kr + ib);
+}
+
+// the (cos, sin) a lane needs for the tile it lands next; requested BEFORE newer rows are
+__device__ __forceinline__ int32_t att_load_trig(f32x4 (&t4)[4], const att_smem *sm, uint32_t slot,
+                                                 const att_args &a, uint32_t ct)
+{
+    const int32_t hit = sm->hit[slot][ct >> 2];
+    const uint32_t safe = hit >= 0 ? (uint32_t)hit : 0u;    // entry 0 always exists
+    const f32x4 *tp = (const f32x4 *)(a.trig + (uint64_t)safe * IRM_KR_PAIRS + 8u * (ct & 3u));
+#pragma unroll
+    for (int w = 0; w < 4; ++w) t4[w] = tp[w];              // (c, s, c, s) of two pairs each
+    return hit;
+}
+
+// rotate k_r in registers (fp32, one rounding to bf16), store the tile into LDS buffer `buf`
+__device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_KSTEPS], const f32x4 (&t4)[4], int32_t hit,
+                                              att_smem *sm, uint32_t slot, uint32_t buf, const att_args &a,
+                                              uint32_t cw, uint32_t lane, uint32_t ct)
+{
+    u32x4 va = vc[16], vb = vc[17];
+    const uint32_t kr_row = ct >> 2, kj = ct & 3u;
+    if (hit >= 0) {
+        if (a.pair_mode == IRM_PAIR_HALF_SPLIT) {
+            uint32_t aw[4] = {va.x, va.y, va.z, va.w}, bw[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float a0 = att_bf16_lo(aw[w]), a1 = att_bf16_hi(aw[w]);
+                const float b0 = att_bf16_lo(bw[w]), b1 = att_bf16_hi(bw[w]);
+                const float c0 = t4[w].x, s0 = t4[w].y, c1 = t4[w].z, s1 = t4[w].w;
+                aw[w] = att_to_bf16(a0 * c0 - b0 * s0) | (att_to_bf16(a1 * c1 - b1 * s1) << 16);
+                bw[w] = att_to_bf16(b0 * c0 + a0 * s0) | (att_to_bf16(b1 * c1 + a1 * s1) << 16);
+            }
+            va = u32x4{aw[0], aw[1], aw[2], aw[3]};
+            vb = u32x4{bw[0], bw[1], bw[2], bw[3]};
+        } else {                                            // one word = one pair (a, b)
+            uint32_t w8[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                const float a0 = att_bf16_lo(w8[w]), b0 = att_bf16_hi(w8[w]);
+                const float c0 = (w & 1) ? t4[w >> 1].z : t4[w >> 1].x;
+                const float s0 = (w & 1) ? t4[w >> 1].w : t4[w >> 1].y;
+                w8[w] = att_to_bf16(a0 * c0 - b0 * s0) | (att_to_bf16(b0 * c0 + a0 * s0) << 16);
+            }
+            va = u32x4{w8[0], w8[1], w8[2], w8[3]};
+            vb = u32x4{w8[4], w8[5], w8[6], w8[7]};
+        }
+    }
+    uint16_t *kt = sm->k[buf];
+    const u32x4 zero = {0, 0, 0, 0};
+    // two base addresses, the rest are immediate offsets of the LDS stores
+    uint16_t *lo = kt + cw * ATT_KROW + lane * 8u, *hi = lo + 32u * ATT_KROW;
+    const int32_t *rows = sm->row[slot] + cw;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        *(u32x4 *)(lo + 4 * j * ATT_KROW) = rows[4 * j] >= 0 ? vc[j] : zero;
+        *(u32x4 *)(hi + 4 * j * ATT_KROW) = rows[32 + 4 * j] >= 0 ? vc[8 + j] : zero;
+    }
+    if (sm->row[slot][kr_row] < 0) {
+        va = zero;
+        vb = zero;
+    }
+    uint16_t *kr = kt + kr_row * ATT_KROW + IRM_CKV_BYTES / 2;
+    if (a.pair_mode == IRM_PAIR_HALF_SPLIT) {
+        *(u32x4 *)(kr + 8 * kj) = va;
+        *(u32x4 *)(kr + 32 + 8 * kj) = vb;
+    } else {
+        *(u32x4 *)(kr + 16 * kj) = va;
+        *(u32x4 *)(kr + 16 * kj + 8) = vb;
+    }
+}
+
+// 8 waves: waves 0..3 compute, waves 4..7 fetch; each half runs its own loop (so that each gets
+// the whole register file for what it alone needs) and both meet at the same barriers: two in
+// the prologue, three per tile (B: tile maxima published, C: P complete, D: buffers change
+// roles), one at the end.  While the compute waves work on tile i in one LDS buffer, the fetch
+// waves request tile i + 2 from HBM and land tile i + 1, requested a tile ago, in the other.
+__global__ __launch_bounds__(512) void attend_ref_split(
     const uint16_t *__restrict__ q, uint32_t n_heads, const char *__restrict__ pool, uint64_t pool_stride,
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
     const int32_t *__restrict__ row_index, const int32_t *__restrict__ hit_index, uint64_t dst_rows,
@@ -60,15 +177,95 @@ __global__ __launch_bounds__(256) void attend_ref_split(
     att_smem *sm = (att_smem *)smem_raw;
     const uint32_t split = blockIdx.x, n_splits = gridDim.x, group = blockIdx.y, n_groups = gridDim.y;
     const uint32_t b = blockIdx.z;
-    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = irm_wave_id();
-    const uint32_t lm = lane & 15, lq = lane >> 4;          // MFMA coordinates of this lane
+    const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
+    const bool fetcher = wave >= 4;                         // uniform per wave
+    const uint32_t cw = wave & 3u;                          // index among the waves of its half
+    const uint32_t ct = threadIdx.x & 255u;                 // lane index within its half
     const uint32_t begin = kv_offsets[b], end = kv_offsets[b + 1];
     const uint32_t n_tok = end - begin;
     const uint32_t n_tiles = (n_tok + ATT_TILE - 1) / ATT_TILE;
     const uint32_t per_split = (n_tiles + n_splits - 1) / n_splits;
     const uint32_t tile0 = split * per_split;
     const uint32_t tile1 = tile0 + per_split < n_tiles ? tile0 + per_split : n_tiles;
+    const uint64_t part = ((uint64_t)b * n_groups + group) * n_splits + split;
+    if (tile0 >= tile1) {                                   // nothing for this split (uniform exit)
+        float *po = part_o + part * (ATT_HEADS * 512u);
+        for (uint32_t i = threadIdx.x; i < ATT_HEADS * 512u; i += blockDim.x) po[i] = 0.0f;
+        if (threadIdx.x < ATT_HEADS) part_ml[part * ATT_HEADS + threadIdx.x] = make_float2(-INFINITY, 0.0f);
+        return;
+    }
+    // tiles are taken two at a time; an odd count is padded by a tile without tokens (its
+    // references are -1: it reads row 0, lands zeros and counts for nothing)
+    const uint32_t n_pairs = (tile1 - tile0 + 1u) >> 1;
 
+    if (fetcher) {
+        const att_args a = {pool, pool_stride, trig, pair_mode};
+        u32x4 ra[ATT_KSTEPS], rb[ATT_KSTEPS];
+        f32x4 t4[4];
+        ATT_SYNC();                                         // prologue 1: references of tiles 0..2 published
+        int32_t hit = att_load_trig(t4, sm, 0, a, ct);
+        att_issue_rows(ra, sm, 0, a, cw, lane, ct);
+        att_issue_rows(rb, sm, 1, a, cw, lane, ct);
+        att_land_rows(ra, t4, hit, sm, 0, 0, a, cw, lane, ct);
+        ATT_SYNC();                                         // prologue 2: tile0 landed
+        for (uint32_t pr = 0; pr < n_pairs; ++pr) {
+            const uint32_t k = 2u * pr;                     // tile - tile0, even
+            // tile k: request k + 2 into ra (k landed from it), land k + 1 from rb into buffer 1
+            hit = att_load_trig(t4, sm, (k + 1u) & 3u, a, ct);
+            att_issue_rows(ra, sm, (k + 2u) & 3u, a, cw, lane, ct);
+            ATT_SYNC();
+            ATT_SYNC();
+            att_land_rows(rb, t4, hit, sm, (k + 1u) & 3u, 1, a, cw, lane, ct);
+            ATT_SYNC();
+            // tile k + 1: request k + 3 into rb, land k + 2 from ra into buffer 0
+            hit = att_load_trig(t4, sm, (k + 2u) & 3u, a, ct);
+            att_issue_rows(rb, sm, (k + 3u) & 3u, a, cw, lane, ct);
+            ATT_SYNC();
+            ATT_SYNC();
+            att_land_rows(ra, t4, hit, sm, (k + 2u) & 3u, 0, a, cw, lane, ct);
+            ATT_SYNC();
+        }
+        __syncthreads();
+        return;
+    }
+
+    // ---- compute half: waves 0..3 -------------------------------------------------------------
+    const uint32_t lm = lane & 15, lq = lane >> 4;          // MFMA coordinates of this lane
+    // References (slot -> pool row, rotation): lanes 0..15 of wave cw for tokens 16 cw .. + 15 of a
+    // tile.  The two dependent loads are spread over three tiles' time so that nobody waits for
+    // them: during tile i the slot ids of tile i + 5 are requested, the rows and rotations of
+    // tile i + 4 (whose slot ids came in during tile i - 1) are requested into one register
+    // pair, and those of tile i + 3, requested a tile ago into the other pair, are checked and
+    // published.  Slot = tile mod 4.
+    const uint32_t ref_tok = 16u * cw + lane;               // meaningful for lane < 16
+    auto refs_slot = [&](uint32_t tile) -> int32_t {
+        if (lane >= 16u || tile >= tile1) return -1;
+        const uint32_t t0 = begin + tile * ATT_TILE;
+        if (ref_tok >= end - t0) return -1;
+        return kv_slots[(uint64_t)t0 + ref_tok];
+    };
+    auto refs_rows = [&](uint32_t tile, int32_t sl, int32_t &row, int32_t &hit) {   // request only
+        row = -2;                                           // the token does not exist
+        hit = -1;
+        if (lane >= 16u || tile >= tile1 || ref_tok >= end - (begin + tile * ATT_TILE)) return;
+        row = -3;                                           // a token whose slot is out of range
+        if (sl >= 0 && (uint64_t)(uint32_t)sl < dst_rows) {
+            row = row_index[sl];
+            hit = hit_index[sl];
+        }
+    };
+    auto refs_publish = [&](uint32_t slot, int32_t row, int32_t hit) {
+        if (row == -2) {
+            row = -1;
+        } else if (row < 0 || (uint64_t)(uint32_t)row >= pool_rows || hit >= (int32_t)trig_hits) {
+            atomicOr(err, IRM_FLAG_ROW_RANGE);              // the token is left out of the attention
+            row = -1;
+        }
+        if (lane < 16u) {
+            sm->row[slot][ref_tok] = row;
+            sm->hit[slot][ref_tok] = hit < 0 ? -1 : hit;
+        }
+    };
     // Q as A operands: lane holds Q[head lm][32 kk + 8 lq .. + 8] for every k-step
     u16x8 qa[ATT_KSTEPS];
     {
@@ -85,116 +282,49 @@ __global__ __launch_bounds__(256) void attend_ref_split(
         m_run[i] = -INFINITY;
         l_part[i] = 0.0f;
     }
+    int32_t next_sl, ref_a_row, ref_a_hit, ref_b_row = -2, ref_b_hit = -1;
+#pragma unroll
+    for (uint32_t k = 0; k < 3; ++k) {
+        refs_rows(tile0 + k, refs_slot(tile0 + k), ref_a_row, ref_a_hit);
+        refs_publish(k, ref_a_row, ref_a_hit);
+    }
+    refs_rows(tile0 + 3, refs_slot(tile0 + 3), ref_a_row, ref_a_hit);
+    next_sl = refs_slot(tile0 + 4);
+    ATT_SYNC();                                             // prologue 1
+    ATT_SYNC();                                             // prologue 2
 
-    for (uint32_t tile = tile0; tile < tile1; ++tile) {
-        const uint32_t t0 = begin + tile * ATT_TILE;
-        const uint32_t n_valid = end - t0 < ATT_TILE ? end - t0 : ATT_TILE;
-        // (1) references of the tile's tokens
-        if (tid < ATT_TILE) {
-            int32_t row = -1, hit = -1;
-            if (tid < n_valid) {
-                const int32_t sl = kv_slots[(uint64_t)t0 + tid];
-                if (sl >= 0 && (uint64_t)(uint32_t)sl < dst_rows) {
-                    row = row_index[sl];
-                    hit = hit_index[sl];
-                }
-                if (row < 0 || (uint64_t)(uint32_t)row >= pool_rows || hit >= (int32_t)trig_hits) {
-                    atomicOr(err, IRM_FLAG_ROW_RANGE);      // the token is left out of the attention
-                    row = -1;
-                }
-                if (hit < 0) hit = -1;
-            }
-            sm->row[tid] = row;
-            sm->hit[tid] = hit;
-        }
-        __syncthreads();
-        // (2) gather 64 rows x 72 16-byte vectors; absent tokens become zero rows
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            u32x4 v[9];
-#pragma unroll
-            for (int j = 0; j < 9; ++j) {
-                const uint32_t idx = tid + 256u * (uint32_t)(half * 9 + j);   // < 4608
-                const uint32_t r = idx / 72u, c = idx - r * 72u;
-                const int32_t row = sm->row[r];
-                v[j] = u32x4{0, 0, 0, 0};
-                if (row >= 0)
-                    v[j] = __builtin_nontemporal_load((const u32x4 *)(pool + (uint64_t)(uint32_t)row * pool_stride) + c);
-            }
-#pragma unroll
-            for (int j = 0; j < 9; ++j) {
-                const uint32_t idx = tid + 256u * (uint32_t)(half * 9 + j);
-                const uint32_t r = idx / 72u, c = idx - r * 72u;
-                *(u32x4 *)(sm->k + r * ATT_KROW + c * 8u) = v[j];
-            }
-        }
-        __syncthreads();
-        // (3) rotate k_r in place: lane (r, j) turns pairs 8j .. 8j+7 of row r
-        {
-            const uint32_t r = tid >> 2, j = tid & 3;
-            const int32_t hit = sm->hit[r];
-            if (hit >= 0) {
-                const f32x4 *tp = (const f32x4 *)(trig + (uint64_t)(uint32_t)hit * IRM_KR_PAIRS + 8u * j);
-                const f32x4 t4[4] = {tp[0], tp[1], tp[2], tp[3]};              // (c, s, c, s) of two pairs each
-                uint16_t *kr = sm->k + r * ATT_KROW + IRM_CKV_BYTES / 2;
-                if (pair_mode == IRM_PAIR_HALF_SPLIT) {
-                    u32x4 a = *(u32x4 *)(kr + 8 * j), bb = *(u32x4 *)(kr + 32 + 8 * j);
-                    uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {bb.x, bb.y, bb.z, bb.w};
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        const float a0 = att_bf16_lo(aw[w]), a1 = att_bf16_hi(aw[w]);
-                        const float b0 = att_bf16_lo(bw[w]), b1 = att_bf16_hi(bw[w]);
-                        const float c0 = t4[w].x, s0 = t4[w].y, c1 = t4[w].z, s1 = t4[w].w;
-                        aw[w] = att_to_bf16(a0 * c0 - b0 * s0) | (att_to_bf16(a1 * c1 - b1 * s1) << 16);
-                        bw[w] = att_to_bf16(b0 * c0 + a0 * s0) | (att_to_bf16(b1 * c1 + a1 * s1) << 16);
-                    }
-                    *(u32x4 *)(kr + 8 * j) = u32x4{aw[0], aw[1], aw[2], aw[3]};
-                    *(u32x4 *)(kr + 32 + 8 * j) = u32x4{bw[0], bw[1], bw[2], bw[3]};
-                } else {                                    // pair p = elements 2p, 2p+1: one word each
-                    u32x4 x = *(u32x4 *)(kr + 16 * j), y = *(u32x4 *)(kr + 16 * j + 8);
-                    uint32_t w8[8] = {x.x, x.y, x.z, x.w, y.x, y.y, y.z, y.w};
-#pragma unroll
-                    for (int w = 0; w < 8; ++w) {
-                        const float a0 = att_bf16_lo(w8[w]), b0 = att_bf16_hi(w8[w]);
-                        const float c0 = (w & 1) ? t4[w >> 1].z : t4[w >> 1].x;
-                        const float s0 = (w & 1) ? t4[w >> 1].w : t4[w >> 1].y;
-                        w8[w] = att_to_bf16(a0 * c0 - b0 * s0) | (att_to_bf16(b0 * c0 + a0 * s0) << 16);
-                    }
-                    *(u32x4 *)(kr + 16 * j) = u32x4{w8[0], w8[1], w8[2], w8[3]};
-                    *(u32x4 *)(kr + 16 * j + 8) = u32x4{w8[4], w8[5], w8[6], w8[7]};
-                }
-            }
-        }
-        __syncthreads();
-        // (4) S = Q K^T for this wave's 16 tokens: lane holds S[head 4 lq + i][token 16 wave + lm]
+    // one tile; req_*: register pair that takes the references of tile + 4, pub_*: the pair
+    // requested a tile ago (tile + 3), published at the end
+    auto tile_step = [&](uint32_t tile, int32_t &req_row, int32_t &req_hit, int32_t pub_row, int32_t pub_hit) {
+        const uint32_t k = tile - tile0, cur = k & 1u;
+        refs_rows(tile + 4, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
+        next_sl = refs_slot(tile + 5);
+        // S = Q K^T for this wave's 16 tokens: lane holds S[head 4 lq + i][token 16 cw + lm]
         f32x4 s = {0, 0, 0, 0};
-        {
-            const uint16_t *krow = sm->k + (16u * wave + lm) * ATT_KROW + 8u * lq;
+        const uint16_t *krow = sm->k[cur] + (16u * cw + lm) * ATT_KROW + 8u * lq;
 #pragma unroll
-            for (int kk = 0; kk < ATT_KSTEPS; ++kk) {
-                const u16x8 kb = *(const u16x8 *)(krow + 32 * kk);
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[kk]),
-                                                            __builtin_bit_cast(bf16x8, kb), s, 0, 0, 0);
-            }
+        for (int kk = 0; kk < ATT_KSTEPS; ++kk) {
+            const u16x8 kb = *(const u16x8 *)(krow + 32 * kk);
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[kk]),
+                                                        __builtin_bit_cast(bf16x8, kb), s, 0, 0, 0);
         }
-        // (5) scores in the log2 domain; tokens that do not exist score -inf
-        const bool live = sm->row[16u * wave + lm] >= 0;
-        float sc[4], tmax[4];
+        // scores in the log2 domain; tokens that do not exist score -inf
+        const bool live = sm->row[k & 3u][16u * cw + lm] >= 0;
+        float pv[4], tmax[4], alpha[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            sc[i] = live ? s[i] * scale_log2 : -INFINITY;
-            tmax[i] = sc[i];
+            pv[i] = live ? s[i] * scale_log2 : -INFINITY;
+            tmax[i] = pv[i];
         }
-        // (6) tile maximum per head: over the 16 lanes that share lq, then over the waves
+        // tile maximum per head: over the 16 lanes that share lq, then over the waves
 #pragma unroll
         for (int d = 1; d < 16; d <<= 1)
 #pragma unroll
             for (int i = 0; i < 4; ++i) tmax[i] = fmaxf(tmax[i], __shfl_xor(tmax[i], d));
         if (lm == 0)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) sm->red[wave * ATT_HEADS + 4 * lq + i] = tmax[i];
-        __syncthreads();
-        float alpha[4], pv[4];
+            for (int i = 0; i < 4; ++i) sm->red[cw * ATT_HEADS + 4 * lq + i] = tmax[i];
+        ATT_SYNC();                                         // B
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t h = 4 * lq + i;
@@ -203,36 +333,40 @@ __global__ __launch_bounds__(256) void attend_ref_split(
             const float m_new = fmaxf(m_run[i], tm);
             // all -inf so far (no live token yet): keep everything at zero
             alpha[i] = m_new == -INFINITY ? 1.0f : exp2f(m_run[i] - m_new);
-            pv[i] = m_new == -INFINITY ? 0.0f : exp2f(sc[i] - m_new);
+            pv[i] = m_new == -INFINITY ? 0.0f : exp2f(pv[i] - m_new);
             m_run[i] = m_new;
             l_part[i] = l_part[i] * alpha[i] + pv[i];
+            // P (bf16) to LDS as the A operand of the second product
+            sm->p[h * ATT_PROW + 16u * cw + lm] = (uint16_t)att_to_bf16(pv[i]);
         }
-        // (7) P (bf16) to LDS as the A operand of the second product; rescale O
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            sm->p[(4 * lq + i) * ATT_PROW + 16u * wave + lm] = (uint16_t)att_to_bf16(pv[i]);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[nt][i] *= alpha[i];
-        __syncthreads();
-        // (8) O += P V: wave owns latent dims [128 wave, 128 wave + 128)
+        ATT_SYNC();                                         // C
+        refs_publish((k + 3u) & 3u, pub_row, pub_hit);      // that slot held tile - 1: long done
+        // O += P V: wave owns latent dims [128 cw, 128 cw + 128)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const u16x8 pa = *(const u16x8 *)(sm->p + lm * ATT_PROW + 32 * ks + 8 * lq);
-            const uint16_t *vcol = sm->k + (32u * ks + 8u * lq) * ATT_KROW + 128u * wave + lm;
+            const uint16_t *vcol = sm->k[cur] + (32u * ks + 8u * lq) * ATT_KROW + 128u * cw + lm;
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt) {
-                u16x8 vb;
+                u16x8 vv;
 #pragma unroll
-                for (int i = 0; i < 8; ++i) vb[i] = vcol[i * ATT_KROW + 16 * nt];
+                for (int i = 0; i < 8; ++i) vv[i] = vcol[i * ATT_KROW + 16 * nt];
                 o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa),
-                                                                __builtin_bit_cast(bf16x8, vb), o[nt], 0, 0, 0);
+                                                                __builtin_bit_cast(bf16x8, vv), o[nt], 0, 0, 0);
             }
         }
-        __syncthreads();                                    // the tile buffers are reused
+        ATT_SYNC();                                         // D
+    };
+    for (uint32_t pr = 0; pr < n_pairs; ++pr) {
+        const uint32_t tile = tile0 + 2u * pr;
+        tile_step(tile, ref_b_row, ref_b_hit, ref_a_row, ref_a_hit);
+        tile_step(tile + 1, ref_a_row, ref_a_hit, ref_b_row, ref_b_hit);
     }
-    // sums over the 16 lanes that share lq, then over the waves (each wave saw its own tokens)
+    // sums over the 16 lanes that share lq, then over the compute waves (each saw its own tokens)
 #pragma unroll
     for (int d = 1; d < 16; d <<= 1)
 #pragma unroll
@@ -240,47 +374,67 @@ __global__ __launch_bounds__(256) void attend_ref_split(
     if (lm == 0)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            sm->red[wave * ATT_HEADS + 4 * lq + i] = l_part[i];
-            if (wave == 0) sm->mfin[4 * lq + i] = m_run[i];  // the same in every wave
+            sm->red[cw * ATT_HEADS + 4 * lq + i] = l_part[i];
+            if (cw == 0) sm->mfin[4 * lq + i] = m_run[i];   // the same in every compute wave
         }
     __syncthreads();
-    const uint64_t part = ((uint64_t)b * n_groups + group) * n_splits + split;
     float *po = part_o + part * (ATT_HEADS * 512u);
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) po[(4 * lq + i) * 512u + 128u * wave + 16u * nt + lm] = o[nt][i];
-    if (tid < ATT_HEADS) {
-        const float l = sm->red[tid] + sm->red[ATT_HEADS + tid] + sm->red[2 * ATT_HEADS + tid] +
-                        sm->red[3 * ATT_HEADS + tid];
-        part_ml[part * ATT_HEADS + tid] = make_float2(sm->mfin[tid], l);
+        for (int i = 0; i < 4; ++i) po[(4 * lq + i) * 512u + 128u * cw + 16u * nt + lm] = o[nt][i];
+    if (threadIdx.x < ATT_HEADS) {
+        const uint32_t h = threadIdx.x;
+        const float l = sm->red[h] + sm->red[ATT_HEADS + h] + sm->red[2 * ATT_HEADS + h] + sm->red[3 * ATT_HEADS + h];
+        part_ml[part * ATT_HEADS + h] = make_float2(sm->mfin[h], l);
     }
 }
 
-// grid (head groups, requests), 512 lanes: lane d owns latent dim d of all 16 heads
+// grid (16 heads, head groups, requests), 512 lanes: lane d owns latent dim d of one head.
+// The splits' (max, sum) pairs are combined once in LDS, then the partial outputs are summed
+// with independent loads.
 __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict__ part_o,
                                                         const float2 *__restrict__ part_ml, uint32_t n_splits,
                                                         uint32_t n_heads, float *__restrict__ out,
                                                         float *__restrict__ lse)
 {
-    const uint32_t group = blockIdx.x, n_groups = gridDim.x, b = blockIdx.y, d = threadIdx.x;
+    __shared__ float w_s[1024];                             // weight of each split, n_splits <= 1024
+    __shared__ float red_s[16];
+    const uint32_t h = blockIdx.x, group = blockIdx.y, n_groups = gridDim.y, b = blockIdx.z, d = threadIdx.x;
     const uint64_t part0 = ((uint64_t)b * n_groups + group) * n_splits;
-    for (uint32_t h = 0; h < ATT_HEADS; ++h) {
-        float m = -INFINITY;
-        for (uint32_t s = 0; s < n_splits; ++s) m = fmaxf(m, part_ml[(part0 + s) * ATT_HEADS + h].x);
-        float l = 0.0f, acc = 0.0f;
-        if (m != -INFINITY) {
-            for (uint32_t s = 0; s < n_splits; ++s) {
-                const float2 ml = part_ml[(part0 + s) * ATT_HEADS + h];
-                const float w = ml.x == -INFINITY ? 0.0f : exp2f(ml.x - m);
-                l += ml.y * w;
-                acc += part_o[((part0 + s) * ATT_HEADS + h) * 512u + d] * w;
-            }
-        }
-        const uint64_t oh = (uint64_t)b * n_heads + group * ATT_HEADS + h;
-        out[oh * 512u + d] = l > 0.0f ? acc / l : 0.0f;
-        if (d == 0) lse[oh] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+    // overall maximum
+    float m = -INFINITY;
+    for (uint32_t s = d; s < n_splits; s += blockDim.x) m = fmaxf(m, part_ml[(part0 + s) * ATT_HEADS + h].x);
+#pragma unroll
+    for (int k = 1; k < 64; k <<= 1) m = fmaxf(m, __shfl_xor(m, k));
+    if ((d & 63u) == 0) red_s[d >> 6] = m;
+    __syncthreads();
+    m = red_s[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) m = fmaxf(m, red_s[k]);
+    // weights and the overall sum
+    float l = 0.0f;
+    for (uint32_t s = d; s < n_splits; s += blockDim.x) {
+        const float2 ml = part_ml[(part0 + s) * ATT_HEADS + h];
+        const float w = (ml.x == -INFINITY || m == -INFINITY) ? 0.0f : exp2f(ml.x - m);
+        w_s[s] = w;
+        l += ml.y * w;
     }
+#pragma unroll
+    for (int k = 1; k < 64; k <<= 1) l += __shfl_xor(l, k);
+    __syncthreads();                                        // everybody has read the maxima
+    if ((d & 63u) == 0) red_s[8 + (d >> 6)] = l;
+    __syncthreads();
+    l = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) l += red_s[8 + k];
+    float acc = 0.0f;
+    const float *po = part_o + (part0 * ATT_HEADS + h) * 512u + d;
+#pragma unroll 4
+    for (uint32_t s = 0; s < n_splits; ++s) acc += po[(uint64_t)s * ATT_HEADS * 512u] * w_s[s];
+    const uint64_t oh = (uint64_t)b * n_heads + group * ATT_HEADS + h;
+    out[oh * 512u + d] = l > 0.0f ? acc / l : 0.0f;
+    if (d == 0) lse[oh] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
 extern "C" uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits)
@@ -304,7 +458,7 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
         return IRM_ERR_INVALID_ARG;
     if (pool_row_stride_bytes < IRM_ROW_BYTES || (pool_row_stride_bytes & 15) || ((uintptr_t)d_pool_layer & 15) ||
         ((uintptr_t)d_q & 15) || ((uintptr_t)d_trig & 15) || pool_rows < 1 || pool_rows > 0x7FFFFFFFull ||
-        dst_rows < 1 || !(scale > 0.0f))
+        dst_rows < 1 || trig_hits < 1 || !(scale > 0.0f))
         return IRM_ERR_INVALID_ARG;
     if (workspace_bytes < irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) || ((uintptr_t)d_workspace & 15))
         return IRM_ERR_CAPACITY;
@@ -318,11 +472,18 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
                                         (int)sizeof(att_smem)));
         lds_set = true;
     }
-    hipLaunchKernelGGL(attend_ref_split, dim3(n_splits, n_groups, n_req), dim3(256), sizeof(att_smem), s,
+    const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
+                        (ctx->prof_calls++ % ctx->prof_every) == 0;
+    if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
+    hipLaunchKernelGGL(attend_ref_split, dim3(n_splits, n_groups, n_req), dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
                        d_kv_slots, d_kv_offsets, d_row_index, d_hit_index, dst_rows, (const float2 *)d_trig,
                        trig_hits, scale * ATT_LOG2E, ctx->cfg.pair_mode, part_o, part_ml, ctx->d_err);
-    hipLaunchKernelGGL(attend_ref_merge, dim3(n_groups, n_req), dim3(512), 0, s, part_o, part_ml, n_splits, n_heads,
+    hipLaunchKernelGGL(attend_ref_merge, dim3(ATT_HEADS, n_groups, n_req), dim3(512), 0, s, part_o, part_ml, n_splits, n_heads,
                        d_out, d_lse);
+    if (sample) {
+        IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
+        ++ctx->prof_n;
+    }
     return irm_launch_status();
 }
