@@ -48,6 +48,9 @@ def main() -> int:
                          "no-materialise variant, only row references and the per-hit rotation table are written "
                          "(8 B per token, once, not per layer)")
     ap.add_argument("--heads", type=int, default=16, help="attend stage: query heads (multiple of 16)")
+    ap.add_argument("--linear-rows", action="store_true",
+                    help="attend stage: every slot refers to the pool row of the same number (no rotation), i.e. "
+                         "purely sequential reads: the yardstick for what the gather pattern costs")
     ap.add_argument("--splits", type=int, default=8, help="attend stage: workgroups per request and 16 heads")
     ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1", "attend"],
                     help="hit = the cache-hit path (the headline); admit = the miss path on a cold registry: "
@@ -329,6 +332,15 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
             step(v)
             stream.synchronize()
             assert sessions[v].error_flags() == 0
+        if args.linear_rows:
+            def step(v):                                         # attention only, rows in slot order
+                s, d = sessions[v], dev_in[v]
+                for l in range(L):
+                    B.irm_attend_ref(s.ctx, q, pool[l], ROW_BYTES, d["dst_slots"], d["req_offsets"], d["row"],
+                                     d["hit"], d["trig"], scale, args.splits, ws, out, lse, stream)
+            for d in dev_in:
+                d["row"].copy_(torch.arange(d["row"].numel(), dtype=torch.int32, device=dev))
+                d["hit"].fill_(-1)
         for k in range(args.warmup):
             step(k % len(works))
         for s in sessions:

@@ -30,6 +30,16 @@
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// LDS read with transpose (ds_read_b64_tr_b16).  Within a block of 16 lanes, lane s points at four
+// consecutive 16-bit elements; lane i receives, as element j, element (i & 3) of the four that lane
+// 4 j + (i >> 2) pointed at.  With lane s pointing at M[r0 + (s >> 2)][c0 + 4 (s & 3) ..] of a
+// row-major matrix, lane i ends up with the column piece M[r0 .. r0 + 3][c0 + i].
+__device__ __forceinline__ s16x4 att_lds_read_tr(const uint16_t *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)p);
+}
 
 __device__ __forceinline__ float att_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float att_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -48,6 +58,7 @@ struct att_smem {
     float mfin[ATT_HEADS];              // running maximum per head at the end
     int32_t row[4][ATT_TILE];           // pool row of each tile token, -1 = no token; slot = tile mod 4
     int32_t hit[4][ATT_TILE];           // rotation of each tile token, -1 = none
+    uint32_t bar;                       // arrivals at the compute waves' own barrier
 };
 
 // Barrier that orders LDS traffic only: global loads issued before it stay in flight.
@@ -57,6 +68,26 @@ struct att_smem {
         __builtin_amdgcn_s_barrier();                                       \
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
     } while (0)
+
+// Barrier among the four compute waves only, through an LDS counter, so that the fetch waves are
+// not held at the two points inside a tile where only the compute waves must agree.  The four
+// waves are resident together and run the same tile loop, so every wait ends; the wait is
+// bounded all the same (a wave that gives up raises IRM_FLAG_ROW_RANGE and carries on).
+__device__ __forceinline__ void att_compute_barrier(att_smem *sm, uint32_t &arrivals, uint32_t lane, uint32_t *err)
+{
+    arrivals += 4u;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    if (lane == 0) __hip_atomic_fetch_add(&sm->bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    uint32_t spins = 0;
+    while ((int32_t)(__hip_atomic_load(&sm->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - arrivals) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > (1u << 22)) {
+            if (lane == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+            break;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // ---- fetch half: waves 4..7 -------------------------------------------------------------------
 // A fetch lane holds, of a tile's 64 rows: c_KV vector `lane` of rows cw + 4j (a wave reads whole
@@ -163,9 +194,9 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_KSTEPS], const f32
 
 // 8 waves: waves 0..3 compute, waves 4..7 fetch; each half runs its own loop (so that each gets
 // the whole register file for what it alone needs) and both meet at the same barriers: two in
-// the prologue, three per tile (B: tile maxima published, C: P complete, D: buffers change
-// roles), one at the end.  While the compute waves work on tile i in one LDS buffer, the fetch
-// waves request tile i + 2 from HBM and land tile i + 1, requested a tile ago, in the other.
+// the prologue, one per tile (the LDS buffers change roles), one at the end.  While the compute
+// waves work on tile i in one LDS buffer, the fetch waves request tile i + 2 from HBM and land
+// tile i + 1, requested a tile ago, in the other buffer, whenever its rows arrive.
 __global__ __launch_bounds__(512) void attend_ref_split(
     const uint16_t *__restrict__ q, uint32_t n_heads, const char *__restrict__ pool, uint64_t pool_stride,
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
@@ -197,6 +228,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     // tiles are taken two at a time; an odd count is padded by a tile without tokens (its
     // references are -1: it reads row 0, lands zeros and counts for nothing)
     const uint32_t n_pairs = (tile1 - tile0 + 1u) >> 1;
+    if (threadIdx.x == 0) sm->bar = 0;
 
     if (fetcher) {
         const att_args a = {pool, pool_stride, trig, pair_mode};
@@ -213,15 +245,11 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             // tile k: request k + 2 into ra (k landed from it), land k + 1 from rb into buffer 1
             hit = att_load_trig(t4, sm, (k + 1u) & 3u, a, ct);
             att_issue_rows(ra, sm, (k + 2u) & 3u, a, cw, lane, ct);
-            ATT_SYNC();
-            ATT_SYNC();
             att_land_rows(rb, t4, hit, sm, (k + 1u) & 3u, 1, a, cw, lane, ct);
             ATT_SYNC();
             // tile k + 1: request k + 3 into rb, land k + 2 from ra into buffer 0
             hit = att_load_trig(t4, sm, (k + 2u) & 3u, a, ct);
             att_issue_rows(rb, sm, (k + 3u) & 3u, a, cw, lane, ct);
-            ATT_SYNC();
-            ATT_SYNC();
             att_land_rows(ra, t4, hit, sm, (k + 2u) & 3u, 0, a, cw, lane, ct);
             ATT_SYNC();
         }
@@ -295,19 +323,27 @@ __global__ __launch_bounds__(512) void attend_ref_split(
 
     // one tile; req_*: register pair that takes the references of tile + 4, pub_*: the pair
     // requested a tile ago (tile + 3), published at the end
+    uint32_t arrivals = 0;
     auto tile_step = [&](uint32_t tile, int32_t &req_row, int32_t &req_hit, int32_t pub_row, int32_t pub_hit) {
         const uint32_t k = tile - tile0, cur = k & 1u;
         refs_rows(tile + 4, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
         next_sl = refs_slot(tile + 5);
         // S = Q K^T for this wave's 16 tokens: lane holds S[head 4 lq + i][token 16 cw + lm]
-        f32x4 s = {0, 0, 0, 0};
+        // (all 18 operands requested first, two accumulators: neither LDS nor MFMA latency adds up)
         const uint16_t *krow = sm->k[cur] + (16u * cw + lm) * ATT_KROW + 8u * lq;
+        u16x8 kb[ATT_KSTEPS];
 #pragma unroll
-        for (int kk = 0; kk < ATT_KSTEPS; ++kk) {
-            const u16x8 kb = *(const u16x8 *)(krow + 32 * kk);
+        for (int kk = 0; kk < ATT_KSTEPS; ++kk) kb[kk] = *(const u16x8 *)(krow + 32 * kk);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x4 s = {0, 0, 0, 0}, s2 = {0, 0, 0, 0};
+#pragma unroll
+        for (int kk = 0; kk < ATT_KSTEPS; kk += 2) {
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[kk]),
-                                                        __builtin_bit_cast(bf16x8, kb), s, 0, 0, 0);
+                                                        __builtin_bit_cast(bf16x8, kb[kk]), s, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[kk + 1]),
+                                                         __builtin_bit_cast(bf16x8, kb[kk + 1]), s2, 0, 0, 0);
         }
+        s += s2;
         // scores in the log2 domain; tokens that do not exist score -inf
         const bool live = sm->row[k & 3u][16u * cw + lm] >= 0;
         float pv[4], tmax[4], alpha[4];
@@ -324,7 +360,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         if (lm == 0)
 #pragma unroll
             for (int i = 0; i < 4; ++i) sm->red[cw * ATT_HEADS + 4 * lq + i] = tmax[i];
-        ATT_SYNC();                                         // B
+        att_compute_barrier(sm, arrivals, lane, err);       // B: tile maxima published
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t h = 4 * lq + i;
@@ -343,18 +379,21 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[nt][i] *= alpha[i];
-        ATT_SYNC();                                         // C
+        att_compute_barrier(sm, arrivals, lane, err);       // C: P complete, maxima consumed
         refs_publish((k + 3u) & 3u, pub_row, pub_hit);      // that slot held tile - 1: long done
         // O += P V: wave owns latent dims [128 cw, 128 cw + 128)
+        // The B operand wants, per lane, 8 consecutive tokens of one latent dim: a column piece
+        // of the row-major tile, fetched by two transposing LDS reads of four tokens each.
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             const u16x8 pa = *(const u16x8 *)(sm->p + lm * ATT_PROW + 32 * ks + 8 * lq);
-            const uint16_t *vcol = sm->k[cur] + (32u * ks + 8u * lq) * ATT_KROW + 128u * cw + lm;
+            const uint16_t *vsrc = sm->k[cur] + (32u * ks + 8u * lq + (lm >> 2)) * ATT_KROW + 128u * cw + 4u * (lm & 3u);
 #pragma unroll
             for (int nt = 0; nt < 8; ++nt) {
-                u16x8 vv;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) vv[i] = vcol[i * ATT_KROW + 16 * nt];
+                const s16x4 v0 = att_lds_read_tr(vsrc + 16 * nt);
+                const s16x4 v1 = att_lds_read_tr(vsrc + 4 * ATT_KROW + 16 * nt);
+                const u16x8 vv = {(uint16_t)v0[0], (uint16_t)v0[1], (uint16_t)v0[2], (uint16_t)v0[3],
+                                  (uint16_t)v1[0], (uint16_t)v1[1], (uint16_t)v1[2], (uint16_t)v1[3]};
                 o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa),
                                                                 __builtin_bit_cast(bf16x8, vv), o[nt], 0, 0, 0);
             }
