@@ -261,3 +261,45 @@ def test_full_size_s1_fallback(name):
             assert torch.all(rig.dst[l].index_select(0, untouched).view(torch.int16) == wl.SENTINEL_BF16)
     finally:
         rig.close()
+
+
+def test_full_size_attend_ref_c2():
+    """The rotate-on-load consumer at the c2 size, in the launch shape bench.py times (16 heads,
+    4 splits): 64 requests x 16,384 context tokens, one layer, every output against the fp64 oracle."""
+    from tests.gpu_util import ROW, hits_to_dev
+    from paper_2605_05696_amd import binding as B
+    w = wl.make_workload("c2", orc.cdc_chunk, size="full")
+    rig = Rig(w, with_table=False)
+    try:
+        hits = rig.o["hits"]
+        pool = rig.src[0]
+        d_hits, d_n = hits_to_dev(hits, rig.buf["cap"])
+        row = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        hit = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.zeros((rig.buf["cap"], 32, 2), dtype=torch.float32, device=DEV)
+        B.irm_reattach_ref(rig.s.ctx, w.src_rows, row, hit, trig, rig.d_dst_slots, d_hits, d_n)
+        row_h = row.cpu().numpy()
+        fresh = np.nonzero(row_h < 0)[0]                                  # prefilled tokens: plain rows anywhere
+        row_h[fresh] = np.random.default_rng(5).integers(0, w.src_rows, len(fresh))
+        row.copy_(torch.from_numpy(row_h))
+        hit_h = hit.cpu().numpy()
+        n_req, H, splits, scale = w.n_req, 16, 4, 1.0 / np.sqrt(192.0)
+        q = torch.randn((n_req, H, 576), device=DEV, generator=torch.Generator(DEV).manual_seed(3)).to(torch.bfloat16)
+        out = torch.zeros((n_req, H, 512), dtype=torch.float32, device=DEV)
+        lse = torch.zeros((n_req, H), dtype=torch.float32, device=DEV)
+        ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, H, splits), dtype=torch.uint8, device=DEV)
+        B.irm_attend_ref(rig.s.ctx, q, pool, ROW * 2, rig.d_dst_slots, rig.d_req_offsets, row, hit, trig, scale, splits,
+                         ws, out, lse)
+        torch.cuda.synchronize()
+        assert rig.s.error_flags() == 0
+        want_row = np.full(w.dst_rows, -1, np.int32)
+        want_hit = np.full(w.dst_rows, -1, np.int32)
+        trig64 = orc.reattach_ref(w.src_rows, want_row, want_hit, w.dst_slots, hits, w.inv_freq)
+        assert np.array_equal(want_hit, hit_h)
+        want, want_lse = orc.attend_ref(bits(q), bits(pool), w.dst_slots, w.req_offsets, row_h, hit_h, trig64, scale)
+        err = np.abs(out.cpu().numpy() - want)
+        # 16,384 tokens per softmax: outputs are averages of thousands of rows, errors shrink with them
+        assert err.max() < 3e-2 and err.mean() < 1e-3, (err.max(), err.mean())
+        assert np.abs(lse.cpu().numpy() - want_lse).max() < 2e-2
+    finally:
+        rig.close()
