@@ -7,7 +7,7 @@
 //   score[b][h][t] = scale * q[b][h] . [ c_KV(row_t) | R_t k_r_base(row_t) ]
 //   out[b][h]      = sum_t softmax_t(score) c_KV(row_t)
 //
-//   attend_ref_split   grid (splits, head groups of 16, requests), 8 waves.  A workgroup walks
+//   attend_ref_split   grid (head groups of 16, splits, requests), 8 waves.  A workgroup walks
 //       its share of the request's tokens in tiles of 64.  Four waves fetch: the tile's 64
 //       rows (1152 B each) come from HBM into registers with 16-byte loads, k_r is rotated
 //       there (fp32, one rounding to bf16: the same values the materialising kernel writes)
@@ -206,7 +206,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     att_smem *sm = (att_smem *)smem_raw;
-    const uint32_t split = blockIdx.x, n_splits = gridDim.x, group = blockIdx.y, n_groups = gridDim.y;
+    // head groups vary fastest: the workgroups that read the same rows are dispatched together
+    const uint32_t group = blockIdx.x, n_groups = gridDim.x, split = blockIdx.y, n_splits = gridDim.y;
     const uint32_t b = blockIdx.z;
     const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
     const bool fetcher = wave >= 4;                         // uniform per wave
@@ -510,7 +511,7 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(attend_ref_split, dim3(n_splits, n_groups, n_req), dim3(512), sizeof(att_smem), s,
+    hipLaunchKernelGGL(attend_ref_split, dim3(n_groups, n_splits, n_req), dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
                        d_kv_slots, d_kv_offsets, d_row_index, d_hit_index, dst_rows, (const float2 *)d_trig,
                        trig_hits, scale * ATT_LOG2E, ctx->cfg.pair_mode, part_o, part_ml, ctx->d_err);
