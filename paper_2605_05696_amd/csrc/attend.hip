@@ -16,8 +16,9 @@
 //         online softmax over the tile (running max per head shared through LDS)
 //         O += P V      wave w: 16 heads x its 128 of the 512 latent dims, 16 MFMA
 //       Q lives in registers as A operands; a row of the tile serves as B operand of S as it
-//       lies (k = dims, contiguous), and as B operand of O through 2-byte LDS reads
-//       (k = tokens, strided).  Every KV byte is read from HBM once per head group.
+//       lies (k = dims, contiguous), and as B operand of O through transposing LDS reads
+//       (k = tokens: column pieces of the row-major tile).  Every KV byte is read from HBM
+//       once per head group.
 //   attend_ref_merge   combines the splits' (max, sum, O) into out and lse.
 #include "irm_internal.hpp"
 
