@@ -309,13 +309,18 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         l_part[i] = 0.0f;
     }
     int32_t next_sl, ref_a_row, ref_a_hit, ref_b_row = -2, ref_b_hit = -1;
+    {
+        // the first four tiles' references: all slot ids first, then all rows, two round trips in all
+        int32_t sl[4], rw[3], ht[3];
 #pragma unroll
-    for (uint32_t k = 0; k < 3; ++k) {
-        refs_rows(tile0 + k, refs_slot(tile0 + k), ref_a_row, ref_a_hit);
-        refs_publish(k, ref_a_row, ref_a_hit);
+        for (uint32_t k = 0; k < 4; ++k) sl[k] = refs_slot(tile0 + k);
+        next_sl = refs_slot(tile0 + 4);
+#pragma unroll
+        for (uint32_t k = 0; k < 3; ++k) refs_rows(tile0 + k, sl[k], rw[k], ht[k]);
+        refs_rows(tile0 + 3, sl[3], ref_a_row, ref_a_hit);
+#pragma unroll
+        for (uint32_t k = 0; k < 3; ++k) refs_publish(k, rw[k], ht[k]);
     }
-    refs_rows(tile0 + 3, refs_slot(tile0 + 3), ref_a_row, ref_a_hit);
-    next_sl = refs_slot(tile0 + 4);
     ATT_SYNC();                                             // prologue 1
     ATT_SYNC();                                             // prologue 2
 
@@ -465,10 +470,20 @@ __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict_
     l = 0.0f;
 #pragma unroll
     for (int k = 0; k < 8; ++k) l += red_s[8 + k];
-    float acc = 0.0f;
-    const float *po = part_o + (part0 * ATT_HEADS + h) * 512u + d;
-#pragma unroll 4
-    for (uint32_t s = 0; s < n_splits; ++s) acc += po[(uint64_t)s * ATT_HEADS * 512u] * w_s[s];
+    // partial outputs: lane (dq, sj) adds dims 4 dq .. 4 dq + 3 of the splits sj, sj + 4, ...,
+    // eight independent 16-byte loads at a time; the four partial sums meet in LDS
+    __shared__ f32x4 acc_s[4][128];
+    {
+        const uint32_t dq = d & 127u, sj = d >> 7;
+        f32x4 a4 = {0, 0, 0, 0};
+        const f32x4 *po = (const f32x4 *)(part_o + (part0 * ATT_HEADS + h) * 512u) + dq;
+#pragma unroll 8
+        for (uint32_t s = sj; s < n_splits; s += 4u) a4 += po[(uint64_t)s * (ATT_HEADS * 512u / 4u)] * w_s[s];
+        acc_s[sj][dq] = a4;
+    }
+    __syncthreads();
+    const float *flat = (const float *)acc_s;
+    const float acc = flat[d] + flat[512 + d] + flat[1024 + d] + flat[1536 + d];
     const uint64_t oh = (uint64_t)b * n_heads + group * ATT_HEADS + h;
     out[oh * 512u + d] = l > 0.0f ? acc / l : 0.0f;
     if (d == 0) lse[oh] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
