@@ -81,7 +81,7 @@ def main() -> int:
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path is built and measured on ONE GPU; --gpus above 1 is not supported "
-              "(it shards by layer or by request with no exchange step, see DESIGN.md)", file=sys.stderr)
+              "(it would shard by layer or by request, with no exchange step)", file=sys.stderr)
         return 2
 
     import torch

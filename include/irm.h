@@ -12,6 +12,16 @@
  *                    c_KV part of each cached row verbatim and write the
  *                    RoPE part k_r rotated by delta into the request's slots
  *
+ * Around it (each declared below with the passage it follows):
+ *
+ *   irm_reattach_kr   split pool: only k_r is materialised, c_KV is referenced
+ *   irm_reattach_ref  nothing is materialised: row references and the per-hit
+ *                     rotation table for a load path that rotates on the fly
+ *   irm_attend_ref    such a load path: MLA decode attention over the references
+ *   irm_admit, irm_table_insert[_counted]   miss path: prefilled chunks into the
+ *                     shared pool and the registry, insert-if-absent
+ *   irm_s1_windows    S1 fallback: fixed windows inside the chunks that missed
+ *
  * Conventions
  *   - Plain C, no C++ or framework types.  Every call returns an irm_status.
  *   - Pointers named d_* are DEVICE pointers owned by the caller; all others
@@ -34,8 +44,8 @@
  *     be ordered on one stream (or otherwise not overlap).
  *
  * KV row layout: 576 bf16 = [ c_KV: 512 | k_r: 64 ] = 1152 bytes
- * (paper Sec. 2 "MLA", App. C).  k_r pairs are half-split: element i pairs
- * with element i+32, i < 32.
+ * (paper Sec. 2 "MLA", App. C).  Rotary pair i of k_r is elements (i, i + 32)
+ * (half-split, the default) or (2i, 2i + 1) (interleaved): irm_config.pair_mode.
  */
 #ifndef IRM_H
 #define IRM_H
@@ -289,7 +299,8 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  *   d_workspace    irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) bytes, 16-byte aligned
  *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]
  * A request without context gives out = 0, lse = -inf.  A slot, row or hit index out of
- * range leaves that token out and raises IRM_FLAG_ROW_RANGE. */
+ * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing; the first
+ * call in a process sets the kernel's LDS limit (one runtime call, no launch). */
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
 irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
                           const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,
