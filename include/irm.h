@@ -299,8 +299,8 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  *   d_workspace    irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) bytes, 16-byte aligned
  *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]
  * A request without context gives out = 0, lse = -inf.  A slot, row or hit index out of
- * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing; the first
- * call in a process sets the kernel's LDS limit (one runtime call, no launch). */
+ * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing, does not
+ * synchronise. */
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
 irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
                           const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,

@@ -489,6 +489,16 @@ __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict_
     if (d == 0) lse[oh] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
+// called by irm_ctx_create with the context's device current: the split kernel needs more LDS
+// than a launch gets by default
+irm_status irm_attend_init(int device)
+{
+    (void)device;
+    IRM_HIP_TRY(hipFuncSetAttribute((const void *)attend_ref_split, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)sizeof(att_smem)));
+    return IRM_OK;
+}
+
 extern "C" uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits)
 {
     return (uint64_t)n_req * n_heads * n_splits * (512u + 2u) * sizeof(float);
@@ -518,12 +528,6 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const uint32_t n_groups = n_heads / ATT_HEADS;
     float *part_o = (float *)d_workspace;
     float2 *part_ml = (float2 *)(part_o + (uint64_t)n_req * n_groups * n_splits * ATT_HEADS * 512u);
-    static bool lds_set = false;
-    if (!lds_set) {
-        IRM_HIP_TRY(hipFuncSetAttribute((const void *)attend_ref_split, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        (int)sizeof(att_smem)));
-        lds_set = true;
-    }
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));

@@ -81,7 +81,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     if (hipMemset(c->slab, 0, off) != hipSuccess ||
         hipMemcpy(c->d_gear, cfg->gear, 256 * 4, hipMemcpyHostToDevice) != hipSuccess ||
         hipMemcpy(c->d_inv_freq, cfg->inv_freq, IRM_KR_PAIRS * 4, hipMemcpyHostToDevice) != hipSuccess ||
-        irm_chunk_hash_init(c->device) != IRM_OK ||
+        irm_chunk_hash_init(c->device) != IRM_OK || irm_attend_init(c->device) != IRM_OK ||
         hipDeviceSynchronize() != hipSuccess) {
         (void)hipGetLastError();
         (void)hipFree(c->slab);

@@ -68,6 +68,8 @@ struct irm_table {
 
 // uploads the fingerprint kernel's constant table to the current device (idempotent)
 irm_status irm_chunk_hash_init(int device);
+// raises the LDS limit of the attention kernel on the current device
+irm_status irm_attend_init(int device);
 
 #define IRM_HIP_TRY(expr)                      \
     do {                                       \
