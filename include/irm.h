@@ -137,7 +137,7 @@ irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
 /* Tuning knobs for measurements (launch shapes only; results never change).
  * knob 0: grid.x of the re-attach row kernel = tile slots per layer (0 = one per
  *         possible tile)
- * knob 1: c_KV rows per wave and tile (1, 2, 4 or 16)
+ * knob 1: c_KV rows per wave and tile (1, 2, 4, 8 or 16)
  * knob 2: bit 0 = non-temporal loads, bit 1 = non-temporal stores
  * knob 3: 1 = each XCD serves a contiguous range of a layer's tiles, 0 = round-robin
  * knob 4: waves per workgroup (1, 2, 4, 8 or 16); a tile is waves x rows-per-wave rows,

@@ -125,7 +125,7 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
         return IRM_OK;
     }
     if (knob == 1) {
-        if (value != 1 && value != 2 && value != 4 && value != 16) return IRM_ERR_INVALID_ARG;
+        if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return IRM_ERR_INVALID_ARG;
         if (value * ctx->block_waves < IRM_TILE_ROWS_MIN) return IRM_ERR_INVALID_ARG;
         ctx->rows_per_wave = value;
         return IRM_OK;

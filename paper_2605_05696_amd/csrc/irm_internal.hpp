@@ -30,7 +30,7 @@ struct irm_ctx {
     uint32_t chunk_cap;     // max_tokens / min_chunk + max_requests
     uint32_t tile_cap;      // max_tokens / IRM_TILE_ROWS + chunk_cap
     uint32_t reattach_grid; // tuning knob 0: grid.x of the row kernel (tile slots per layer), 0 = default
-    uint32_t rows_per_wave; // knob 1: 4, 8 or 16 c_KV rows per wave and tile
+    uint32_t rows_per_wave; // knob 1: 1, 2, 4, 8 or 16 c_KV rows per wave and tile
     uint32_t block_waves;   // knob 4: 4, 8 or 16 waves per workgroup (tile = waves * rows_per_wave rows)
     uint32_t mem_mode;      // knob 2: bit 0 non-temporal loads, bit 1 non-temporal stores
     uint32_t cdc_serial;    // knob 5: 1 = always use the serial cut selection
