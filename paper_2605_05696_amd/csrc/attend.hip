@@ -60,6 +60,8 @@ struct att_smem {
     int32_t row[4][ATT_TILE];           // pool row of each tile token, -1 = no token; slot = tile mod 4
     int32_t hit[4][ATT_TILE];           // rotation of each tile token, -1 = none
     uint32_t bar;                       // arrivals at the compute waves' own barrier
+    uint32_t landed;                    // + 1 per fetch wave and tile landed
+    uint32_t consumed;                  // + 1 per compute wave and tile worked off
 };
 
 // Barrier that orders LDS traffic only: global loads issued before it stay in flight.
@@ -82,7 +84,29 @@ __device__ __forceinline__ void att_compute_barrier(att_smem *sm, uint32_t &arri
     uint32_t spins = 0;
     while ((int32_t)(__hip_atomic_load(&sm->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - arrivals) < 0) {
         __builtin_amdgcn_s_sleep(1);
-        if (++spins > (1u << 22)) {
+        if (++spins > (1u << 18)) {
+            if (lane == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+            break;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Hand-over between the halves, through two LDS counters that only grow: a fetch wave adds one to
+// `landed` per tile it has stored, a compute wave one to `consumed` per tile it is done with.
+// Nobody waits at a common point, so the fetch waves drift apart and HBM sees a steady stream
+// instead of four waves' loads in lockstep.  Waits are bounded like the compute barrier's.
+__device__ __forceinline__ void att_signal(uint32_t *counter, uint32_t lane)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    if (lane == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+__device__ __forceinline__ void att_wait(uint32_t *counter, uint32_t target, uint32_t lane, uint32_t *err)
+{
+    uint32_t spins = 0;
+    while ((int32_t)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - target) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > (1u << 18)) {
             if (lane == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
             break;
         }
@@ -195,9 +219,9 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_KSTEPS], const f32
 
 // 8 waves: waves 0..3 compute, waves 4..7 fetch; each half runs its own loop (so that each gets
 // the whole register file for what it alone needs) and both meet at the same barriers: two in
-// the prologue, one per tile (the LDS buffers change roles), one at the end.  While the compute
-// waves work on tile i in one LDS buffer, the fetch waves land tile i + 1, requested a tile ago,
-// in the other buffer as its rows arrive, and request tile i + 2 right after.
+// the prologue and one at the end; in between the halves hand tiles over through LDS counters.
+// While the compute waves work on tile i in one LDS buffer, the fetch waves land tile i + 1,
+// requested a tile ago, in the other buffer as its rows arrive, and request tile i + 2 right after.
 __global__ __launch_bounds__(512) void attend_ref_split(
     const uint16_t *__restrict__ q, uint32_t n_heads, const char *__restrict__ pool, uint64_t pool_stride,
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
@@ -230,7 +254,11 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     // tiles are taken two at a time; an odd count is padded by a tile without tokens (its
     // references are -1: it reads row 0, lands zeros and counts for nothing)
     const uint32_t n_pairs = (tile1 - tile0 + 1u) >> 1;
-    if (threadIdx.x == 0) sm->bar = 0;
+    if (threadIdx.x == 0) {
+        sm->bar = 0;
+        sm->landed = 0;
+        sm->consumed = 0;
+    }
 
     if (fetcher) {
         const att_args a = {pool, pool_stride, trig, pair_mode};
@@ -242,14 +270,17 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         att_land_rows(r, t4, hit, sm, 0, 0, a, cw, lane, ct);
         hit = att_load_trig(t4, sm, 1, a, ct);
         att_issue_rows(r, sm, 1, a, cw, lane, ct);
-        ATT_SYNC();                                         // prologue 2: tile0 landed, tile0 + 1 on its way
-        for (uint32_t k = 0; k < 2u * n_pairs; ++k) {       // k = tile - tile0
-            // during tile k: land k + 1 (requested during tile k - 1) as its rows arrive, then
-            // request k + 2 at once, so that it has a whole tile's time to arrive
-            att_land_rows(r, t4, hit, sm, (k + 1u) & 3u, (k + 1u) & 1u, a, cw, lane, ct);
-            hit = att_load_trig(t4, sm, (k + 2u) & 3u, a, ct);
-            att_issue_rows(r, sm, (k + 2u) & 3u, a, cw, lane, ct);
-            ATT_SYNC();
+        ATT_SYNC();                                         // prologue 2: counters are zero, tile0 is in place
+        att_signal(&sm->landed, lane);
+        for (uint32_t t = 1; t < 2u * n_pairs; ++t) {       // t = tile - tile0
+            // Tile t goes into the buffer tile t - 2 was worked off from; by then the references of
+            // tile t + 1 are published too.  Request t + 1 at once after landing t, so that it has a
+            // whole tile's time to arrive.
+            att_wait(&sm->consumed, 4u * (t - 1u), lane, err);
+            att_land_rows(r, t4, hit, sm, t & 3u, t & 1u, a, cw, lane, ct);
+            att_signal(&sm->landed, lane);
+            hit = att_load_trig(t4, sm, (t + 1u) & 3u, a, ct);
+            att_issue_rows(r, sm, (t + 1u) & 3u, a, cw, lane, ct);
         }
         __syncthreads();
         return;
@@ -331,6 +362,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         const uint32_t k = tile - tile0, cur = k & 1u;
         refs_rows(tile + 4, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
         next_sl = refs_slot(tile + 5);
+        att_wait(&sm->landed, 4u * (k + 1u), lane, err);    // tiles 0 .. k are in place
         // S = Q K^T for this wave's 16 tokens: lane holds S[head 4 lq + i][token 16 cw + lm]
         // (all 18 operands requested first, two accumulators: neither LDS nor MFMA latency adds up)
         const uint16_t *krow = sm->k[cur] + (16u * cw + lm) * ATT_KROW + 8u * lq;
@@ -401,7 +433,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
                                                                 __builtin_bit_cast(bf16x8, vv), o[nt], 0, 0, 0);
             }
         }
-        ATT_SYNC();                                         // D
+        att_signal(&sm->consumed, lane);                    // this wave is done with tile k
     };
     for (uint32_t pr = 0; pr < n_pairs; ++pr) {
         const uint32_t tile = tile0 + 2u * pr;
