@@ -31,6 +31,12 @@
  *   oracle_reattach_kr   the split-pool variant of the same step: c_KV is only
  *                        referenced, k_r alone is materialised (App. C "Split
  *                        TokenToKVPool")
+ *   oracle_s1_windows    S1 fallback: fixed windows inside chunks that missed
+ *                        (Sec. 4 "CDC+fallback"; App. G "S1")
+ *   oracle_reattach_ref  the no-materialise variant: row references and the per-hit
+ *                        rotation table (Sec. 7.2; App. C)
+ * (its consumer, attention over the references with the rotation applied on load, is
+ * stated in numpy in irm_oracle.py: attend_ref)
  *
  * Floating point: fp64 throughout, one round-to-nearest-even to bf16 at the
  * store.  Parity status: every function below is pinned by the CPU tests to
