@@ -70,6 +70,8 @@ typedef enum irm_status {
 #define IRM_FLAG_TABLE_FULL 0x2u     /* an insert found no free slot                             */
 #define IRM_FLAG_ROW_RANGE 0x4u      /* a hit or slot pointed outside its pool; row skipped      */
 #define IRM_FLAG_BAD_CHUNK 0x8u      /* a chunk record pointed outside the token array; skipped  */
+#define IRM_FLAG_WAIT_TIMEOUT 0x10u  /* a bounded in-kernel wait gave up (irm_attend_ref); the
+                                        kernel ended, its results are not to be used              */
 
 /* which two k_r elements form rotary pair i (App. D: DSv2-form and DSv3-form rotaries) */
 #define IRM_PAIR_HALF_SPLIT 0u  /* elements i and i + 32 */

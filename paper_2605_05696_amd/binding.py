@@ -19,6 +19,7 @@ IRM_OK, IRM_ERR_INVALID_ARG, IRM_ERR_CAPACITY, IRM_ERR_UNSUPPORTED, IRM_ERR_DEVI
 STATUS_NAMES = {0: "IRM_OK", 1: "IRM_ERR_INVALID_ARG", 2: "IRM_ERR_CAPACITY", 3: "IRM_ERR_UNSUPPORTED",
                 4: "IRM_ERR_DEVICE", 5: "IRM_ERR_TABLE_FULL"}
 IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_CHUNK = 1, 2, 4, 8
+IRM_FLAG_WAIT_TIMEOUT = 16
 
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",

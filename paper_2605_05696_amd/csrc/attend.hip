@@ -75,7 +75,7 @@ struct att_smem {
 // Barrier among the four compute waves only, through an LDS counter, so that the fetch waves are
 // not held at the two points inside a tile where only the compute waves must agree.  The four
 // waves are resident together and run the same tile loop, so every wait ends; the wait is
-// bounded all the same (a wave that gives up raises IRM_FLAG_ROW_RANGE and carries on).
+// bounded all the same (a wave that gives up raises IRM_FLAG_WAIT_TIMEOUT and carries on).
 __device__ __forceinline__ void att_compute_barrier(att_smem *sm, uint32_t &arrivals, uint32_t lane, uint32_t *err)
 {
     arrivals += 4u;
@@ -85,7 +85,7 @@ __device__ __forceinline__ void att_compute_barrier(att_smem *sm, uint32_t &arri
     while ((int32_t)(__hip_atomic_load(&sm->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - arrivals) < 0) {
         __builtin_amdgcn_s_sleep(1);
         if (++spins > (1u << 18)) {
-            if (lane == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+            if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
             break;
         }
     }
@@ -107,7 +107,7 @@ __device__ __forceinline__ void att_wait(uint32_t *counter, uint32_t target, uin
     while ((int32_t)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - target) < 0) {
         __builtin_amdgcn_s_sleep(1);
         if (++spins > (1u << 18)) {
-            if (lane == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+            if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
             break;
         }
     }
