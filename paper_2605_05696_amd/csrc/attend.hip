@@ -59,8 +59,8 @@ struct att_smem {
     float mfin[ATT_HEADS];              // running maximum per head at the end
     int32_t row[4][ATT_TILE];           // pool row of each tile token, -1 = no token; slot = tile mod 4
     int32_t hit[4][ATT_TILE];           // rotation of each tile token, -1 = none
+    uint32_t landed[4];                 // per fetch wave: tiles it has landed so far
     uint32_t bar;                       // arrivals at the compute waves' own barrier
-    uint32_t landed;                    // + 1 per fetch wave and tile landed
     uint32_t consumed;                  // + 1 per compute wave and tile worked off
 };
 
@@ -92,10 +92,15 @@ __device__ __forceinline__ void att_compute_barrier(att_smem *sm, uint32_t &arri
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// Hand-over between the halves, through two LDS counters that only grow: a fetch wave adds one to
-// `landed` per tile it has stored, a compute wave one to `consumed` per tile it is done with.
-// Nobody waits at a common point, so the fetch waves drift apart and HBM sees a steady stream
-// instead of four waves' loads in lockstep.  Waits are bounded like the compute barrier's.
+// Hand-over between the halves, through LDS counters that only grow: a fetch wave adds one to
+// its own `landed` entry per tile it has stored, a compute wave one to `consumed` per tile it is
+// done with.  Nobody waits at a common point, so the fetch waves drift apart and HBM sees a steady
+// stream instead of four waves' loads in lockstep.  Waits are bounded like the compute barrier's.
+// The fetch waves may be a tile apart (one may land tile t + 1 while another still lands t), so
+// a sum over them would not say that tile t is whole: each has its own counter and a compute
+// wave waits for all four.  The compute waves meet at their barrier twice per tile and are never
+// a whole tile apart, so for them the sum in `consumed` is enough: it reaches 4 n only when each
+// has finished n tiles.
 __device__ __forceinline__ void att_signal(uint32_t *counter, uint32_t lane)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -105,6 +110,25 @@ __device__ __forceinline__ void att_wait(uint32_t *counter, uint32_t target, uin
 {
     uint32_t spins = 0;
     while ((int32_t)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - target) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > (1u << 18)) {
+            if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
+            break;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+__device__ __forceinline__ void att_wait_landed(uint32_t *landed, uint32_t target, uint32_t lane, uint32_t *err)
+{
+    uint32_t spins = 0;
+    for (;;) {
+        uint32_t least = __hip_atomic_load(landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const uint32_t v = __hip_atomic_load(landed + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            least = (int32_t)(v - least) < 0 ? v : least;
+        }
+        if ((int32_t)(least - target) >= 0) break;
         __builtin_amdgcn_s_sleep(1);
         if (++spins > (1u << 18)) {
             if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
@@ -256,8 +280,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     const uint32_t n_pairs = (tile1 - tile0 + 1u) >> 1;
     if (threadIdx.x == 0) {
         sm->bar = 0;
-        sm->landed = 0;
         sm->consumed = 0;
+        for (int w = 0; w < 4; ++w) sm->landed[w] = 0;
     }
 
     if (fetcher) {
@@ -271,14 +295,14 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         hit = att_load_trig(t4, sm, 1, a, ct);
         att_issue_rows(r, sm, 1, a, cw, lane, ct);
         ATT_SYNC();                                         // prologue 2: counters are zero, tile0 is in place
-        att_signal(&sm->landed, lane);
+        att_signal(&sm->landed[cw], lane);
         for (uint32_t t = 1; t < 2u * n_pairs; ++t) {       // t = tile - tile0
             // Tile t goes into the buffer tile t - 2 was worked off from; by then the references of
             // tile t + 1 are published too.  Request t + 1 at once after landing t, so that it has a
             // whole tile's time to arrive.
             att_wait(&sm->consumed, 4u * (t - 1u), lane, err);
             att_land_rows(r, t4, hit, sm, t & 3u, t & 1u, a, cw, lane, ct);
-            att_signal(&sm->landed, lane);
+            att_signal(&sm->landed[cw], lane);
             hit = att_load_trig(t4, sm, (t + 1u) & 3u, a, ct);
             att_issue_rows(r, sm, (t + 1u) & 3u, a, cw, lane, ct);
         }
@@ -362,7 +386,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         const uint32_t k = tile - tile0, cur = k & 1u;
         refs_rows(tile + 4, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
         next_sl = refs_slot(tile + 5);
-        att_wait(&sm->landed, 4u * (k + 1u), lane, err);    // tiles 0 .. k are in place
+        att_wait_landed(sm->landed, k + 1u, lane, err);     // tiles 0 .. k are in place, whole
         // S = Q K^T for this wave's 16 tokens: lane holds S[head 4 lq + i][token 16 cw + lm]
         // (all 18 operands requested first, two accumulators: neither LDS nor MFMA latency adds up)
         const uint16_t *krow = sm->k[cur] + (16u * cw + lm) * ATT_KROW + 8u * lq;

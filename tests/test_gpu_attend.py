@@ -1,11 +1,17 @@
 """GPU parity of the rotate-on-load consumer, irm_attend_ref (paper Sec. 2 "MLA"; Sec. 7.2 and
 App. C: rotation fused into the attention load path), against the fp64 oracle.
 
-Tolerance.  The kernel rounds the rotated k_r, the softmax numerators and (as inputs) q and the
-pool rows to bf16 (relative 2^-9) and accumulates in fp32.  With N(0,1) data, 576-dim dots scaled by
-1/sqrt(192), the scores carry an absolute error of about 2^-9 * scale * |q_r| |k_r| ~ 1e-2, i.e.
-about 1 % on a probability, and the numerators another 2^-9; an output is a convex combination of
-N(0,1) values, so |out - oracle| stays below 3e-2 (mean far smaller), |lse - oracle| below 2e-2.
+Tolerance.  The kernel rounds the rotated k_r and the softmax numerators to bf16 (relative error
+at most 2^-9, about 1e-3 rms) and accumulates in fp32; the oracle rounds nothing.  With N(0,1) data
+and scale 1/sqrt(192) the 64 rounded k_r elements put about scale * 8 * 1e-3 ~ 6e-4 rms on a score
+(worst case, all 64 errors aligned: 2^-9 * scale * sum |q_i k_i| ~ 6e-3, which is what the lse of
+a context of a few tokens, which follows its largest score, is allowed), and a numerator carries
+another 2^-9.  An output is a convex combination of pool values of size <= 3, so a context of a few
+tokens can be off by 2^-9 * 3 ~ 6e-3; over thousands of tokens the independent errors average out
+and the measured maxima are 7e-4 (output) and 2e-4 (lse), against which a context of 4,096 tokens
+or more is held to 2e-3 and 6e-4.  That bound is what catches a broken hand-over between the waves:
+one 64-token tile lost or taken twice moves the lse of a 16,384-token context by 4e-3.  The
+kernel has no floating-point atomics: the same call twice gives the same bits.
 """
 import numpy as np
 import pytest
@@ -70,12 +76,14 @@ def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None):
         s.close()
 
 
-def check(got, got_lse, want, want_lse):
+def check(got, got_lse, want, want_lse, long_contexts=False):
+    tol_out, tol_lse = (2e-3, 6e-4) if long_contexts else (6e-3, 6e-3)
     err = np.abs(got - want)
-    assert err.max() < 3e-2 and err.mean() < 4e-3, (err.max(), err.mean())
+    assert err.max() < tol_out and err.mean() < 4e-4, (err.max(), err.mean())
     fin = np.isfinite(want_lse)
     assert np.array_equal(np.isfinite(got_lse), fin)
-    assert np.all(np.isneginf(got_lse[~fin])) and np.abs(got_lse[fin] - want_lse[fin]).max() < 2e-2
+    assert np.all(np.isneginf(got_lse[~fin]))
+    assert np.abs(got_lse[fin] - want_lse[fin]).max() < tol_lse, np.abs(got_lse[fin] - want_lse[fin]).max()
 
 
 @pytest.mark.parametrize("name,n_heads,n_splits,pair_mode", [("c2", 16, 1, 0), ("c2", 16, 5, 1), ("c1", 32, 8, 0),
@@ -84,7 +92,10 @@ def test_attend_ref_small_configs(name, n_heads, n_splits, pair_mode):
     w = wl.make_workload(name, orc.cdc_chunk, size="small")
     hits = oracle_front(w)["hits"]
     got, got_lse, want, want_lse = run_case(w, hits, n_heads, n_splits, pair_mode, seed=11)
-    check(got, got_lse, want, want_lse)
+    assert np.diff(w.req_offsets).min() >= 4096
+    check(got, got_lse, want, want_lse, long_contexts=True)
+    again, again_lse, _, _ = run_case(w, hits, n_heads, n_splits, pair_mode, seed=11)
+    assert np.array_equal(got, again) and np.array_equal(got_lse, again_lse)
 
 
 def test_attend_ref_ragged_contexts_empty_and_short_requests():

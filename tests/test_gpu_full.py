@@ -290,6 +290,12 @@ def test_full_size_attend_ref_c2():
         ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, H, splits), dtype=torch.uint8, device=DEV)
         B.irm_attend_ref(rig.s.ctx, q, pool, ROW * 2, rig.d_dst_slots, rig.d_req_offsets, row, hit, trig, scale, splits,
                          ws, out, lse)
+        first = out.clone()
+        for _ in range(3):                                                # same bits every time: no tile is handed
+            out.zero_()                                                   # over early or late now and then
+            B.irm_attend_ref(rig.s.ctx, q, pool, ROW * 2, rig.d_dst_slots, rig.d_req_offsets, row, hit, trig, scale,
+                             splits, ws, out, lse)
+            assert torch.equal(out, first)
         torch.cuda.synchronize()
         assert rig.s.error_flags() == 0
         want_row = np.full(w.dst_rows, -1, np.int32)
@@ -298,8 +304,9 @@ def test_full_size_attend_ref_c2():
         assert np.array_equal(want_hit, hit_h)
         want, want_lse = orc.attend_ref(bits(q), bits(pool), w.dst_slots, w.req_offsets, row_h, hit_h, trig64, scale)
         err = np.abs(out.cpu().numpy() - want)
-        # 16,384 tokens per softmax: outputs are averages of thousands of rows, errors shrink with them
-        assert err.max() < 3e-2 and err.mean() < 1e-3, (err.max(), err.mean())
-        assert np.abs(lse.cpu().numpy() - want_lse).max() < 2e-2
+        # 16,384 tokens per softmax: the bf16 roundings average out (measured 6e-4 and 2e-4); one 64-token
+        # tile lost or doubled would move the lse by 4e-3 and the outputs by about as much
+        assert err.max() < 2e-3 and err.mean() < 2e-4, (err.max(), err.mean())
+        assert np.abs(lse.cpu().numpy() - want_lse).max() < 6e-4
     finally:
         rig.close()
