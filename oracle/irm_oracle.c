@@ -50,6 +50,17 @@
 
 #define ORACLE_ROW_DIM 576 /* 512 c_KV + 64 k_r elements per token row (Sec. 2 "MLA") */
 #define ORACLE_CKV_DIM 512
+/* Row formats.  A row is a position-free part followed by the 64 bf16 elements of k_r; its
+ * size is given in 16-bit words ("ckv_words") wherever a function takes rows:
+ *   512  bf16 rows: c_KV as 512 bf16
+ *   264  fp8 rows (Sec. 7.2 names FP8 KV quantisation as accepted practice; the layout is the
+ *        one published for fp8 MLA caches): c_KV as 512 e4m3 bytes, then four fp32 scales,
+ *        one per 128 elements -- 528 bytes that depend on the content only -- and k_r kept
+ *        in bf16.
+ * The position-free part is copied bit for bit, whatever it encodes; the rotation acts on
+ * k_r alone (Alg. 1 steps 9-10). */
+#define ORACLE_CKV_WORDS_BF16 512
+#define ORACLE_CKV_WORDS_FP8 264
 #define ORACLE_KR_DIM 64
 #define ORACLE_KR_PAIRS 32
 
@@ -278,37 +289,39 @@ void oracle_rotate_kr_f64(const double *k_in /* [64] */, int64_t delta,
     }
 }
 
-/* One 576-element bf16 KV row: c_KV bits copied, k_r rotated and rounded once. */
+/* One KV row of ckv_words + 64 words: the position-free part copied, k_r rotated and
+ * rounded once. */
 void oracle_reattach_row(const uint16_t *row_in, int32_t delta, const float *inv_freq,
-                         uint32_t pair_mode, uint16_t *row_out)
+                         uint32_t pair_mode, uint32_t ckv_words, uint16_t *row_out)
 {
-    for (int d = 0; d < ORACLE_CKV_DIM; ++d) row_out[d] = row_in[d];
+    for (uint32_t d = 0; d < ckv_words; ++d) row_out[d] = row_in[d];
     double k[ORACLE_KR_DIM], kr[ORACLE_KR_DIM];
-    for (int d = 0; d < ORACLE_KR_DIM; ++d) k[d] = oracle_bf16_to_f64(row_in[ORACLE_CKV_DIM + d]);
+    for (int d = 0; d < ORACLE_KR_DIM; ++d) k[d] = oracle_bf16_to_f64(row_in[ckv_words + d]);
     oracle_rotate_kr_f64(k, (int64_t)delta, inv_freq, pair_mode, kr);
-    for (int d = 0; d < ORACLE_KR_DIM; ++d) row_out[ORACLE_CKV_DIM + d] = oracle_f64_to_bf16(kr[d]);
+    for (int d = 0; d < ORACLE_KR_DIM; ++d) row_out[ckv_words + d] = oracle_f64_to_bf16(kr[d]);
 }
 
 /* For every hit h, layer l and j < len[h]:
  *   dst[l][ dst_slots[dst_tok[h] + j] ] <- reattach_row( src[l][ src_row[h] + j ], delta[h] )
- * src is [n_layers][src_rows][576] bf16, dst is [n_layers][dst_rows][576] bf16,
+ * src is [n_layers][src_rows][ckv_words + 64], dst is [n_layers][dst_rows][ckv_words + 64],
  * both dense.  Rows of dst that no hit covers are left as they were.
  * Returns 0, or -1 when an index falls outside its pool. */
 int oracle_reattach(const uint16_t *src, uint64_t src_rows, uint16_t *dst, uint64_t dst_rows,
                     uint32_t n_layers, const int32_t *dst_slots, const uint32_t *hit_src_row,
                     const uint32_t *hit_dst_tok, const uint32_t *hit_len,
                     const int32_t *hit_delta, uint32_t n_hits, const float *inv_freq,
-                    uint32_t pair_mode)
+                    uint32_t pair_mode, uint32_t ckv_words)
 {
+    const uint64_t row_words = (uint64_t)ckv_words + ORACLE_KR_DIM;
     for (uint32_t h = 0; h < n_hits; ++h) {
         for (uint32_t l = 0; l < n_layers; ++l) {
             for (uint32_t j = 0; j < hit_len[h]; ++j) {
                 uint64_t srow = (uint64_t)hit_src_row[h] + j;
                 int64_t drow = dst_slots[(uint64_t)hit_dst_tok[h] + j];
                 if (srow >= src_rows || drow < 0 || (uint64_t)drow >= dst_rows) return -1;
-                const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * ORACLE_ROW_DIM;
-                uint16_t *out = dst + ((uint64_t)l * dst_rows + (uint64_t)drow) * ORACLE_ROW_DIM;
-                oracle_reattach_row(in, hit_delta[h], inv_freq, pair_mode, out);
+                const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * row_words;
+                uint16_t *out = dst + ((uint64_t)l * dst_rows + (uint64_t)drow) * row_words;
+                oracle_reattach_row(in, hit_delta[h], inv_freq, pair_mode, ckv_words, out);
             }
         }
     }
@@ -321,15 +334,16 @@ int oracle_reattach(const uint16_t *src, uint64_t src_rows, uint16_t *dst, uint6
 /* slice alone is materialised per request, rotated by delta.                  */
 /* For every hit h, j < len[h], slot = dst_slots[dst_tok[h] + j]:              */
 /*   ckv_index[slot]      <- src_row[h] + j              (same for all layers) */
-/*   kr_dst[l][slot][0:64] <- R(delta[h]) src[l][src_row[h] + j][512:576]       */
-/* src is [n_layers][src_rows][576] bf16, kr_dst is [n_layers][kr_rows][64].    */
+/*   kr_dst[l][slot][0:64] <- R(delta[h]) k_r of src[l][src_row[h] + j]         */
+/* src is [n_layers][src_rows][ckv_words + 64], kr_dst is [n_layers][kr_rows][64]. */
 /* ------------------------------------------------------------------------- */
 int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst, uint64_t kr_rows,
                        int32_t *ckv_index, uint32_t n_layers, const int32_t *dst_slots,
                        const uint32_t *hit_src_row, const uint32_t *hit_dst_tok,
                        const uint32_t *hit_len, const int32_t *hit_delta, uint32_t n_hits,
-                       const float *inv_freq, uint32_t pair_mode)
+                       const float *inv_freq, uint32_t pair_mode, uint32_t ckv_words)
 {
+    const uint64_t row_words = (uint64_t)ckv_words + ORACLE_KR_DIM;
     for (uint32_t h = 0; h < n_hits; ++h) {
         for (uint32_t j = 0; j < hit_len[h]; ++j) {
             uint64_t srow = (uint64_t)hit_src_row[h] + j;
@@ -337,7 +351,7 @@ int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst,
             if (srow >= src_rows || slot < 0 || (uint64_t)slot >= kr_rows) return -1;
             ckv_index[slot] = (int32_t)srow;
             for (uint32_t l = 0; l < n_layers; ++l) {
-                const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * ORACLE_ROW_DIM + ORACLE_CKV_DIM;
+                const uint16_t *in = src + ((uint64_t)l * src_rows + srow) * row_words + ckv_words;
                 uint16_t *out = kr_dst + ((uint64_t)l * kr_rows + (uint64_t)slot) * ORACLE_KR_DIM;
                 double k[ORACLE_KR_DIM], kr[ORACLE_KR_DIM];
                 for (int d = 0; d < ORACLE_KR_DIM; ++d) k[d] = oracle_bf16_to_f64(in[d]);
@@ -366,7 +380,7 @@ int oracle_reattach_kr(const uint16_t *src, uint64_t src_rows, uint16_t *kr_dst,
 /* p_src = p), *cursor advances, and admitted_row[c] is the first row; all      */
 /* other chunks get admitted_row[c] = -1.  new_* receive the registry entries   */
 /* in admission order (entry_id = first pool row).  Returns their number.       */
-/* req is [n_layers][req_rows][576], pool is [n_layers][pool_rows][576].        */
+/* req is [n_layers][req_rows][ckv_words + 64], pool the same with pool_rows.   */
 /* ------------------------------------------------------------------------- */
 int64_t oracle_admit(const uint64_t *reg_hash, uint64_t n_reg, const uint64_t *chunk_hash,
                      const uint32_t *chunk_start, const uint32_t *chunk_len,
@@ -375,8 +389,9 @@ int64_t oracle_admit(const uint64_t *reg_hash, uint64_t n_reg, const uint64_t *c
                      const int32_t *chunk_entry, const uint16_t *req, uint64_t req_rows,
                      const int32_t *slots, uint16_t *pool, uint64_t pool_rows, uint32_t n_layers,
                      uint32_t *cursor, int32_t *admitted_row, uint64_t *new_hash,
-                     uint32_t *new_src_row, int32_t *new_p_src, uint32_t *new_len)
+                     uint32_t *new_src_row, int32_t *new_p_src, uint32_t *new_len, uint32_t ckv_words)
 {
+    const uint64_t row_words = (uint64_t)ckv_words + ORACLE_KR_DIM;
     int64_t n_new = 0;
     int pool_closed = 0;
     for (uint32_t r = 0; r < n_req; ++r) {
@@ -396,9 +411,9 @@ int64_t oracle_admit(const uint64_t *reg_hash, uint64_t n_reg, const uint64_t *c
                 for (uint32_t j = 0; j < chunk_len[c]; ++j) {
                     int64_t slot = slots[(uint64_t)chunk_start[c] + j];
                     if (slot < 0 || (uint64_t)slot >= req_rows) return -1;
-                    memcpy(pool + ((uint64_t)l * pool_rows + *cursor + j) * ORACLE_ROW_DIM,
-                           req + ((uint64_t)l * req_rows + (uint64_t)slot) * ORACLE_ROW_DIM,
-                           ORACLE_ROW_DIM * sizeof(uint16_t));
+                    memcpy(pool + ((uint64_t)l * pool_rows + *cursor + j) * row_words,
+                           req + ((uint64_t)l * req_rows + (uint64_t)slot) * row_words,
+                           row_words * sizeof(uint16_t));
                 }
             }
             admitted_row[c] = (int32_t)*cursor;

@@ -19,6 +19,14 @@ _SRC = os.path.join(_HERE, "irm_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 ROW_DIM = 576
+# 16-bit words of a row's position-free part: bf16 rows (512 bf16 c_KV) / fp8 rows (512 e4m3 bytes
+# and four fp32 block scales); the 64 bf16 elements of k_r follow
+CKV_WORDS_BF16, CKV_WORDS_FP8 = 512, 264
+
+
+def _ckv_words(row_words: int) -> int:
+    assert row_words - KR_DIM in (CKV_WORDS_BF16, CKV_WORDS_FP8), "rows are 576 (bf16) or 328 (fp8) words"
+    return row_words - KR_DIM
 CKV_DIM = 512
 KR_DIM = 64
 
@@ -182,20 +190,23 @@ def rotate_kr_f64(k, delta, inv_freq, pair_mode=0) -> np.ndarray:
 def reattach_row(row_bits, delta, inv_freq, pair_mode=0) -> np.ndarray:
     row_bits = _arr(row_bits, np.uint16)
     inv_freq = _arr(inv_freq, np.float32)
-    assert row_bits.shape == (ROW_DIM,) and inv_freq.shape == (KR_DIM // 2,)
-    out = np.zeros(ROW_DIM, np.uint16)
+    assert row_bits.ndim == 1 and inv_freq.shape == (KR_DIM // 2,)
+    ckv_words = _ckv_words(len(row_bits))
+    out = np.zeros(len(row_bits), np.uint16)
     lib().oracle_reattach_row(_p(row_bits, ctypes.c_uint16), ctypes.c_int32(int(delta)),
                               _p(inv_freq, ctypes.c_float), ctypes.c_uint32(pair_mode),
-                              _p(out, ctypes.c_uint16))
+                              ctypes.c_uint32(ckv_words), _p(out, ctypes.c_uint16))
     return out
 
 
 def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq, pair_mode=0) -> None:
-    """In place on ``dst_bits``.  src_bits [L][src_rows][576] u16, dst_bits [L][dst_rows][576] u16."""
+    """In place on ``dst_bits``.  src_bits [L][src_rows][W] u16, dst_bits [L][dst_rows][W] u16,
+    W = 576 (bf16 rows) or 328 (fp8 rows)."""
     assert src_bits.dtype == np.uint16 and dst_bits.dtype == np.uint16
     assert src_bits.flags.c_contiguous and dst_bits.flags.c_contiguous
     assert src_bits.ndim == 3 and dst_bits.ndim == 3
-    assert src_bits.shape[2] == ROW_DIM and dst_bits.shape[2] == ROW_DIM
+    assert src_bits.shape[2] == dst_bits.shape[2]
+    ckv_words = _ckv_words(src_bits.shape[2])
     assert src_bits.shape[0] == dst_bits.shape[0]
     dst_slots = _arr(dst_slots, np.int32)
     inv_freq = _arr(inv_freq, np.float32)
@@ -210,7 +221,7 @@ def reattach(src_bits, dst_bits, dst_slots, hits: Hits, inv_freq, pair_mode=0) -
         ctypes.c_uint32(src_bits.shape[0]), _p(dst_slots, ctypes.c_int32),
         _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32),
         _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float),
-        ctypes.c_uint32(pair_mode))
+        ctypes.c_uint32(pair_mode), ctypes.c_uint32(ckv_words))
     if rc != 0:
         raise IndexError("oracle_reattach: a hit or slot points outside its pool")
 
@@ -219,7 +230,8 @@ def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq, p
     """Split-pool variant, in place on ``kr_bits`` [L][kr_rows][64] u16 and ``ckv_index`` i32[kr_rows]."""
     assert src_bits.dtype == np.uint16 and kr_bits.dtype == np.uint16 and ckv_index.dtype == np.int32
     assert src_bits.flags.c_contiguous and kr_bits.flags.c_contiguous and ckv_index.flags.c_contiguous
-    assert src_bits.ndim == 3 and kr_bits.ndim == 3 and src_bits.shape[2] == ROW_DIM and kr_bits.shape[2] == KR_DIM
+    assert src_bits.ndim == 3 and kr_bits.ndim == 3 and kr_bits.shape[2] == KR_DIM
+    ckv_words = _ckv_words(src_bits.shape[2])
     assert src_bits.shape[0] == kr_bits.shape[0] and len(ckv_index) == kr_bits.shape[1]
     dst_slots = _arr(dst_slots, np.int32)
     inv_freq = _arr(inv_freq, np.float32)
@@ -233,7 +245,7 @@ def reattach_kr(src_bits, kr_bits, ckv_index, dst_slots, hits: Hits, inv_freq, p
         ctypes.c_uint32(src_bits.shape[0]), _p(dst_slots, ctypes.c_int32),
         _p(hs, ctypes.c_uint32), _p(hd, ctypes.c_uint32), _p(hl, ctypes.c_uint32),
         _p(hx, ctypes.c_int32), ctypes.c_uint32(len(hs)), _p(inv_freq, ctypes.c_float),
-        ctypes.c_uint32(pair_mode))
+        ctypes.c_uint32(pair_mode), ctypes.c_uint32(ckv_words))
     if rc != 0:
         raise IndexError("oracle_reattach_kr: a hit or slot points outside its pool")
 
@@ -253,7 +265,8 @@ def admit(reg_hash, chunk_hash_, chunk_start, chunk_len, req_chunk_offsets, req_
     slots = _arr(slots, np.int32)
     assert req_bits.dtype == np.uint16 and pool_bits.dtype == np.uint16
     assert req_bits.flags.c_contiguous and pool_bits.flags.c_contiguous
-    assert req_bits.ndim == 3 and pool_bits.ndim == 3 and req_bits.shape[2] == ROW_DIM == pool_bits.shape[2]
+    assert req_bits.ndim == 3 and pool_bits.ndim == 3 and req_bits.shape[2] == pool_bits.shape[2]
+    ckv_words = _ckv_words(req_bits.shape[2])
     assert req_bits.shape[0] == pool_bits.shape[0]
     C = len(chunk_hash_)
     cur = ctypes.c_uint32(int(cursor))
@@ -270,7 +283,7 @@ def admit(reg_hash, chunk_hash_, chunk_start, chunk_len, req_chunk_offsets, req_
         ctypes.c_uint64(req_bits.shape[1]), _p(slots, ctypes.c_int32), _p(pool_bits, ctypes.c_uint16),
         ctypes.c_uint64(pool_bits.shape[1]), ctypes.c_uint32(req_bits.shape[0]), ctypes.byref(cur),
         _p(admitted, ctypes.c_int32), _p(nh, ctypes.c_uint64), _p(ns, ctypes.c_uint32),
-        _p(npos, ctypes.c_int32), _p(nl, ctypes.c_uint32))
+        _p(npos, ctypes.c_int32), _p(nl, ctypes.c_uint32), ctypes.c_uint32(ckv_words))
     if n < 0:
         raise IndexError("oracle_admit: a slot points outside the request pool")
     new = dict(hash=nh[:n].copy(), src_row=ns[:n].copy(), p_src=npos[:n].copy(), len=nl[:n].copy(),

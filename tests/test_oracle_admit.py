@@ -87,3 +87,21 @@ def test_insert_if_absent_carve_out_and_pool_full():
     assert cursor == 164 and new["hash"].tolist() == [11] and new["p_src"].tolist() == [64]
     assert np.array_equal(pool[0, 100:164], req[0, slots[64:128]])
     assert np.all(pool[0, 164:] == 0) and np.all(pool[0, :100] == 0)
+
+
+def test_fp8_rows_are_admitted_whole():
+    """656-byte rows (quantised c_KV, its scales, bf16 k_r) go into the pool bit for bit."""
+    rng = np.random.default_rng(5)
+    L, n = 2, 200
+    start = np.array([0, 70, 140], np.uint32)
+    length = np.array([70, 70, 60], np.uint32)
+    req = rng.integers(0, 65536, (L, n, 328), dtype=np.uint16)
+    slots = rng.permutation(n).astype(np.int32)
+    pool = np.zeros((L, 150, 328), np.uint16)
+    admitted, new, cursor = orc.admit(np.zeros(0, np.uint64), np.array([7, 8, 9], np.uint64), start, length,
+                                      np.array([0, 3], np.uint32), np.array([0, n], np.uint32),
+                                      np.array([100], np.int32), 32, np.full(3, -1, np.int32), req, slots, pool, 5)
+    assert admitted.tolist() == [5, 75, -1] and cursor == 145       # the third chunk does not fit
+    assert np.array_equal(pool[:, 5:75], req[:, slots[0:70]]) and np.array_equal(pool[:, 75:145], req[:, slots[70:140]])
+    assert np.all(pool[:, :5] == 0) and np.all(pool[:, 145:] == 0)
+    assert new["p_src"].tolist() == [100, 170] and new["src_row"].tolist() == [5, 75]

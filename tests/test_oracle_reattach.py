@@ -374,3 +374,65 @@ def test_reference_variant_rotated_at_load_time_equals_the_materialised_rows(pai
         step = np.abs(got.astype(np.int32) - want[:, slot, 512:].astype(np.int32))
         assert step.max() <= 1                                             # complex product vs the oracle's a c - b s
         assert (step == 0).mean() > 0.99
+
+
+# ----------------------------------------------------------------- fp8 rows --
+
+def fp8_rows(rng, shape_lr, kr_bits):
+    """[L][rows][328] u16: 512 arbitrary bytes (e4m3 codes, every pattern allowed), four fp32 scales,
+    then the given 64 bf16 k_r elements."""
+    L, rows = shape_lr
+    out = np.empty((L, rows, 328), np.uint16)
+    out[:, :, :256] = rng.integers(0, 65536, (L, rows, 256), dtype=np.uint16)
+    scales = rng.uniform(1e-3, 4.0, (L, rows, 4)).astype(np.float32)
+    out[:, :, 256:264] = scales.view(np.uint16).reshape(L, rows, 8)
+    out[:, :, 264:] = kr_bits
+    return out
+
+
+@pytest.mark.parametrize("pair_mode", [0, 1], ids=["half-split", "interleaved"])
+def test_fp8_rows_copy_the_quantised_part_and_rotate_kr_as_in_bf16_rows(pair_mode):
+    """Rows whose c_KV is quantised (512 e4m3 bytes and four fp32 block scales, k_r left in bf16):
+    the 528 position-free bytes come through bit for bit, the k_r that follows them is the k_r a
+    bf16 row with the same key gets, and nothing else is written."""
+    rng = np.random.default_rng(21)
+    L, src_rows, dst_rows = 2, 40, 33
+    wide = bf16_bits(rng.standard_normal((L, src_rows, 576)))
+    src = fp8_rows(rng, (L, src_rows), wide[:, :, 512:])
+    slots = rng.permutation(dst_rows).astype(np.int32)
+    hits = orc.Hits(src_row=np.array([4, 22], np.uint32), dst_tok=np.array([0, 17], np.uint32),
+                    len=np.array([6, 10], np.uint32), delta=np.array([1234, -77], np.int32))
+    dst = np.full((L, dst_rows, 328), wl.SENTINEL_BF16, np.uint16)
+    orc.reattach(src, dst, slots, hits, INV, pair_mode)
+    ref = np.full((L, dst_rows, 576), wl.SENTINEL_BF16, np.uint16)
+    orc.reattach(wide, ref, slots, hits, INV, pair_mode)
+    assert np.array_equal(dst[:, :, 264:], ref[:, :, 512:])            # same keys, same untouched rows
+    touched = np.zeros(dst_rows, bool)
+    for h in range(2):
+        for j in range(int(hits.len[h])):
+            srow, drow = int(hits.src_row[h]) + j, int(slots[int(hits.dst_tok[h]) + j])
+            touched[drow] = True
+            assert np.array_equal(dst[:, drow, :264], src[:, srow, :264])
+            # the key sits right behind the 528 bytes: complex form of the rotation, one bf16 step allowed
+            k = orc.bf16_to_f64(src[0, srow, 264:])
+            a, b = (k[0::2], k[1::2]) if pair_mode else (k[:32], k[32:])
+            z = (a + 1j * b) * np.exp(1j * int(hits.delta[h]) * INV.astype(np.float64))
+            got = orc.bf16_to_f64(dst[0, drow, 264:])
+            ga, gb = (got[0::2], got[1::2]) if pair_mode else (got[:32], got[32:])
+            assert np.all(np.abs(ga - z.real) <= np.abs(z.real) * 2.0 ** -8 + 1e-30)
+            assert np.all(np.abs(gb - z.imag) <= np.abs(z.imag) * 2.0 ** -8 + 1e-30)
+    assert touched.sum() == 16 and np.all(dst[:, ~touched] == wl.SENTINEL_BF16)
+    # one row alone, and the identity
+    one = orc.reattach_row(src[1, 9], 0, INV, pair_mode)
+    assert one.shape == (328,) and np.array_equal(one, src[1, 9])
+    # split pool over fp8 rows: the same keys, references to the same rows
+    kr = np.full((L, dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
+    idx = np.full(dst_rows, -1, np.int32)
+    orc.reattach_kr(src, kr, idx, slots, hits, INV, pair_mode)
+    assert np.array_equal(kr, dst[:, :, 264:]) and np.array_equal(idx >= 0, touched)
+    assert np.array_equal(src[:, idx[touched], :264], dst[:, touched, :264])
+
+
+def test_rows_of_any_other_width_are_refused():
+    with pytest.raises(AssertionError):
+        orc.reattach_row(np.zeros(320, np.uint16), 1, INV)
