@@ -78,6 +78,14 @@ typedef enum irm_status {
 #define IRM_PAIR_INTERLEAVED 1u /* elements 2i and 2i + 1 */
 #define IRM_KR_PAIRS 32
 
+/* layout of one token's KV row in every pool the library reads or writes: a position-free
+ * part, then k_r as 64 bf16 elements.  The position-free part is moved bit for bit, the
+ * rotation acts on k_r alone (Alg. 1 steps 9-10), so a quantised c_KV needs no arithmetic. */
+#define IRM_ROW_BF16 0u /* 1152 bytes: c_KV as 512 bf16 | k_r                                   */
+#define IRM_ROW_FP8 1u  /* 656 bytes: c_KV as 512 e4m3 bytes | four fp32 scales, one per 128
+                           elements | k_r (Sec. 7.2 counts FP8 KV quantisation as accepted
+                           practice; this is the layout published for fp8 MLA caches)          */
+
 typedef struct irm_config {
     /* CDC (paper Sec. 4, Sec. 7.2 "CDC boundary rule", App. B) */
     uint32_t gear[256];   /* gear table; one step per token, indexed by the id's low byte */
@@ -86,11 +94,13 @@ typedef struct irm_config {
     uint32_t max_chunk;   /* >= min_chunk, <= 65536                                         */
     /* lookup (Sec. 7.1): chunks at absolute position < carve_out are never served; 0 = off */
     uint32_t carve_out;
-    /* KV geometry: only 512 + 64; pair_mode is IRM_PAIR_HALF_SPLIT or IRM_PAIR_INTERLEAVED */
+    /* KV geometry: only 512 + 64; pair_mode is IRM_PAIR_HALF_SPLIT or IRM_PAIR_INTERLEAVED;
+     * row_format is IRM_ROW_BF16 or IRM_ROW_FP8 */
     uint32_t n_layers;
     uint32_t ckv_dim;
     uint32_t kr_dim;
     uint32_t pair_mode;
+    uint32_t row_format;
     /* the model's fp32 rotary inverse frequencies (App. D: cos/sin are derived from
      * this buffer, never from a position table); pure rotation, no magnitude factor */
     float inv_freq[IRM_KR_PAIRS];
@@ -117,6 +127,10 @@ typedef struct irm_hit {
 
 typedef struct irm_ctx irm_ctx;
 typedef struct irm_table irm_table;
+
+/* bytes of one row, and of its position-free part, in a row format */
+static inline uint32_t irm_row_bytes(uint32_t row_format) { return row_format == IRM_ROW_FP8 ? 656u : 1152u; }
+static inline uint32_t irm_ckv_bytes(uint32_t row_format) { return row_format == IRM_ROW_FP8 ? 528u : 1024u; }
 
 /* Chunks a batch can produce at most, given per-request lengths n_r:
  * sum over r of (n_r / min_chunk + 1).  A safe bound from totals only. */
@@ -225,10 +239,11 @@ irm_status irm_lookup(irm_ctx *ctx, const irm_table *table, const uint64_t *d_ch
  *   dst[l][ ... ][512 + i], [512 + 32 + i]     = the pair (k_i, k_{i+32}) turned by
  *                                                delta * inv_freq[i], i < 32
  * with the angle reduced in fp64, the rotation in fp32 and one
- * round-to-nearest-even to bf16.
+ * round-to-nearest-even to bf16.  (Element indices of IRM_ROW_BF16 rows; in IRM_ROW_FP8
+ * rows the first 528 bytes are the bit copy and the 64 bf16 of k_r follow them.)
  *   d_src_layer_ptrs / d_dst_layer_ptrs  device arrays of n_layers device pointers
  *                                        to row 0 of each layer (16-byte aligned)
- *   *_row_stride_bytes                   >= 1152, multiple of 16
+ *   *_row_stride_bytes                   >= irm_row_bytes(row_format), multiple of 16
  *   src_rows / dst_rows                  rows per layer (bounds; rows outside are skipped
  *                                        and raise IRM_FLAG_ROW_RANGE)
  *   d_dst_slots                          int32[n_slots_tokens]: destination row per batch token
@@ -249,8 +264,8 @@ irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
  *   d_ckv_index[slot]          = src_row + j   (the pool row whose c_KV the token uses)
  *   kr[l][slot][0:64]          = the k_r of source row src_row + j of layer l, rotated by delta
  *   d_src_kr_layer_ptrs        device array of n_layers pointers to the k_r slice (64 bf16) of
- *                              source row 0: base + 1024 for packed 576-wide rows, or the base
- *                              of a dense k_r_base pool
+ *                              source row 0: base + irm_ckv_bytes(row_format) for packed
+ *                              rows, or the base of a dense k_r_base pool
  *   src_kr_row_stride_bytes    >= 128, multiple of 16 (1152 for packed rows, 128 for a dense pool)
  *   d_kr_layer_ptrs            device array of n_layers pointers to [kr_rows][64] bf16
  *   kr_row_stride_bytes        >= 128, multiple of 16
@@ -302,7 +317,7 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]
  * A request without context gives out = 0, lse = -inf.  A slot, row or hit index out of
  * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing, does not
- * synchronise. */
+ * synchronise.  IRM_ROW_BF16 contexts only (IRM_ERR_UNSUPPORTED otherwise). */
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
 irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
                           const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,

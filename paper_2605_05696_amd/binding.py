@@ -20,6 +20,7 @@ STATUS_NAMES = {0: "IRM_OK", 1: "IRM_ERR_INVALID_ARG", 2: "IRM_ERR_CAPACITY", 3:
                 4: "IRM_ERR_DEVICE", 5: "IRM_ERR_TABLE_FULL"}
 IRM_FLAG_CHUNK_OVERFLOW, IRM_FLAG_TABLE_FULL, IRM_FLAG_ROW_RANGE, IRM_FLAG_BAD_CHUNK = 1, 2, 4, 8
 IRM_FLAG_WAIT_TIMEOUT = 16
+IRM_ROW_BF16, IRM_ROW_FP8 = 0, 1
 
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
@@ -38,7 +39,8 @@ class irm_config(ctypes.Structure):
                 ("min_chunk", ctypes.c_uint32), ("max_chunk", ctypes.c_uint32),
                 ("carve_out", ctypes.c_uint32), ("n_layers", ctypes.c_uint32),
                 ("ckv_dim", ctypes.c_uint32), ("kr_dim", ctypes.c_uint32),
-                ("pair_mode", ctypes.c_uint32), ("inv_freq", ctypes.c_float * 32),
+                ("pair_mode", ctypes.c_uint32), ("row_format", ctypes.c_uint32),
+                ("inv_freq", ctypes.c_float * 32),
                 ("max_tokens", ctypes.c_uint64), ("max_requests", ctypes.c_uint32)]
 
 
@@ -111,7 +113,7 @@ def _stream(stream):
 
 
 def make_config(gear, mask, min_chunk, max_chunk, carve_out, n_layers, inv_freq, max_tokens,
-                max_requests, ckv_dim=512, kr_dim=64, pair_mode=0) -> irm_config:
+                max_requests, ckv_dim=512, kr_dim=64, pair_mode=0, row_format=0) -> irm_config:
     cfg = irm_config()
     gear = np.ascontiguousarray(gear, np.uint32)
     inv_freq = np.ascontiguousarray(inv_freq, np.float32)
@@ -120,7 +122,7 @@ def make_config(gear, mask, min_chunk, max_chunk, carve_out, n_layers, inv_freq,
     cfg.inv_freq[:] = inv_freq.tolist()
     cfg.mask, cfg.min_chunk, cfg.max_chunk, cfg.carve_out = mask, min_chunk, max_chunk, carve_out
     cfg.n_layers, cfg.ckv_dim, cfg.kr_dim, cfg.pair_mode = n_layers, ckv_dim, kr_dim, pair_mode
-    cfg.max_tokens, cfg.max_requests = max_tokens, max_requests
+    cfg.max_tokens, cfg.max_requests, cfg.row_format = max_tokens, max_requests, row_format
     return cfg
 
 
@@ -272,12 +274,17 @@ def irm_lookup(ctx, table, d_chunk_hash, d_chunk_start, d_chunk_len, d_req_chunk
         _dev(d_hit_tokens, i64, "d_hit_tokens"), _stream(stream)))
 
 
+ROW_WORDS = {IRM_ROW_BF16: 576, IRM_ROW_FP8: 328}      # 16-bit words per row
+
+
 def layer_pointers(pool):
-    """Device array of per-layer base pointers of a [L, rows, 576] bf16 pool tensor."""
+    """Device array of per-layer base pointers of a pool tensor [L, rows, W] of 16-bit words
+    (dtype bf16): W = 576 for bf16 rows, 328 for fp8 rows (whose first 264 words are bytes and
+    scales, not bf16 values)."""
     import torch
-    if pool.dim() != 3 or pool.shape[2] != 576 or pool.dtype != torch.bfloat16 or not pool.is_cuda:
-        raise TypeError("pool: need a [L, rows, 576] bf16 device tensor")
-    if pool.stride(2) != 1 or pool.stride(1) < 576:
+    if pool.dim() != 3 or pool.shape[2] not in (576, 328) or pool.dtype != torch.bfloat16 or not pool.is_cuda:
+        raise TypeError("pool: need a [L, rows, 576 or 328] bf16 device tensor")
+    if pool.stride(2) != 1 or pool.stride(1) < pool.shape[2]:
         raise TypeError("pool: rows must be dense")
     ptrs = [pool.data_ptr() + l * pool.stride(0) * 2 for l in range(pool.shape[0])]
     return torch.tensor(ptrs, dtype=torch.int64, device=pool.device)
@@ -299,8 +306,8 @@ def irm_reattach(ctx, d_src_layer_ptrs, src_row_stride_bytes, src_rows, d_dst_la
 
 
 def kr_slice_pointers(pool):
-    """Per-layer pointers to the k_r slice of row 0 of a packed [L, rows, 576] bf16 pool."""
-    return layer_pointers(pool) + 1024
+    """Per-layer pointers to the k_r slice of row 0 of a packed pool (see layer_pointers)."""
+    return layer_pointers(pool) + (pool.shape[2] - 64) * 2
 
 
 def kr_layer_pointers(pool):

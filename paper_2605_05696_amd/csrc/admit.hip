@@ -129,6 +129,8 @@ __global__ __launch_bounds__(256) void admit_claim(
     }
 }
 
+// VPR: 16-byte vectors per row (72 for bf16 rows, 41 for fp8 rows)
+template <uint32_t VPR>
 __global__ __launch_bounds__(256) void admit_rows(const void *const *__restrict__ req_ptrs, uint64_t req_stride,
                                                   uint64_t req_rows, void *const *__restrict__ pool_ptrs,
                                                   uint64_t pool_stride, const int32_t *__restrict__ slots,
@@ -156,9 +158,9 @@ __global__ __launch_bounds__(256) void admit_rows(const void *const *__restrict_
         __syncthreads();
         const char *sbase = (const char *)req_ptrs[layer];
         char *dbase = (char *)pool_ptrs[layer] + (uint64_t)row0 * pool_stride;
-        // 72 vectors per row; a row's vectors are consecutive work items
-        for (uint32_t i = threadIdx.x; i < n_rows * 72u; i += blockDim.x) {
-            const uint32_t r = i / 72u, col = i - r * 72u;
+        // a row's vectors are consecutive work items
+        for (uint32_t i = threadIdx.x; i < n_rows * VPR; i += blockDim.x) {
+            const uint32_t r = i / VPR, col = i - r * VPR;
             const int32_t sl = slot_s[r];
             if (sl < 0) continue;
             const u32x4 v = __builtin_nontemporal_load((const u32x4 *)(sbase + (uint64_t)(uint32_t)sl * req_stride) + col);
@@ -182,7 +184,8 @@ extern "C" irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *
         !d_pool_layer_ptrs || !d_cursor || !d_admitted_row)
         return IRM_ERR_INVALID_ARG;
     if (table->ctx != ctx || n_req < 1 || chunk_capacity < 1 || n_slot_tokens < 1) return IRM_ERR_INVALID_ARG;
-    if (req_row_stride_bytes < IRM_ROW_BYTES || pool_row_stride_bytes < IRM_ROW_BYTES ||
+    const uint32_t row_bytes = irm_row_bytes(ctx->cfg.row_format);
+    if (req_row_stride_bytes < row_bytes || pool_row_stride_bytes < row_bytes ||
         (req_row_stride_bytes & 15) || (pool_row_stride_bytes & 15))
         return IRM_ERR_INVALID_ARG;
     if (req_rows < 1 || pool_rows < 1 || req_rows > 0x7FFFFFFFull || pool_rows > 0x7FFFFFFFull)
@@ -199,7 +202,8 @@ extern "C" irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *
                        ctx->d_err);
     uint64_t tile_slots = n_slot_tokens / ADMIT_TILE_ROWS + chunk_capacity;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
-    hipLaunchKernelGGL(admit_rows, dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
+    hipLaunchKernelGGL(ctx->cfg.row_format == IRM_ROW_FP8 ? admit_rows<IRM_F8_ROW_BYTES / 16> : admit_rows<IRM_ROW_BYTES / 16>,
+                       dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
                        d_req_layer_ptrs, req_row_stride_bytes, req_rows, d_pool_layer_ptrs,
                        pool_row_stride_bytes, d_slots, ctx->d_tiles, ctx->d_plan, ctx->d_err);
     return irm_launch_status();

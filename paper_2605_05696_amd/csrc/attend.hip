@@ -574,6 +574,7 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     if (n_req < 1 || n_heads < ATT_HEADS || n_heads % ATT_HEADS || n_heads > 128 || n_splits < 1 ||
         n_splits > 1024 || n_req > 65535)
         return IRM_ERR_INVALID_ARG;
+    if (ctx && ctx->cfg.row_format != IRM_ROW_BF16) return IRM_ERR_UNSUPPORTED;   // bf16 products over bf16 rows
     if (pool_row_stride_bytes < IRM_ROW_BYTES || (pool_row_stride_bytes & 15) || ((uintptr_t)d_pool_layer & 15) ||
         ((uintptr_t)d_q & 15) || ((uintptr_t)d_trig & 15) || pool_rows < 1 || pool_rows > 0x7FFFFFFFull ||
         dst_rows < 1 || trig_hits < 1 || !(scale > 0.0f))

@@ -11,7 +11,8 @@ static inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a
 extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
 {
     if (!cfg || !out) return IRM_ERR_INVALID_ARG;
-    if (cfg->ckv_dim != 512 || cfg->kr_dim != 64 || cfg->pair_mode > IRM_PAIR_INTERLEAVED)
+    if (cfg->ckv_dim != 512 || cfg->kr_dim != 64 || cfg->pair_mode > IRM_PAIR_INTERLEAVED ||
+        cfg->row_format > IRM_ROW_FP8)
         return IRM_ERR_UNSUPPORTED;
     const uint64_t m = cfg->mask;
     if ((m & (m + 1)) != 0) return IRM_ERR_UNSUPPORTED;        // mask must be 2^k - 1
@@ -34,7 +35,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     c->k_bits = k_bits;
     c->chunk_cap = (uint32_t)chunk_cap64;
     c->tile_cap = (uint32_t)(cfg->max_tokens / IRM_TILE_ROWS_MIN + chunk_cap64);
-    c->rows_per_wave = 2;
+    c->rows_per_wave = cfg->row_format == IRM_ROW_FP8 ? 4 : 2;    // about 2 KB per wave in flight either way
     c->block_waves = 8;
     c->mem_mode = 3;
     c->xcd_ranges = 1;
@@ -127,6 +128,7 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
     if (knob == 1) {
         if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return IRM_ERR_INVALID_ARG;
         if (value * ctx->block_waves < IRM_TILE_ROWS_MIN) return IRM_ERR_INVALID_ARG;
+        if (ctx->cfg.row_format == IRM_ROW_FP8 && value == 1) return IRM_ERR_INVALID_ARG;   // two rows per load
         ctx->rows_per_wave = value;
         return IRM_OK;
     }
@@ -138,6 +140,7 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
     if (knob == 4) {
         if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return IRM_ERR_INVALID_ARG;
         if (value * ctx->rows_per_wave < IRM_TILE_ROWS_MIN) return IRM_ERR_INVALID_ARG;
+        if (ctx->cfg.row_format == IRM_ROW_FP8 && value < 4) return IRM_ERR_INVALID_ARG;
         ctx->block_waves = value;
         return IRM_OK;
     }

@@ -6,8 +6,10 @@
 
 #include "irm.h"
 
-#define IRM_ROW_BYTES 1152u     // 576 bf16
-#define IRM_CKV_BYTES 1024u     // 512 bf16
+#define IRM_ROW_BYTES 1152u     // bf16 rows: 576 bf16
+#define IRM_CKV_BYTES 1024u     // bf16 rows: 512 bf16
+#define IRM_F8_ROW_BYTES 656u   // fp8 rows: 512 e4m3 | 4 fp32 scales | 64 bf16
+#define IRM_F8_CKV_BYTES 528u   // their position-free part; the scales are its last 16 bytes
 #define IRM_KR_BYTES 128u       // 64 bf16
 #define IRM_TILE_ROWS_MIN 4u    // smallest tile of the re-attach row kernel (sizes the tile list)
 #define IRM_WAVE 64

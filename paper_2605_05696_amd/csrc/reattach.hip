@@ -199,31 +199,39 @@ __device__ __forceinline__ void st16(u32x4 v, u32x4 *p)
 // One tile: up to WAVES * RPW rows.  Wave w moves the c_KV of rows [w*RPW, (w+1)*RPW)
 // and rotates the k_r of rows [16w, 16w+16) (four lanes per row).  slot[q] holds the
 // destination row of tile row 64q + lane (-1: absent or unusable).
-template <int WAVES, int RPW, bool FULL, bool NT_LD, bool NT_ST>
+// F8 rows (512 e4m3 bytes | 16 bytes of scales | k_r): the quantised c_KV is 32 vectors, so
+// half a wave takes a row and one load covers two rows; the scales travel with the k_r
+// lanes, which sit right behind them.
+template <int WAVES, int RPW, bool FULL, bool NT_LD, bool NT_ST, bool F8>
 __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, uint64_t src_stride,
                                               char *__restrict__ dbase, uint64_t dst_stride,
                                               const int32_t (&slot)[(WAVES * RPW + 63) / 64],
                                               uint32_t n_rows, const float2 *__restrict__ trig_hit,
                                               uint32_t wave, uint32_t lane, bool il)
 {
+    static_assert(!F8 || RPW % 2 == 0, "fp8 rows are moved two at a time");
     constexpr int TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
+    constexpr int NLD = F8 ? RPW / 2 : RPW;             // c_KV loads per lane
+    constexpr uint32_t CKV = F8 ? IRM_F8_CKV_BYTES : IRM_CKV_BYTES;
     const uint32_t row0 = wave * RPW;
+    const uint32_t sub = F8 ? lane >> 5 : 0u, vec = F8 ? lane & 31u : lane;
     // c_KV: issue every load of this wave's rows before the first store
-    u32x4 v[RPW];
+    u32x4 v[NLD];
 #pragma unroll
-    for (int i = 0; i < RPW; ++i) {
-        const uint32_t r = row0 + i;
-        if (FULL || r < n_rows) v[i] = ld16<NT_LD>((const u32x4 *)(sbase + (uint64_t)r * src_stride) + lane);
+    for (int i = 0; i < NLD; ++i) {
+        const uint32_t r = F8 ? row0 + 2 * i + sub : row0 + i;
+        if (FULL || r < n_rows) v[i] = ld16<NT_LD>((const u32x4 *)(sbase + (uint64_t)r * src_stride) + vec);
     }
     // k_r: lane (rr, j) owns pairs 8j .. 8j+7 of row rr
     const uint32_t rr = wave * 16 + (lane >> 2), j = lane & 3;
     const bool kr_on = rr < n_rows;                   // n_rows <= TILE
-    u32x4 ka = {0, 0, 0, 0}, kb = {0, 0, 0, 0};
+    u32x4 ka = {0, 0, 0, 0}, kb = {0, 0, 0, 0}, scales = {0, 0, 0, 0};
     f32x4 t0 = {1, 0, 1, 0}, t1 = t0, t2 = t0, t3 = t0;
     if (kr_on) {
-        const u32x4 *kr = (const u32x4 *)(sbase + (uint64_t)rr * src_stride + IRM_CKV_BYTES);
+        const u32x4 *kr = (const u32x4 *)(sbase + (uint64_t)rr * src_stride + CKV);
         ka = ld16<NT_LD>(kr + j);
         kb = ld16<NT_LD>(kr + 4 + j);
+        if (F8 && j == 0) scales = ld16<NT_LD>(kr - 1);
         const f32x4 *tp = (const f32x4 *)(trig_hit + 8 * j);
         t0 = tp[0];
         t1 = tp[1];
@@ -238,14 +246,29 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
         if ((wave >> 2) == (uint32_t)q) kr_slot = cand;
     }
 #pragma unroll
-    for (int i = 0; i < RPW; ++i) {
-        const uint32_t r = row0 + i;
-        if (FULL || r < n_rows) {
-            int32_t s = -1;
+    for (int i = 0; i < NLD; ++i) {
+        if (F8) {
+            // rows r and r + 1 (r even) lie in the same slot word
+            const uint32_t r = row0 + 2 * i;
+            int32_t s0 = -1, s1 = -1;
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
-                if ((r >> 6) == (uint32_t)q) s = __builtin_amdgcn_readlane(slot[q], (int)(r & 63));
-            if (s >= 0) st16<NT_ST>(v[i], (u32x4 *)(dbase + (uint64_t)(uint32_t)s * dst_stride) + lane);
+                if ((r >> 6) == (uint32_t)q) {
+                    s0 = __builtin_amdgcn_readlane(slot[q], (int)(r & 63));
+                    s1 = __builtin_amdgcn_readlane(slot[q], (int)((r & 63) + 1));
+                }
+            const int32_t sl = sub ? s1 : s0;
+            if ((FULL || r + sub < n_rows) && sl >= 0)
+                st16<NT_ST>(v[i], (u32x4 *)(dbase + (uint64_t)(uint32_t)sl * dst_stride) + vec);
+        } else {
+            const uint32_t r = row0 + i;
+            if (FULL || r < n_rows) {
+                int32_t sl = -1;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+                    if ((r >> 6) == (uint32_t)q) sl = __builtin_amdgcn_readlane(slot[q], (int)(r & 63));
+                if (sl >= 0) st16<NT_ST>(v[i], (u32x4 *)(dbase + (uint64_t)(uint32_t)sl * dst_stride) + vec);
+            }
         }
     }
     if (kr_on && kr_slot >= 0) {
@@ -268,9 +291,10 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
             pair_regroup(a3, b3);
         }
         const u32x4 oa = {a0, a1, a2, a3}, ob = {b0, b1, b2, b3};
-        u32x4 *out = (u32x4 *)(dbase + (uint64_t)(uint32_t)kr_slot * dst_stride + IRM_CKV_BYTES);
+        u32x4 *out = (u32x4 *)(dbase + (uint64_t)(uint32_t)kr_slot * dst_stride + CKV);
         st16<NT_ST>(oa, out + j);
         st16<NT_ST>(ob, out + 4 + j);
+        if (F8 && j == 0) st16<NT_ST>(scales, out - 1);
     }
 }
 
@@ -279,7 +303,7 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
 // dispatcher deals workgroups round-robin to the 8 XCDs, so with `xcd_ranges` workgroup
 // x serves tile (x % 8) * ceil(n_tiles / 8) + x / 8: each XCD streams one contiguous
 // eighth of the layer's tile list.  Workgroups past the last tile leave at once.
-template <int WAVES, int RPW, bool NT_LD, bool NT_ST>
+template <int WAVES, int RPW, bool NT_LD, bool NT_ST, bool F8>
 __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ dst_ptrs,
     uint64_t dst_stride, uint64_t dst_rows, const int32_t *__restrict__ dst_slots,
@@ -317,11 +341,11 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
         }
         const float2 *trig_hit = trig + (uint64_t)hit * IRM_KR_PAIRS;
         if (n_rows == TILE)
-            reattach_tile<WAVES, RPW, true, NT_LD, NT_ST>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
-                                                          trig_hit, wave, lane, il);
+            reattach_tile<WAVES, RPW, true, NT_LD, NT_ST, F8>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
+                                                              trig_hit, wave, lane, il);
         else
-            reattach_tile<WAVES, RPW, false, NT_LD, NT_ST>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
-                                                           trig_hit, wave, lane, il);
+            reattach_tile<WAVES, RPW, false, NT_LD, NT_ST, F8>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
+                                                               trig_hit, wave, lane, il);
     }
 }
 
@@ -329,14 +353,14 @@ typedef void (*rows_kernel_t)(const void *const *, uint64_t, void *const *, uint
                               const int32_t *, const irm_tile *, const uint32_t *, const float2 *, uint32_t,
                               uint32_t, uint32_t *);
 
-template <int WAVES, int RPW>
+template <int WAVES, int RPW, bool F8>
 static rows_kernel_t pick_mode(uint32_t mode)
 {
     switch (mode & 3u) {
-    case 0: return reattach_rows<WAVES, RPW, false, false>;
-    case 1: return reattach_rows<WAVES, RPW, true, false>;
-    case 2: return reattach_rows<WAVES, RPW, false, true>;
-    default: return reattach_rows<WAVES, RPW, true, true>;
+    case 0: return reattach_rows<WAVES, RPW, false, false, F8>;
+    case 1: return reattach_rows<WAVES, RPW, true, false, F8>;
+    case 2: return reattach_rows<WAVES, RPW, false, true, F8>;
+    default: return reattach_rows<WAVES, RPW, true, true, F8>;
     }
 }
 
@@ -344,16 +368,35 @@ template <int WAVES>
 static rows_kernel_t pick_rpw(uint32_t rpw, uint32_t mode)
 {
     switch (rpw) {
-    case 1: return pick_mode<WAVES, 1>(mode);
-    case 2: return pick_mode<WAVES, 2>(mode);
-    case 4: return pick_mode<WAVES, 4>(mode);
-    case 8: return pick_mode<WAVES, 8>(mode);
-    default: return pick_mode<WAVES, 16>(mode);
+    case 1: return pick_mode<WAVES, 1, false>(mode);
+    case 2: return pick_mode<WAVES, 2, false>(mode);
+    case 4: return pick_mode<WAVES, 4, false>(mode);
+    case 8: return pick_mode<WAVES, 8, false>(mode);
+    default: return pick_mode<WAVES, 16, false>(mode);
     }
 }
 
-static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode)
+// fp8 rows: an even number of rows per wave, 4 waves or more (irm_ctx_tune admits no others)
+template <int WAVES>
+static rows_kernel_t pick_rpw_f8(uint32_t rpw, uint32_t mode)
 {
+    switch (rpw) {
+    case 2: return pick_mode<WAVES, 2, true>(mode);
+    case 4: return pick_mode<WAVES, 4, true>(mode);
+    case 8: return pick_mode<WAVES, 8, true>(mode);
+    default: return pick_mode<WAVES, 16, true>(mode);
+    }
+}
+
+static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode, uint32_t row_format)
+{
+    if (row_format == IRM_ROW_FP8) {
+        switch (waves) {
+        case 4: return pick_rpw_f8<4>(rpw, mode);
+        case 8: return pick_rpw_f8<8>(rpw, mode);
+        default: return pick_rpw_f8<16>(rpw, mode);
+        }
+    }
     switch (waves) {
     case 1: return pick_rpw<1>(rpw, mode);
     case 2: return pick_rpw<2>(rpw, mode);
@@ -533,7 +576,8 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
 {
     if (!ctx || !d_src_layer_ptrs || !d_dst_layer_ptrs || !d_dst_slots || !d_hits || !d_n_hits)
         return IRM_ERR_INVALID_ARG;
-    if (src_row_stride_bytes < IRM_ROW_BYTES || dst_row_stride_bytes < IRM_ROW_BYTES ||
+    const uint32_t row_bytes = irm_row_bytes(ctx->cfg.row_format);
+    if (src_row_stride_bytes < row_bytes || dst_row_stride_bytes < row_bytes ||
         (src_row_stride_bytes & 15) || (dst_row_stride_bytes & 15))
         return IRM_ERR_INVALID_ARG;
     if (src_rows < 1 || dst_rows < 1 || src_rows > 0xFFFFFFFFull || dst_rows > 0x7FFFFFFFull ||
@@ -557,7 +601,7 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode),
+    hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode, ctx->cfg.row_format),
                        dim3(grid_x, ctx->cfg.n_layers), dim3(ctx->block_waves * 64), 0, s,
                        d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
                        d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->xcd_ranges, ctx->cfg.pair_mode,

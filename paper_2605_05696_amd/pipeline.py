@@ -23,21 +23,21 @@ class Session:
     """One context (+ optional registry) on the current device."""
 
     def __init__(self, gear, mask, min_chunk, max_chunk, carve_out, n_layers, inv_freq,
-                 max_tokens, max_requests, device="cuda:0", pair_mode=0):
+                 max_tokens, max_requests, device="cuda:0", pair_mode=0, row_format=0):
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.cfg = B.make_config(gear, mask, min_chunk, max_chunk, carve_out, n_layers, inv_freq,
-                                 max_tokens, max_requests, pair_mode=pair_mode)
+                                 max_tokens, max_requests, pair_mode=pair_mode, row_format=row_format)
         self.min_chunk = min_chunk
         self.n_layers = n_layers
         self.ctx = B.irm_ctx_create(self.cfg)
         self.table = None
 
     @classmethod
-    def for_workload(cls, w, device="cuda:0", max_tokens=None, max_requests=None, pair_mode=0):
+    def for_workload(cls, w, device="cuda:0", max_tokens=None, max_requests=None, pair_mode=0, row_format=0):
         n_max = max(len(w.tokens), len(w.pool_tokens), 1)
         return cls(w.gear, w.mask, w.min_chunk, w.max_chunk, w.carve_out, w.n_layers, w.inv_freq,
-                   max_tokens or n_max, max_requests or max(w.n_req, 1), device, pair_mode)
+                   max_tokens or n_max, max_requests or max(w.n_req, 1), device, pair_mode, row_format)
 
     def close(self):
         if self.table is not None:

@@ -411,8 +411,27 @@ def kv_pool_torch(n_layers: int, rows: int, seed: int, device="cpu", layers_per_
     return out
 
 
-def sentinel_pool_torch(n_layers: int, rows: int, device="cpu"):
+def kv_pool_fp8_torch(n_layers: int, rows: int, seed: int, device="cpu", layers_per_step: int = 1):
+    """fp8 rows as [n_layers][rows][328] 16-bit words (typed bf16 like the other pools): 512 uniformly
+    random bytes standing for e4m3 codes, four fp32 block scales in [1e-3, 4), then k_r as 64 bf16
+    ~ N(0,1).  The library moves the first 528 bytes bit for bit, so any byte values serve."""
     import torch
-    out = torch.empty((n_layers, rows, 576), dtype=torch.int16, device=device)
+    out = torch.empty((n_layers, rows, 328), dtype=torch.int16, device=device)
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    for l0 in range(0, n_layers, layers_per_step):
+        l1 = min(n_layers, l0 + layers_per_step)
+        codes = torch.randint(0, 65536, (l1 - l0, rows, 256), generator=g, device=device, dtype=torch.int32)
+        out[l0:l1, :, :256] = (codes - 32768).to(torch.int16)
+        scales = torch.empty((l1 - l0, rows, 4), dtype=torch.float32, device=device).uniform_(1e-3, 4.0, generator=g)
+        out[l0:l1, :, 256:264] = scales.view(torch.int16)
+        kr = torch.empty((l1 - l0, rows, 64), dtype=torch.bfloat16, device=device).normal_(0.0, 1.0, generator=g)
+        out[l0:l1, :, 264:] = kr.view(torch.int16)
+    return out.view(torch.bfloat16)
+
+
+def sentinel_pool_torch(n_layers: int, rows: int, device="cpu", row_words: int = 576):
+    import torch
+    out = torch.empty((n_layers, rows, row_words), dtype=torch.int16, device=device)
     out.fill_(SENTINEL_BF16 - 0x10000 if SENTINEL_BF16 >= 0x8000 else SENTINEL_BF16)
     return out.view(torch.bfloat16)

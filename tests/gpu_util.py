@@ -57,12 +57,14 @@ def ordered(b: np.ndarray) -> np.ndarray:
 
 
 def compare_rows(got: np.ndarray, want: np.ndarray, what=""):
-    """got/want: [..., 576] uint16.  c_KV bit-exact; k_r within 2 bf16 steps of the
-    oracle's fp64-rounded value, or within 1e-2 absolute."""
-    assert got.shape == want.shape
-    ckv_bad = np.nonzero(got[..., :512] != want[..., :512])
+    """got/want: [..., 576 or 328] uint16.  The position-free part (c_KV, for fp8 rows with its
+    scales) bit-exact; k_r within 2 bf16 steps of the oracle's fp64-rounded value, or within 1e-2
+    absolute."""
+    assert got.shape == want.shape and got.shape[-1] in (576, 328)
+    ckv = got.shape[-1] - 64
+    ckv_bad = np.nonzero(got[..., :ckv] != want[..., :ckv])
     assert len(ckv_bad[0]) == 0, f"{what}: c_KV differs at {[a[:5] for a in ckv_bad]}"
-    g, o = got[..., 512:], want[..., 512:]
+    g, o = got[..., ckv:], want[..., ckv:]
     step = np.abs(ordered(g) - ordered(o))
     far = step > 2
     if far.any():
@@ -110,10 +112,11 @@ def covered_rows(w, hits: orc.Hits) -> np.ndarray:
 class Rig:
     """A workload on the device: session, token arrays, pools, table."""
 
-    def __init__(self, w, o=None, with_pools=True, with_table=True, pair_mode=0):
+    def __init__(self, w, o=None, with_pools=True, with_table=True, pair_mode=0, row_format=0):
         self.w = w
         self.o = o if o is not None else oracle_front(w)
-        self.s = Session.for_workload(w, DEV, pair_mode=pair_mode)
+        self.s = Session.for_workload(w, DEV, pair_mode=pair_mode, row_format=row_format)
+        self.row_bytes = B.ROW_WORDS[row_format] * 2
         self.d_tokens = torch.from_numpy(w.tokens).to(DEV)
         self.d_req_offsets = self.s.to_dev_u32(w.req_offsets)
         self.d_pos_base = torch.from_numpy(w.pos_base).to(DEV)
@@ -123,18 +126,19 @@ class Rig:
             self.s.build_table(w.table_slots, self.o["reg"])
         if with_pools:
             name = w.name.split("-")[0]
-            self.src = wl.kv_pool_torch(w.n_layers, w.src_rows, wl.kv_seed(name), DEV)
-            self.dst = wl.sentinel_pool_torch(w.n_layers, w.dst_rows, DEV)
+            make = wl.kv_pool_fp8_torch if row_format == B.IRM_ROW_FP8 else wl.kv_pool_torch
+            self.src = make(w.n_layers, w.src_rows, wl.kv_seed(name), DEV)
+            self.dst = wl.sentinel_pool_torch(w.n_layers, w.dst_rows, DEV, B.ROW_WORDS[row_format])
             self.src_ptrs = B.layer_pointers(self.src)
             self.dst_ptrs = B.layer_pointers(self.dst)
 
     def reattach(self, d_hits, d_n_hits):
-        B.irm_reattach(self.s.ctx, self.src_ptrs, ROW * 2, self.w.src_rows, self.dst_ptrs, ROW * 2,
+        B.irm_reattach(self.s.ctx, self.src_ptrs, self.row_bytes, self.w.src_rows, self.dst_ptrs, self.row_bytes,
                        self.w.dst_rows, self.d_dst_slots, d_hits, d_n_hits)
 
     def serve(self):
         self.s.serve(self.d_tokens, self.d_req_offsets, self.d_pos_base, self.d_dst_slots, self.src_ptrs,
-                     ROW * 2, self.w.src_rows, self.dst_ptrs, ROW * 2, self.w.dst_rows, self.buf)
+                     self.row_bytes, self.w.src_rows, self.dst_ptrs, self.row_bytes, self.w.dst_rows, self.buf)
 
     def close(self):
         self.s.close()

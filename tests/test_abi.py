@@ -28,9 +28,25 @@ def test_every_declared_symbol_is_exported():
     assert sorted(B.SYMBOLS) == names
 
 
-def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(B.irm_config) == 256 * 4 + 8 * 4 + 32 * 4 + 8 + 8   # max_requests padded to 8
-    assert B.ENTRY_DTYPE.itemsize == 16 and B.HIT_DTYPE.itemsize == 16
+def test_struct_layouts_match_the_header(tmp_path):
+    """Sizes and field offsets as the C compiler lays the header's structs out, against the binding's."""
+    import subprocess
+    fields = [f[0] for f in B.irm_config._fields_]
+    prog = ['#include <stdio.h>', '#include <stddef.h>', '#include "irm.h"', 'int main(void) {',
+            '  printf("%zu %zu %zu\\n", sizeof(irm_config), sizeof(irm_entry), sizeof(irm_hit));']
+    prog += [f'  printf("%zu\\n", offsetof(irm_config, {f}));' for f in fields]
+    prog += ['  return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(prog))
+    exe = tmp_path / "layout"
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe)], check=True)
+    lines = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    sizes = [int(x) for x in lines[0].split()]
+    assert sizes == [ctypes.sizeof(B.irm_config), B.ENTRY_DTYPE.itemsize, B.HIT_DTYPE.itemsize]
+    assert sizes[1:] == [16, 16]
+    for f, line in zip(fields, lines[1:]):
+        assert getattr(B.irm_config, f).offset == int(line), f
 
 
 def good_config(**over):
