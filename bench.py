@@ -26,9 +26,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-ROW_BYTES = 1152
+ROW_BYTES = 1152                                     # bf16 rows; main() takes the format's own size
 HBM_PEAK_GBS = 8000.0
-PROFILE_TRAFFIC = os.path.join(ROOT, "profiles", "reattach_rows_c1_traffic.json")
+PROFILE_TRAFFIC = {"bf16": os.path.join(ROOT, "profiles", "reattach_rows_c1_traffic.json"),
+                   "fp8": os.path.join(ROOT, "profiles", "reattach_rows_fp8_c1_traffic.json")}
 
 
 def main() -> int:
@@ -47,6 +48,10 @@ def main() -> int:
                          "the packed 576-wide source rows; kr-dense = the same from a dense k_r_base pool; ref = "
                          "no-materialise variant, only row references and the per-hit rotation table are written "
                          "(8 B per token, once, not per layer)")
+    ap.add_argument("--rows", default="bf16", choices=["bf16", "fp8"],
+                    help="row format of the pools: bf16 = 1152-byte rows (the headline); fp8 = 656-byte rows, c_KV "
+                         "as 512 e4m3 bytes and four fp32 scales moved bit for bit, k_r in bf16 rotated as usual "
+                         "(hit stage with --reattach full or kr, admit stage)")
     ap.add_argument("--heads", type=int, default=16, help="attend stage: query heads (multiple of 16)")
     ap.add_argument("--linear-rows", action="store_true",
                     help="attend stage: every slot refers to the pool row of the same number (no rotation), i.e. "
@@ -118,14 +123,20 @@ def main() -> int:
     front.close()
 
     L = w0.n_layers
-    src = wl.kv_pool_torch(L, w0.src_rows, wl.kv_seed(name), dev)
+    fp8 = args.rows == "fp8"
+    row_format = B.IRM_ROW_FP8 if fp8 else B.IRM_ROW_BF16
+    ROW_BYTES = B.ROW_WORDS[row_format] * 2
+    if fp8:
+        assert args.stage in ("hit", "admit") and args.reattach in ("full", "kr"), \
+            "--rows fp8: hit stage with --reattach full or kr, or the admit stage"
+    src = (wl.kv_pool_fp8_torch if fp8 else wl.kv_pool_torch)(L, w0.src_rows, wl.kv_seed(name), dev)
     src_ptrs = B.layer_pointers(src)
     n_streams = max(1, args.streams)
     if n_streams > 1:
         assert args.reattach == "full" and args.stage != "admit" and n_var % n_streams == 0, \
             "--streams needs --reattach full, the hit or s1 stage, and --variants divisible by it"
     if args.reattach == "full":
-        dsts = [wl.sentinel_pool_torch(L, w0.dst_rows, dev) for _ in range(n_streams)]
+        dsts = [wl.sentinel_pool_torch(L, w0.dst_rows, dev, ROW_BYTES // 2) for _ in range(n_streams)]
         dst_ptrs_of = [B.layer_pointers(d) for d in dsts]
         dst, dst_ptrs = dsts[0], dst_ptrs_of[0]
         bytes_per_token_layer = 2 * ROW_BYTES                        # one row read, one written
@@ -148,7 +159,7 @@ def main() -> int:
 
     sessions, dev_in = [], []
     for w in works:
-        s = Session.for_workload(w, dev)
+        s = Session.for_workload(w, dev, row_format=row_format)
         reg = w.registry(pool_hash)
         if s1:
             wreg = w.window_registry(pool_windows[0], pool_windows[1], pool_windows[2], pool_windows[3], len(reg["hash"]))
@@ -256,8 +267,8 @@ def main() -> int:
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
     traffic = None
     if (name == "c1" and args.size == "full" and args.reattach == "full" and args.stage == "hit"
-            and os.path.exists(PROFILE_TRAFFIC)):
-        traffic = json.load(open(PROFILE_TRAFFIC)).get("hbm_bytes_per_launch")
+            and args.slots == "contiguous" and os.path.exists(PROFILE_TRAFFIC[args.rows])):
+        traffic = json.load(open(PROFILE_TRAFFIC[args.rows])).get("hbm_bytes_per_launch")
 
     out = {
         "metric": "re-attached KV tokens/s (all layers), whole hot path, 1 MI355X",
@@ -265,7 +276,8 @@ def main() -> int:
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
-                               f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}",
+                               f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}"
+                               + (", fp8 rows (656 B: e4m3 c_KV + scales copied, bf16 k_r rotated)" if fp8 else ""),
                    "variants": n_var, "streams": n_streams, "hip_graph": bool(args.graph), "hit_tokens_per_step": float(np.mean(hit_tokens)),
                    "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s %s"
                              % ({"full": "", "ref": "_ref"}.get(args.reattach, "_kr"),
@@ -400,7 +412,9 @@ def bench_admit(args, works, sessions, dev_in, pool, stream):
 
     w0 = works[0]
     L, dev = w0.n_layers, pool.device
-    req = wl.kv_pool_torch(L, w0.dst_rows, 4242, dev)
+    fp8 = pool.shape[2] == 328
+    ROW_BYTES = pool.shape[2] * 2
+    req = (wl.kv_pool_fp8_torch if fp8 else wl.kv_pool_torch)(L, w0.dst_rows, 4242, dev)
     req_ptrs, pool_ptrs = B.layer_pointers(req), B.layer_pointers(pool)
     cursor = torch.zeros(1, dtype=torch.int32, device=dev)
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -442,7 +456,8 @@ def bench_admit(args, works, sessions, dev_in, pool, stream):
             "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": ms / args.steps, "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-            "config": {"workload": f"{w0.name}: every chunk past the carve-out admitted, {L} layers, slots {args.slots}",
+            "config": {"workload": f"{w0.name}: every chunk past the carve-out admitted, {L} layers, slots {args.slots}"
+                                   + (", fp8 rows (656 B)" if fp8 else ""),
                        "variants": len(works), "admitted_tokens_per_step": float(np.mean(admitted_tokens)),
                        "stages": "irm_admit (admit_claim + admit_rows), events on its stream; chunking, hashing, "
                                  "the lookup against the empty table and the table reset are outside the timed span",

@@ -310,3 +310,41 @@ def test_full_size_attend_ref_c2():
         assert np.abs(lse.cpu().numpy() - want_lse).max() < 6e-4
     finally:
         rig.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_full_size_fp8_rows(name):
+    """656-byte rows at the benchmark's sizes and launch shape: c1 every row, c2 a sample of hits; the
+    528 position-free bytes bit for bit on every re-attached row of two layers, untouched rows untouched."""
+    from paper_2605_05696_amd import binding as B
+    w = wl.make_workload(name, orc.cdc_chunk, size="full")
+    rig = Rig(w, row_format=B.IRM_ROW_FP8)
+    try:
+        rig.serve()
+        assert rig.s.error_flags() == 0
+        check_front(rig)
+        hits = rig.o["hits"]
+        L = w.n_layers
+        if name == "c1":
+            total = 0
+            for l0 in range(0, L, 9):
+                total += verify_reattach(w, hits, rig.src, rig.dst, layers=range(l0, min(L, l0 + 9)), what=w.name)["rows"]
+            assert total == rig.o["hit_tokens"] * L
+        else:
+            sel = np.sort(np.random.default_rng(41).choice(len(hits), size=256, replace=False))
+            stats = verify_reattach(w, hits, rig.src, rig.dst, hit_sel=sel, what=f"{w.name} sample")
+            assert stats["rows"] == int(hits.len[sel].sum()) * L
+        lens = hits.len.astype(np.int64)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        within = np.arange(off[-1]) - np.repeat(off[:-1], lens)
+        src_idx = torch.from_numpy(np.repeat(hits.src_row.astype(np.int64), lens) + within).to(DEV)
+        dst_idx = torch.from_numpy(w.dst_slots[np.repeat(hits.dst_tok.astype(np.int64), lens) + within].astype(np.int64)).to(DEV)
+        untouched = torch.from_numpy(np.nonzero(~covered_rows(w, hits))[0]).to(DEV)
+        for l in (0, L - 1):
+            for a in range(0, len(src_idx), 1 << 18):
+                s = rig.src[l].index_select(0, src_idx[a:a + (1 << 18)])
+                d = rig.dst[l].index_select(0, dst_idx[a:a + (1 << 18)])
+                assert torch.equal(s[:, :264].view(torch.int16), d[:, :264].view(torch.int16)), f"layer {l}"
+            assert torch.all(rig.dst[l].index_select(0, untouched).view(torch.int16) == wl.SENTINEL_BF16)
+    finally:
+        rig.close()
