@@ -308,6 +308,21 @@ def test_full_size_attend_ref_c2():
         # tile lost or doubled would move the lse by 4e-3 and the outputs by about as much
         assert err.max() < 2e-3 and err.mean() < 2e-4, (err.max(), err.mean())
         assert np.abs(lse.cpu().numpy() - want_lse).max() < 6e-4
+        # other splits of the same contexts (64 to 1024 workgroups in flight): the same result up to the
+        # order of the partial sums, and the same bits from one call to the next
+        lse4 = lse.clone()
+        for other in (1, 8, 16):
+            ws2 = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, H, other), dtype=torch.uint8, device=DEV)
+            outs = []
+            for _ in range(2):
+                o2 = torch.zeros_like(out)
+                l2 = torch.zeros_like(lse)
+                B.irm_attend_ref(rig.s.ctx, q, pool, ROW * 2, rig.d_dst_slots, rig.d_req_offsets, row, hit, trig, scale,
+                                 other, ws2, o2, l2)
+                outs.append((o2, l2))
+            assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]), other
+            assert (outs[0][0] - first).abs().max().item() < 1e-3 and (outs[0][1] - lse4).abs().max().item() < 3e-4, other
+        assert rig.s.error_flags() == 0
     finally:
         rig.close()
 
