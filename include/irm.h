@@ -286,8 +286,8 @@ irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
  *   d_row_index[slot] = src_row + j   pool row that holds the slot's (c_KV, k_r_base)
  *   d_hit_index[slot] = h             which rotation the load path applies to that row
  * and d_trig[h][i] = (cos, sin)(delta_h * inv_freq[i]), i < 32, fp32 pairs in pair order
- * (exactly (1, 0) when delta = 0; angle reduced in fp64).  The consumer, an attention
- * kernel that rotates k_r on load, is not part of this library.
+ * (exactly (1, 0) when delta = 0; angle reduced in fp64).  A consumer, an attention
+ * kernel that rotates k_r on load, is irm_attend_ref below.
  *   d_row_index, d_hit_index  int32[dst_rows], slots no hit covers are left as they were
  *   d_trig                    float[hit_capacity][32][2], 8-byte aligned
  * Bad indices are skipped and flagged like in irm_reattach. */
