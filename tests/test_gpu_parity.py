@@ -69,7 +69,7 @@ def test_cdc_ragged_requests_and_edge_lengths(serial):
 
 @pytest.mark.parametrize("mask,lo,hi", [(0x7F, 32, 512), (0x1, 1, 3), (0xFFFF, 16, 100), (0x0, 4, 9),
                                         (0xF, 4, 4), (0xFFFFF, 64, 65536), (0xFF, 64, 1024),
-                                        (0xFFFFFFFF, 32, 40)])
+                                        (0xFFFFFFFF, 32, 40), (0xFF, 128, 128), (0x1, 1, 1)])   # last two: fixed blocks
 @pytest.mark.parametrize("serial", [False, True])
 def test_cdc_other_masks_and_clamps(mask, lo, hi, serial):
     rng = np.random.default_rng(mask % 1000 + lo)

@@ -207,3 +207,25 @@ def test_gear_table_is_the_splitmix64_stream():
     g = wl.gear_table(seed=0)
     assert [int(v) for v in g[:3]] == [0x7B1DCDAF, 0xA1B965F4, 0x8009454F]
     assert len(set(wl.gear_table().tolist())) == 256
+
+
+def test_equal_clamps_give_the_fixed_block_chunking():
+    """min = max = B turns the rule into fixed-size blocks counted from each request's start (the
+    fixed-block hashing the paper compares against in Sec. 4): no candidate can cut before B tokens,
+    the clamp cuts at B, only a request's tail is shorter.  Content plays no part."""
+    rng = np.random.default_rng(12)
+    off = np.array([0, 1000, 1000, 1128, 1500], np.uint32)
+    for B in (128, 64, 1):
+        outs = []
+        for gear_seed in (0, 5):
+            tokens = rng.integers(0, 102400, 1500).astype(np.int32)
+            st, ln, rco = orc.cdc_chunk(tokens, off, wl.gear_table(seed=gear_seed), 0xFF, B, B)
+            want_st, want_ln, want_rco = [], [], [0]
+            for r in range(4):
+                for s in range(int(off[r]), int(off[r + 1]), B):
+                    want_st.append(s)
+                    want_ln.append(min(B, int(off[r + 1]) - s))
+                want_rco.append(len(want_st))
+            assert st.tolist() == want_st and ln.tolist() == want_ln and rco.tolist() == want_rco
+            outs.append((st, ln))
+        assert np.array_equal(outs[0][0], outs[1][0])
