@@ -333,6 +333,31 @@ def reattach_ref(src_rows, row_index, hit_index, dst_slots, hits: Hits, inv_freq
     return trig
 
 
+def e4m3_to_f64(codes) -> np.ndarray:
+    """The 8-bit floating-point format E4M3 in its finite-only form (the one fp8 KV caches use): one
+    sign bit, four exponent bits with bias 7, three fraction bits; exponent 0 holds the subnormals
+    f/8 * 2^-6; there are no infinities and only S.1111.111 is NaN, so the largest value is 448."""
+    c = np.asarray(codes, np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    e, f = (c >> 3) & 0xF, c & 0x7
+    val = np.where(e == 0, f / 8.0 * 2.0 ** -6, (1.0 + f / 8.0) * 2.0 ** (e.astype(np.float64) - 7.0))
+    val = np.where((e == 15) & (f == 7), np.nan, val)
+    return sign * val
+
+
+def dequant_fp8_rows(row_bits) -> np.ndarray:
+    """fp8 rows [n][328] u16 (512 E4M3 codes | four fp32 scales | 64 bf16 of k_r) -> [n][576] f64:
+    c_KV element d = value of code d times the scale of its block of 128, exact in fp64 (an 4-bit
+    by 24-bit product); k_r widened from bf16."""
+    row_bits = np.ascontiguousarray(row_bits, np.uint16)
+    assert row_bits.ndim == 2 and row_bits.shape[1] == CKV_WORDS_FP8 + KR_DIM
+    n = row_bits.shape[0]
+    codes = row_bits[:, :256].copy().view(np.uint8).reshape(n, 512)            # little-endian byte order
+    scales = row_bits[:, 256:264].copy().view(np.float32).reshape(n, 4).astype(np.float64)
+    ckv = e4m3_to_f64(codes) * np.repeat(scales, 128, axis=1)
+    return np.concatenate([ckv, bf16_to_f64(row_bits[:, 264:])], axis=1)
+
+
 def attend_ref(q_bits, pool_bits, kv_slots, kv_offsets, row_index, hit_index, trig, scale, pair_mode=0):
     """The consumer of the no-materialise variant: MLA decode attention in the latent ("absorbed")
     form (Sec. 2 "MLA": per token a 512-dim c_KV and a 64-dim RoPE key k_r, V derived from c_KV),
@@ -347,6 +372,7 @@ def attend_ref(q_bits, pool_bits, kv_slots, kv_offsets, row_index, hit_index, tr
 
     q_bits [B][H][576] and pool_bits [rows][576] are bf16 bit patterns, everything is computed in
     fp64, nothing is rounded.  A request without context gives out = 0, lse = -inf.
+    pool_bits may also be [rows][328]: fp8 rows, whose c_KV is read through ``dequant_fp8_rows``.
     -> (out f64 [B][H][512], lse f64 [B][H])"""
     q = bf16_to_f64(np.asarray(q_bits, np.uint16))
     pool_bits = np.asarray(pool_bits, np.uint16)
@@ -355,7 +381,9 @@ def attend_ref(q_bits, pool_bits, kv_slots, kv_offsets, row_index, hit_index, tr
     row_index = np.asarray(row_index, np.int64)
     hit_index = np.asarray(hit_index, np.int64)
     n_req, n_heads = q.shape[0], q.shape[1]
-    assert q.shape[2] == ROW_DIM and pool_bits.shape[1] == ROW_DIM and len(kv_offsets) == n_req + 1
+    assert q.shape[2] == ROW_DIM and len(kv_offsets) == n_req + 1
+    fp8 = pool_bits.shape[1] == CKV_WORDS_FP8 + KR_DIM
+    assert fp8 or pool_bits.shape[1] == ROW_DIM
     out = np.zeros((n_req, n_heads, CKV_DIM), np.float64)
     lse = np.full((n_req, n_heads), -np.inf, np.float64)
     half = KR_DIM // 2
@@ -365,7 +393,7 @@ def attend_ref(q_bits, pool_bits, kv_slots, kv_offsets, row_index, hit_index, tr
             continue
         rows = row_index[slots]
         assert rows.min() >= 0 and rows.max() < pool_bits.shape[0]
-        k = bf16_to_f64(pool_bits[rows])                               # [n][576]
+        k = dequant_fp8_rows(pool_bits[rows]) if fp8 else bf16_to_f64(pool_bits[rows])   # [n][576]
         hit = hit_index[slots]
         c = np.ones((len(slots), half))
         s = np.zeros((len(slots), half))

@@ -132,3 +132,61 @@ def test_agrees_with_attention_over_materialised_bf16_rows_to_rounding():
     got, got_lse = orc.attend_ref(c["q"], c["pool"], c["kv_slots"], c["kv_offsets"], c["row_index"], c["hit_index"],
                                   c["trig"], c["scale"])
     assert 0 < np.max(np.abs(got - want)) < 2e-2 and np.max(np.abs(got_lse - want_lse)) < 2e-2
+
+
+# ------------------------------------------------------------------ fp8 rows --
+
+def test_e4m3_decoding_all_codes_against_the_library_type_and_the_format_anchors():
+    codes = np.arange(256, dtype=np.uint8)
+    got = orc.e4m3_to_f64(codes)
+    want = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan) and np.array_equal(np.nonzero(nan)[0], [0x7F, 0xFF])
+    assert np.array_equal(got[~nan], want[~nan]) and np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+    # anchors of the format itself: bias 7, subnormal step 2^-9, largest finite 448, no infinities
+    anchors = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x38: 1.0, 0x39: 1.125,
+               0x40: 2.0, 0x7E: 448.0, 0xFE: -448.0, 0xB8: -1.0}
+    for c, v in anchors.items():
+        assert got[c] == v, hex(c)
+    assert np.all(np.diff(got[:0x7F]) > 0)                                   # ordered like the codes
+
+
+def test_fp8_row_layout_bytes_blocks_and_scales():
+    """Element d of c_KV is byte d of the row, its scale the fp32 number d // 128 behind the 512 bytes;
+    k_r follows as bf16."""
+    rng = np.random.default_rng(3)
+    raw = np.zeros(656, np.uint8)
+    raw[:512] = 0x38                                                         # 1.0 everywhere
+    raw[5], raw[130], raw[511] = 0x40, 0xB8, 0x01                            # 2, -1, 2^-9
+    raw[512:528] = np.array([0.5, 3.0, 10.0, 1e-3], np.float32).view(np.uint8)
+    kr = bf16_bits(rng.standard_normal(64))
+    raw[528:] = kr.view(np.uint8)
+    row = orc.dequant_fp8_rows(raw.view(np.uint16)[None, :])[0]
+    want = np.repeat(np.array([0.5, 3.0, 10.0, 1e-3], np.float32).astype(np.float64), 128)
+    want[5], want[130], want[511] = 2 * 0.5, -1 * 3.0, 2.0 ** -9 * np.float64(np.float32(1e-3))
+    assert np.array_equal(row[:512], want)
+    assert np.array_equal(row[512:], orc.bf16_to_f64(kr))
+
+
+def test_attention_over_fp8_rows_equals_attention_over_the_same_values_in_bf16_rows():
+    """With power-of-two scales every dequantised value is a bf16 number: the fp8 pool and a bf16 pool
+    that holds those values must give the same attention, to fp64 rounding."""
+    c = case(5, pair_mode=0)
+    rng = np.random.default_rng(77)
+    rows = c["pool"].shape[0]
+    codes = rng.integers(0, 256, (rows, 512)).astype(np.uint8)
+    codes[(codes & 0x7F) == 0x7F] = 0x38                                     # no NaN codes
+    codes[(codes & 0x78) >= 0x50] &= 0xB7                                    # keep magnitudes below 16
+    scales = (2.0 ** rng.integers(-4, 1, (rows, 4))).astype(np.float32)
+    fp8 = np.empty((rows, 328), np.uint16)
+    fp8[:, :256] = codes.view(np.uint16)
+    fp8[:, 256:264] = scales.view(np.uint16)
+    fp8[:, 264:] = c["pool"][:, 512:]
+    vals = orc.e4m3_to_f64(codes) * np.repeat(scales.astype(np.float64), 128, axis=1)
+    wide = np.concatenate([bf16_bits(vals), c["pool"][:, 512:]], axis=1)
+    assert np.array_equal(orc.bf16_to_f64(wide[:, :512]), vals)              # exactly representable
+    args = (c["kv_slots"], c["kv_offsets"], c["row_index"], c["hit_index"], c["trig"], c["scale"])
+    got, got_lse = orc.attend_ref(c["q"], fp8, *args)
+    want, want_lse = orc.attend_ref(c["q"], wide, *args)
+    assert np.allclose(got, want, rtol=0, atol=1e-12) and np.allclose(got_lse, want_lse, rtol=0, atol=1e-12)
+    assert np.abs(want).max() > 0.05
