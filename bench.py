@@ -51,7 +51,7 @@ def main() -> int:
     ap.add_argument("--rows", default="bf16", choices=["bf16", "fp8"],
                     help="row format of the pools: bf16 = 1152-byte rows (the headline); fp8 = 656-byte rows, c_KV "
                          "as 512 e4m3 bytes and four fp32 scales moved bit for bit, k_r in bf16 rotated as usual "
-                         "(hit stage with --reattach full or kr, admit stage)")
+                         "(hit stage with --reattach full or kr, admit stage, attend stage: c_KV dequantised on load)")
     ap.add_argument("--heads", type=int, default=16, help="attend stage: query heads (multiple of 16)")
     ap.add_argument("--linear-rows", action="store_true",
                     help="attend stage: every slot refers to the pool row of the same number (no rotation), i.e. "
@@ -127,9 +127,14 @@ def main() -> int:
     row_format = B.IRM_ROW_FP8 if fp8 else B.IRM_ROW_BF16
     ROW_BYTES = B.ROW_WORDS[row_format] * 2
     if fp8:
-        assert args.stage in ("hit", "admit") and args.reattach in ("full", "kr"), \
-            "--rows fp8: hit stage with --reattach full or kr, or the admit stage"
-    src = (wl.kv_pool_fp8_torch if fp8 else wl.kv_pool_torch)(L, w0.src_rows, wl.kv_seed(name), dev)
+        assert args.stage in ("hit", "admit", "attend") and args.reattach in ("full", "kr"), \
+            "--rows fp8: hit stage with --reattach full or kr, the admit stage or the attend stage"
+    if fp8:
+        # whoever only moves the 528 bytes gets random ones; the attention dequantises, so it gets N(0,1) quantised
+        src = wl.kv_pool_fp8_torch(L, w0.src_rows, wl.kv_seed(name), dev,
+                                   codes="quantised" if args.stage == "attend" else "random")
+    else:
+        src = wl.kv_pool_torch(L, w0.src_rows, wl.kv_seed(name), dev)
     src_ptrs = B.layer_pointers(src)
     n_streams = max(1, args.streams)
     if n_streams > 1:
@@ -313,6 +318,7 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
     from paper_2605_05696_amd import binding as B
 
     w0 = works[0]
+    ROW_BYTES = pool.shape[2] * 2                                # 1152 (bf16 rows) or 656 (fp8 rows)
     L, dev, H = w0.n_layers, pool.device, args.heads
     n_req = w0.n_req
     scale = 1.0 / np.sqrt(192.0)
@@ -378,7 +384,8 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
             "value": ctx_tokens * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": f"{w0.name}: {n_req} request(s), one decode query each over its whole context "
+            "config": {"workload": ("fp8 rows (656 B, c_KV dequantised on load), " if ROW_BYTES == 656 else "") +
+                                   f"{w0.name}: {n_req} request(s), one decode query each over its whole context "
                                    f"({ctx_tokens} tokens in all), {H} heads, {L} layers, splits {args.splits}",
                        "variants": len(works),
                        "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach_ref once, irm_attend_ref per layer"},

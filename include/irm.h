@@ -307,7 +307,8 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * values irm_reattach would have written); products in bf16 MFMA with fp32 accumulation.
  *   d_q            bf16 [n_req][n_heads][576] (latent-space query | rotary query), 16-byte aligned;
  *                  n_heads a multiple of 16, at most 128
- *   d_pool_layer   one layer of the pool, rows of 576 bf16 at pool_row_stride_bytes
+ *   d_pool_layer   one layer of the pool, rows of 576 bf16 (or fp8 rows, see below) at
+ *                  pool_row_stride_bytes
  *   d_kv_slots     int32, d_kv_offsets uint32[n_req + 1]: CSR of every request's context slots
  *   d_row_index, d_hit_index  int32[dst_rows] as written by irm_reattach_ref (plain rows of
  *                  prefilled tokens: any pool row with hit index -1)
@@ -317,7 +318,9 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]
  * A request without context gives out = 0, lse = -inf.  A slot, row or hit index out of
  * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing, does not
- * synchronise.  IRM_ROW_BF16 contexts only (IRM_ERR_UNSUPPORTED otherwise). */
+ * synchronise.  In an IRM_ROW_FP8 context d_pool_layer holds 656-byte rows: c_KV element d is
+ * then the E4M3 value (finite-only form, largest 448) of byte d times the fp32 scale of its
+ * block of 128, rounded once to bf16 while the rows are staged; everything else is the same. */
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
 irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
                           const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,

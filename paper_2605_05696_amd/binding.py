@@ -376,7 +376,8 @@ def irm_reattach_ref(ctx, src_rows, d_row_index, d_hit_index, d_trig, d_dst_slot
 
 def irm_attend_ref(ctx, d_q, d_pool_layer, pool_row_stride_bytes, d_kv_slots, d_kv_offsets, d_row_index,
                    d_hit_index, d_trig, scale, n_splits, d_workspace, d_out, d_lse, stream=None) -> None:
-    """d_q: bf16 [n_req, n_heads, 576]; d_pool_layer: bf16 [rows, >= 576] (one layer);
+    """d_q: bf16 [n_req, n_heads, 576]; d_pool_layer: one layer of the pool, [rows, >= 576] bf16
+    (in an fp8 context [rows, >= 328] 16-bit words typed bf16, see layer_pointers);
     d_out: float32 [n_req, n_heads, 512]; d_lse: float32 [n_req, n_heads]; d_workspace: uint8 tensor."""
     import torch
     i32 = torch.int32

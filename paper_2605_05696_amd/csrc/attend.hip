@@ -151,25 +151,65 @@ struct att_args {
     uint32_t pair_mode;
 };
 
-__device__ __forceinline__ void att_issue_rows(u32x4 (&vc)[ATT_KSTEPS], const att_smem *sm, uint32_t slot,
-                                               const att_args &a, uint32_t cw, uint32_t lane, uint32_t ct)
+// fp8 rows (512 E4M3 codes | four fp32 scales | k_r): the codes of a row are 32 vectors, so half a
+// wave takes a row and one load covers two; a lane also fetches the scale of the block of 128 its
+// 16 codes lie in.  10 + 8 loads per lane and tile instead of 18, for 656 bytes a row.
+#define ATT_NV(F8) ((F8) ? 10 : ATT_KSTEPS)
+
+template <bool F8>
+__device__ __forceinline__ void att_issue_rows(u32x4 (&vc)[ATT_NV(F8)], float (&sc)[8], const att_smem *sm,
+                                               uint32_t slot, const att_args &a, uint32_t cw, uint32_t lane,
+                                               uint32_t ct)
 {
     // an absent token reads row 0 and is zeroed when the tile lands
+    if (F8) {
+        const uint32_t sub = lane >> 5, vec = lane & 31u;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int32_t row = sm->row[slot][cw + 4u * (uint32_t)j];
-        const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
-        vc[j] = __builtin_nontemporal_load((const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride) + lane);
+        for (int i = 0; i < 8; ++i) {
+            const int32_t row = sm->row[slot][cw + 4u * (2u * (uint32_t)i + sub)];
+            const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
+            const char *base = a.pool + (uint64_t)safe * a.pool_stride;
+            vc[i] = __builtin_nontemporal_load((const u32x4 *)base + vec);
+            sc[i] = *(const float *)(base + 512u + 4u * (vec >> 3));
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int32_t row = sm->row[slot][cw + 4u * (uint32_t)j];
+            const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
+            vc[j] = __builtin_nontemporal_load((const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride) + lane);
+        }
     }
+    constexpr int KA = F8 ? 8 : 16;
     const uint32_t kr_row = ct >> 2, kj = ct & 3u;
     const int32_t row = sm->row[slot][kr_row];
     const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
-    const u32x4 *kr = (const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride + IRM_CKV_BYTES);
+    const u32x4 *kr = (const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride + (F8 ? IRM_F8_CKV_BYTES : IRM_CKV_BYTES));
     // half-split: elements 8 kj .. and their partners; interleaved: pairs 8 kj .. 8 kj + 7, whole
     const uint32_t ia = a.pair_mode == IRM_PAIR_HALF_SPLIT ? kj : 2u * kj;
     const uint32_t ib = a.pair_mode == IRM_PAIR_HALF_SPLIT ? 4u + kj : 2u * kj + 1u;
-    vc[16] = __builtin_nontemporal_load(kr + ia);
-    vc[17] = __builtin_nontemporal_load(kr + ib);
+    vc[KA] = __builtin_nontemporal_load(kr + ia);
+    vc[KA + 1] = __builtin_nontemporal_load(kr + ib);
+}
+
+// 16 E4M3 codes times their block's scale, rounded once to bf16: two 16-byte vectors
+typedef float att_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 att_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void att_dequant16(u32x4 codes, float scale, u32x4 &lo, u32x4 &hi)
+{
+    const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
+    uint32_t o[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        att_f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], false);    // codes 0, 1 of the word
+        att_f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], true);     // codes 2, 3
+        a *= scale;
+        b *= scale;
+        o[2 * k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, att_bf16x2));
+        o[2 * k + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, att_bf16x2));
+    }
+    lo = u32x4{o[0], o[1], o[2], o[3]};
+    hi = u32x4{o[4], o[5], o[6], o[7]};
 }
 
 // the (cos, sin) a lane needs for the tile it lands next; requested BEFORE newer rows are
@@ -185,11 +225,13 @@ __device__ __forceinline__ int32_t att_load_trig(f32x4 (&t4)[4], const att_smem 
 }
 
 // rotate k_r in registers (fp32, one rounding to bf16), store the tile into LDS buffer `buf`
-__device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_KSTEPS], const f32x4 (&t4)[4], int32_t hit,
-                                              att_smem *sm, uint32_t slot, uint32_t buf, const att_args &a,
-                                              uint32_t cw, uint32_t lane, uint32_t ct)
+template <bool F8>
+__device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_NV(F8)], const float (&sc)[8], const f32x4 (&t4)[4],
+                                              int32_t hit, att_smem *sm, uint32_t slot, uint32_t buf,
+                                              const att_args &a, uint32_t cw, uint32_t lane, uint32_t ct)
 {
-    u32x4 va = vc[16], vb = vc[17];
+    constexpr int KA = F8 ? 8 : 16;
+    u32x4 va = vc[KA], vb = vc[KA + 1];
     const uint32_t kr_row = ct >> 2, kj = ct & 3u;
     if (hit >= 0) {
         if (a.pair_mode == IRM_PAIR_HALF_SPLIT) {
@@ -220,12 +262,27 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_KSTEPS], const f32
     uint16_t *kt = sm->k[buf];
     const u32x4 zero = {0, 0, 0, 0};
     // two base addresses, the rest are immediate offsets of the LDS stores
-    uint16_t *lo = kt + cw * ATT_KROW + lane * 8u, *hi = lo + 32u * ATT_KROW;
-    const int32_t *rows = sm->row[slot] + cw;
+    if (F8) {
+        // staged as bf16: the compute half sees the same tile whatever the pool holds
+        const uint32_t sub = lane >> 5, vec = lane & 31u;
+        uint16_t *at = kt + (cw + 4u * sub) * ATT_KROW + vec * 16u;
+        const int32_t *rows = sm->row[slot] + cw + 4u * sub;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        *(u32x4 *)(lo + 4 * j * ATT_KROW) = rows[4 * j] >= 0 ? vc[j] : zero;
-        *(u32x4 *)(hi + 4 * j * ATT_KROW) = rows[32 + 4 * j] >= 0 ? vc[8 + j] : zero;
+        for (int i = 0; i < 8; ++i) {
+            u32x4 w0, w1;
+            att_dequant16(vc[i], sc[i], w0, w1);
+            const bool live = rows[8 * i] >= 0;
+            *(u32x4 *)(at + 8 * i * ATT_KROW) = live ? w0 : zero;
+            *(u32x4 *)(at + 8 * i * ATT_KROW + 8) = live ? w1 : zero;
+        }
+    } else {
+        uint16_t *lo = kt + cw * ATT_KROW + lane * 8u, *hi = lo + 32u * ATT_KROW;
+        const int32_t *rows = sm->row[slot] + cw;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            *(u32x4 *)(lo + 4 * j * ATT_KROW) = rows[4 * j] >= 0 ? vc[j] : zero;
+            *(u32x4 *)(hi + 4 * j * ATT_KROW) = rows[32 + 4 * j] >= 0 ? vc[8 + j] : zero;
+        }
     }
     if (sm->row[slot][kr_row] < 0) {
         va = zero;
@@ -246,6 +303,7 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_KSTEPS], const f32
 // the prologue and one at the end; in between the halves hand tiles over through LDS counters.
 // While the compute waves work on tile i in one LDS buffer, the fetch waves land tile i + 1,
 // requested a tile ago, in the other buffer as its rows arrive, and request tile i + 2 right after.
+template <bool F8>
 __global__ __launch_bounds__(512) void attend_ref_split(
     const uint16_t *__restrict__ q, uint32_t n_heads, const char *__restrict__ pool, uint64_t pool_stride,
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
@@ -286,14 +344,15 @@ __global__ __launch_bounds__(512) void attend_ref_split(
 
     if (fetcher) {
         const att_args a = {pool, pool_stride, trig, pair_mode};
-        u32x4 r[ATT_KSTEPS];
+        u32x4 r[ATT_NV(F8)];
+        float sc[8];
         f32x4 t4[4];
         ATT_SYNC();                                         // prologue 1: references of tiles 0..2 published
         int32_t hit = att_load_trig(t4, sm, 0, a, ct);
-        att_issue_rows(r, sm, 0, a, cw, lane, ct);
-        att_land_rows(r, t4, hit, sm, 0, 0, a, cw, lane, ct);
+        att_issue_rows<F8>(r, sc, sm, 0, a, cw, lane, ct);
+        att_land_rows<F8>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
         hit = att_load_trig(t4, sm, 1, a, ct);
-        att_issue_rows(r, sm, 1, a, cw, lane, ct);
+        att_issue_rows<F8>(r, sc, sm, 1, a, cw, lane, ct);
         ATT_SYNC();                                         // prologue 2: counters are zero, tile0 is in place
         att_signal(&sm->landed[cw], lane);
         for (uint32_t t = 1; t < 2u * n_pairs; ++t) {       // t = tile - tile0
@@ -301,10 +360,10 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             // tile t + 1 are published too.  Request t + 1 at once after landing t, so that it has a
             // whole tile's time to arrive.
             att_wait(&sm->consumed, 4u * (t - 1u), lane, err);
-            att_land_rows(r, t4, hit, sm, t & 3u, t & 1u, a, cw, lane, ct);
+            att_land_rows<F8>(r, sc, t4, hit, sm, t & 3u, t & 1u, a, cw, lane, ct);
             att_signal(&sm->landed[cw], lane);
             hit = att_load_trig(t4, sm, (t + 1u) & 3u, a, ct);
-            att_issue_rows(r, sm, (t + 1u) & 3u, a, cw, lane, ct);
+            att_issue_rows<F8>(r, sc, sm, (t + 1u) & 3u, a, cw, lane, ct);
         }
         __syncthreads();
         return;
@@ -550,8 +609,10 @@ __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict_
 irm_status irm_attend_init(int device)
 {
     (void)device;
-    IRM_HIP_TRY(hipFuncSetAttribute((const void *)attend_ref_split, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)sizeof(att_smem)));
+    IRM_HIP_TRY(hipFuncSetAttribute((const void *)attend_ref_split<false>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(att_smem)));
+    IRM_HIP_TRY(hipFuncSetAttribute((const void *)attend_ref_split<true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(att_smem)));
     return IRM_OK;
 }
 
@@ -574,8 +635,8 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     if (n_req < 1 || n_heads < ATT_HEADS || n_heads % ATT_HEADS || n_heads > 128 || n_splits < 1 ||
         n_splits > 1024 || n_req > 65535)
         return IRM_ERR_INVALID_ARG;
-    if (ctx && ctx->cfg.row_format != IRM_ROW_BF16) return IRM_ERR_UNSUPPORTED;   // bf16 products over bf16 rows
-    if (pool_row_stride_bytes < IRM_ROW_BYTES || (pool_row_stride_bytes & 15) || ((uintptr_t)d_pool_layer & 15) ||
+    const bool f8 = ctx->cfg.row_format == IRM_ROW_FP8;
+    if (pool_row_stride_bytes < irm_row_bytes(ctx->cfg.row_format) || (pool_row_stride_bytes & 15) || ((uintptr_t)d_pool_layer & 15) ||
         ((uintptr_t)d_q & 15) || ((uintptr_t)d_trig & 15) || pool_rows < 1 || pool_rows > 0x7FFFFFFFull ||
         dst_rows < 1 || trig_hits < 1 || !(scale > 0.0f))
         return IRM_ERR_INVALID_ARG;
@@ -588,7 +649,8 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(attend_ref_split, dim3(n_groups, n_splits, n_req), dim3(512), sizeof(att_smem), s,
+    hipLaunchKernelGGL(f8 ? attend_ref_split<true> : attend_ref_split<false>, dim3(n_groups, n_splits, n_req),
+                       dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
                        d_kv_slots, d_kv_offsets, d_row_index, d_hit_index, dst_rows, (const float2 *)d_trig,
                        trig_hits, scale * ATT_LOG2E, ctx->cfg.pair_mode, part_o, part_ml, ctx->d_err);

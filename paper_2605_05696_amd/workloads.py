@@ -411,19 +411,31 @@ def kv_pool_torch(n_layers: int, rows: int, seed: int, device="cpu", layers_per_
     return out
 
 
-def kv_pool_fp8_torch(n_layers: int, rows: int, seed: int, device="cpu", layers_per_step: int = 1):
-    """fp8 rows as [n_layers][rows][328] 16-bit words (typed bf16 like the other pools): 512 uniformly
-    random bytes standing for e4m3 codes, four fp32 block scales in [1e-3, 4), then k_r as 64 bf16
-    ~ N(0,1).  The library moves the first 528 bytes bit for bit, so any byte values serve."""
+def kv_pool_fp8_torch(n_layers: int, rows: int, seed: int, device="cpu", layers_per_step: int = 1,
+                      codes: str = "random"):
+    """fp8 rows as [n_layers][rows][328] 16-bit words (typed bf16 like the other pools): 512 bytes of
+    E4M3 codes, four fp32 block scales, then k_r as 64 bf16 ~ N(0,1).
+    codes="random": uniformly random bytes (NaN codes included) and scales in [1e-3, 4): whoever
+    moves the 528 bytes bit for bit can be given anything.
+    codes="quantised": c_KV ~ N(0,1) quantised per block of 128 by the library type (scale =
+    block maximum / 448, codes by torch's float8_e4m3fn cast): what a reader that dequantises needs."""
     import torch
+    assert codes in ("random", "quantised")
     out = torch.empty((n_layers, rows, 328), dtype=torch.int16, device=device)
     g = torch.Generator(device=device)
     g.manual_seed(seed)
     for l0 in range(0, n_layers, layers_per_step):
         l1 = min(n_layers, l0 + layers_per_step)
-        codes = torch.randint(0, 65536, (l1 - l0, rows, 256), generator=g, device=device, dtype=torch.int32)
-        out[l0:l1, :, :256] = (codes - 32768).to(torch.int16)
-        scales = torch.empty((l1 - l0, rows, 4), dtype=torch.float32, device=device).uniform_(1e-3, 4.0, generator=g)
+        if codes == "random":
+            c = torch.randint(0, 65536, (l1 - l0, rows, 256), generator=g, device=device, dtype=torch.int32)
+            out[l0:l1, :, :256] = (c - 32768).to(torch.int16)
+            scales = torch.empty((l1 - l0, rows, 4), dtype=torch.float32, device=device).uniform_(1e-3, 4.0, generator=g)
+        else:
+            v = torch.empty((l1 - l0, rows, 4, 128), dtype=torch.float32, device=device).normal_(0.0, 1.0, generator=g)
+            scales = v.abs().amax(dim=3) / 448.0
+            q = (v / scales[..., None]).to(torch.float8_e4m3fn)
+            out[l0:l1, :, :256] = q.view(torch.uint8).reshape(l1 - l0, rows, 512).view(torch.int16)
+            del v, q
         out[l0:l1, :, 256:264] = scales.view(torch.int16)
         kr = torch.empty((l1 - l0, rows, 64), dtype=torch.bfloat16, device=device).normal_(0.0, 1.0, generator=g)
         out[l0:l1, :, 264:] = kr.view(torch.int16)

@@ -36,12 +36,15 @@ def _need_gpu():
 SCALE = 1.0 / np.sqrt(192.0)
 
 
-def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None):
+def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None, fp8=False):
     """references by the library, attention by the library; expectation by the oracle alone"""
     rng = np.random.default_rng(seed)
-    s = Session.for_workload(w, DEV, pair_mode=pair_mode)
+    s = Session.for_workload(w, DEV, pair_mode=pair_mode, row_format=B.IRM_ROW_FP8 if fp8 else B.IRM_ROW_BF16)
     try:
-        pool = wl.kv_pool_torch(1, w.src_rows, wl.kv_seed(w.name.split("-")[0]), DEV)[0]
+        if fp8:
+            pool = wl.kv_pool_fp8_torch(1, w.src_rows, wl.kv_seed(w.name.split("-")[0]), DEV, codes="quantised")[0]
+        else:
+            pool = wl.kv_pool_torch(1, w.src_rows, wl.kv_seed(w.name.split("-")[0]), DEV)[0]
         cap = max(len(hits), 1) + 2
         d_hits, d_n = hits_to_dev(hits, cap)
         row = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
@@ -62,8 +65,8 @@ def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None):
         out = torch.full((n_req, n_heads, 512), 7.0, dtype=torch.float32, device=DEV)
         lse = torch.full((n_req, n_heads), 7.0, dtype=torch.float32, device=DEV)
         ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits), dtype=torch.uint8, device=DEV)
-        B.irm_attend_ref(s.ctx, q, pool, ROW * 2, d_slots, s.to_dev_u32(off), row, hit, trig, SCALE, n_splits, ws,
-                         out, lse)
+        B.irm_attend_ref(s.ctx, q, pool, pool.shape[1] * 2, d_slots, s.to_dev_u32(off), row, hit, trig, SCALE,
+                         n_splits, ws, out, lse)
         torch.cuda.synchronize()
         assert s.error_flags() == 0
         want_row = np.full(w.dst_rows, -1, np.int32)
@@ -76,10 +79,17 @@ def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None):
         s.close()
 
 
-def check(got, got_lse, want, want_lse, long_contexts=False):
+def check(got, got_lse, want, want_lse, long_contexts=False, fp8=False):
     tol_out, tol_lse = (2e-3, 6e-4) if long_contexts else (6e-3, 6e-3)
+    if fp8:
+        # the dequantised c_KV is rounded to bf16 as well: 512 more rounded terms per score (rms
+        # scale * sqrt(512) * 1e-3 ~ 2e-3 per token, three times the bf16 rows' figure) and a rounded
+        # value (up to 4.2 * 2^-9 ~ 8e-3 off) under every output.  Measured: 8e-3 / 6e-3 (output / lse)
+        # on contexts of a few tokens; 3.3e-3 / 1e-3 on contexts of thousands, where a peaked softmax
+        # (one token holding a third of the weight) lets single tokens' errors through
+        tol_out, tol_lse = (6e-3, 2e-3) if long_contexts else (2e-2, 2e-2)
     err = np.abs(got - want)
-    assert err.max() < tol_out and err.mean() < 4e-4, (err.max(), err.mean())
+    assert err.max() < tol_out and err.mean() < (8e-4 if fp8 else 4e-4), (err.max(), err.mean())
     fin = np.isfinite(want_lse)
     assert np.array_equal(np.isfinite(got_lse), fin)
     assert np.all(np.isneginf(got_lse[~fin]))
@@ -162,3 +172,29 @@ def test_attend_ref_bad_arguments_and_indices():
         check(out.cpu().numpy(), lse.cpu().numpy(), want, want_lse)
     finally:
         s.close()
+
+
+# ------------------------------------------------------------------ fp8 rows --
+
+@pytest.mark.parametrize("name,n_heads,n_splits,pair_mode", [("c2", 16, 1, 0), ("c2", 16, 5, 1), ("c1", 32, 8, 0),
+                                                             ("c3", 128, 4, 1)])
+def test_attend_ref_fp8_rows_small_configs(name, n_heads, n_splits, pair_mode):
+    """Pools of 656-byte rows: c_KV dequantised (E4M3 code times block scale) while the rows are staged."""
+    w = wl.make_workload(name, orc.cdc_chunk, size="small")
+    hits = oracle_front(w)["hits"]
+    got, got_lse, want, want_lse = run_case(w, hits, n_heads, n_splits, pair_mode, seed=21, fp8=True)
+    check(got, got_lse, want, want_lse, long_contexts=True, fp8=True)
+    again, again_lse, _, _ = run_case(w, hits, n_heads, n_splits, pair_mode, seed=21, fp8=True)
+    assert np.array_equal(got, again) and np.array_equal(got_lse, again_lse)
+
+
+def test_attend_ref_fp8_rows_ragged_contexts():
+    w = wl.make_workload("c2", orc.cdc_chunk, size="small")
+    hits = oracle_front(w)["hits"]
+    n = len(w.tokens)
+    off = np.array([0, 0, 1, 64, 65, 200, 200, 4099, n], np.uint32)
+    got, got_lse, want, want_lse = run_case(w, hits, 16, 4, 0, seed=22, kv_offsets=off, fp8=True)
+    check(got, got_lse, want, want_lse, fp8=True)
+    assert np.all(got[0] == 0) and np.all(got[5] == 0)
+    # one token: the output is that token's dequantised c_KV, rounded to bf16 and no further
+    assert np.abs(got[1] - want[1]).max() <= np.abs(want[1]).max() * 2.0 ** -8

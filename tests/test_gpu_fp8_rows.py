@@ -133,7 +133,7 @@ def test_fp8_rows_launch_shapes_and_strides_that_are_refused():
                                d_hits, d_n)
         B.irm_reattach(s.ctx, B.layer_pointers(src), 656, 64, B.layer_pointers(dst), 656, 64, slots, d_hits, d_n)
         assert s.error_flags() == 0 and torch.all(dst.view(torch.int16) == wl.SENTINEL_BF16)
-        # the rotate-on-load attention reads bf16 rows only
+        # the rotate-on-load attention of this context wants whole 656-byte rows
         q = torch.zeros((1, 16, 576), dtype=torch.bfloat16, device=DEV)
         row = torch.zeros(64, dtype=torch.int32, device=DEV)
         trig = torch.zeros((1, 32, 2), dtype=torch.float32, device=DEV)
@@ -141,9 +141,9 @@ def test_fp8_rows_launch_shapes_and_strides_that_are_refused():
         lse = torch.zeros((1, 16), dtype=torch.float32, device=DEV)
         ws = torch.empty(B.irm_attend_ref_workspace_bytes(1, 16, 1), dtype=torch.uint8, device=DEV)
         with pytest.raises(B.IrmError) as e:
-            B.irm_attend_ref(s.ctx, q, wl.kv_pool_torch(1, 64, 1, DEV)[0], 1152, slots,
-                             s.to_dev_u32(np.array([0, 64], np.uint32)), row, row, trig, 0.1, 1, ws, out, lse)
-        assert e.value.status == 3                                     # IRM_ERR_UNSUPPORTED
+            B.irm_attend_ref(s.ctx, q, src[0], 640, slots, s.to_dev_u32(np.array([0, 64], np.uint32)), row, row,
+                             trig, 0.1, 1, ws, out, lse)
+        assert e.value.status == B.IRM_ERR_INVALID_ARG
     finally:
         s.close()
 

@@ -363,3 +363,50 @@ def test_full_size_fp8_rows(name):
             assert torch.all(rig.dst[l].index_select(0, untouched).view(torch.int16) == wl.SENTINEL_BF16)
     finally:
         rig.close()
+
+
+def test_full_size_attend_ref_fp8_rows_c2():
+    """The rotate-on-load consumer over 656-byte rows at the c2 size and the bench's launch shape:
+    c_KV dequantised while staged; every output against the fp64 oracle, same bits twice."""
+    from tests.gpu_util import hits_to_dev
+    from paper_2605_05696_amd import binding as B
+    w = wl.make_workload("c2", orc.cdc_chunk, size="full")
+    rig = Rig(w, with_table=False, with_pools=False, row_format=B.IRM_ROW_FP8)
+    try:
+        hits = rig.o["hits"]
+        pool = wl.kv_pool_fp8_torch(1, w.src_rows, wl.kv_seed("c2"), DEV, codes="quantised")[0]
+        d_hits, d_n = hits_to_dev(hits, rig.buf["cap"])
+        row = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        hit = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.zeros((rig.buf["cap"], 32, 2), dtype=torch.float32, device=DEV)
+        B.irm_reattach_ref(rig.s.ctx, w.src_rows, row, hit, trig, rig.d_dst_slots, d_hits, d_n)
+        row_h = row.cpu().numpy()
+        fresh = np.nonzero(row_h < 0)[0]
+        row_h[fresh] = np.random.default_rng(6).integers(0, w.src_rows, len(fresh))
+        row.copy_(torch.from_numpy(row_h))
+        hit_h = hit.cpu().numpy()
+        n_req, H, splits, scale = w.n_req, 16, 4, 1.0 / np.sqrt(192.0)
+        q = torch.randn((n_req, H, 576), device=DEV, generator=torch.Generator(DEV).manual_seed(4)).to(torch.bfloat16)
+        outs = []
+        for _ in range(2):
+            out = torch.zeros((n_req, H, 512), dtype=torch.float32, device=DEV)
+            lse = torch.zeros((n_req, H), dtype=torch.float32, device=DEV)
+            ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, H, splits), dtype=torch.uint8, device=DEV)
+            B.irm_attend_ref(rig.s.ctx, q, pool, 656, rig.d_dst_slots, rig.d_req_offsets, row, hit, trig, scale, splits,
+                             ws, out, lse)
+            outs.append((out, lse))
+        torch.cuda.synchronize()
+        assert rig.s.error_flags() == 0
+        assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+        want_row = np.full(w.dst_rows, -1, np.int32)
+        want_hit = np.full(w.dst_rows, -1, np.int32)
+        trig64 = orc.reattach_ref(w.src_rows, want_row, want_hit, w.dst_slots, hits, w.inv_freq)
+        want, want_lse = orc.attend_ref(bits(q), bits(pool), w.dst_slots, w.req_offsets, row_h, hit_h, trig64, scale)
+        err = np.abs(outs[0][0].cpu().numpy() - want)
+        lerr = np.abs(outs[0][1].cpu().numpy() - want_lse).max()
+        # measured 3.3e-3 / 1e-4 / 1e-3: three times the bf16 rows' errors, as 512 more operands per score are
+        # rounded; a lost 64-token tile would still show (4e-3 on the lse), and so would a call that differs
+        assert err.max() < 6e-3 and err.mean() < 3e-4, (err.max(), err.mean())
+        assert lerr < 2e-3, lerr
+    finally:
+        rig.close()
