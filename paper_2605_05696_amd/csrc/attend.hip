@@ -11,20 +11,22 @@
 //       its share of the request's tokens in tiles of 64.  Four waves fetch: the tile's 64
 //       rows (1152 B each) come from HBM into registers with 16-byte loads, k_r is rotated
 //       there (fp32, one rounding to bf16: the same values the materialising kernel writes)
-//       and the tile lands in one of two LDS buffers.  Four waves compute on the other buffer:
-//         S = Q K^T     wave w: 16 heads x its 16 tokens, 18 MFMA 16x16x32 (bf16 in, fp32 acc)
-//         online softmax over the tile (running max per head shared through LDS)
-//         O += P V      wave w: 16 heads x its 128 of the 512 latent dims, 16 MFMA
-//       Q lives in registers as A operands; a row of the tile serves as B operand of S as it
-//       lies (k = dims, contiguous), and as B operand of O through transposing LDS reads
-//       (k = tokens: column pieces of the row-major tile).  Every KV byte is read from HBM
-//       once per head group.
+//       and the tile lands in one of two LDS buffers.  Four waves compute on the other buffer,
+//       each on its own 16 of the tile's 64 tokens and without a word to the others:
+//         S^T = K Q^T   16 tokens x 16 heads, 18 MFMA 16x16x32 (bf16 in, fp32 acc): a staged row
+//                       is an A operand as it lies, Q lives in registers as B operands
+//         online softmax over its tokens (the running maximum per head lives in the lanes)
+//         O^T += V^T P^T   all 512 latent dims x 16 heads, 32 MFMA 16x16x16: the softmax'd S^T
+//                       registers are the B operand as they are, V^T comes through transposing
+//                       LDS reads (column pieces of the row-major tile)
+//       At the end the four waves' (max, sum, O) meet once in LDS.  Every KV byte is read from
+//       HBM once per head group.
 //   attend_ref_merge   combines the splits' (max, sum, O) into out and lse.
 #include "irm_internal.hpp"
 
 #define ATT_TILE 64u                   // tokens per tile
 #define ATT_KROW 584u                  // bf16 per staged row: 576 + 8 of padding (1168 B)
-#define ATT_PROW 72u                   // bf16 per row of P: 64 + 8 of padding
+#define ATT_OROW 516u                  // floats per head of a wave's partial output in LDS: 512 + 4 of padding
 #define ATT_HEADS 16u                  // heads per workgroup
 #define ATT_KSTEPS 18                  // 576 / 32
 #define ATT_LOG2E 1.4426950408889634f
@@ -53,15 +55,14 @@ __device__ __forceinline__ uint32_t att_to_bf16(float x)
 }
 
 struct att_smem {
-    uint16_t k[2][ATT_TILE * ATT_KROW]; // staged rows, k_r rotated: the tile in work and the next one
-    uint16_t p[ATT_HEADS * ATT_PROW];   // softmax numerators of the tile, bf16
-    float red[4 * ATT_HEADS];           // per compute wave and head: tile maximum / final sums
-    float mfin[ATT_HEADS];              // running maximum per head at the end
+    uint16_t k[2][ATT_TILE * ATT_KROW]; // staged rows, k_r rotated: the tile in work and the next one;
+                                        // at the end the compute waves' partial outputs (fp32)
+    float wmax[4 * ATT_HEADS];          // per compute wave and head: running maximum at the end
+    float wsum[4 * ATT_HEADS];          // ... and sum
     int32_t row[4][ATT_TILE];           // pool row of each tile token, -1 = no token; slot = tile mod 4
     int32_t hit[4][ATT_TILE];           // rotation of each tile token, -1 = none
     uint32_t landed[4];                 // per fetch wave: tiles it has landed so far
-    uint32_t bar;                       // arrivals at the compute waves' own barrier
-    uint32_t consumed;                  // + 1 per compute wave and tile worked off
+    uint32_t consumed[4];               // per compute wave: tiles it is done with
 };
 
 // Barrier that orders LDS traffic only: global loads issued before it stay in flight.
@@ -72,60 +73,27 @@ struct att_smem {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");     \
     } while (0)
 
-// Barrier among the four compute waves only, through an LDS counter, so that the fetch waves are
-// not held at the two points inside a tile where only the compute waves must agree.  The four
-// waves are resident together and run the same tile loop, so every wait ends; the wait is
-// bounded all the same (a wave that gives up raises IRM_FLAG_WAIT_TIMEOUT and carries on).
-__device__ __forceinline__ void att_compute_barrier(att_smem *sm, uint32_t &arrivals, uint32_t lane, uint32_t *err)
-{
-    arrivals += 4u;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    if (lane == 0) __hip_atomic_fetch_add(&sm->bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    uint32_t spins = 0;
-    while ((int32_t)(__hip_atomic_load(&sm->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - arrivals) < 0) {
-        __builtin_amdgcn_s_sleep(1);
-        if (++spins > (1u << 18)) {
-            if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
-            break;
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 // Hand-over between the halves, through LDS counters that only grow: a fetch wave adds one to
-// its own `landed` entry per tile it has stored, a compute wave one to `consumed` per tile it is
-// done with.  Nobody waits at a common point, so the fetch waves drift apart and HBM sees a steady
-// stream instead of four waves' loads in lockstep.  Waits are bounded like the compute barrier's.
-// The fetch waves may be a tile apart (one may land tile t + 1 while another still lands t), so
-// a sum over them would not say that tile t is whole: each has its own counter and a compute
-// wave waits for all four.  The compute waves meet at their barrier twice per tile and are never
-// a whole tile apart, so for them the sum in `consumed` is enough: it reaches 4 n only when each
-// has finished n tiles.
+// its own `landed` entry per tile it has stored, a compute wave one to its own `consumed` entry
+// per tile it is done with.  Nobody waits at a common point: the fetch waves drift apart and HBM
+// sees a steady stream instead of four waves' loads in lockstep, and the compute waves never wait
+// for each other at all.  Waves of one half may therefore be a tile or more apart, so a sum over
+// them would not say that a tile is whole (or wholly worked off): whoever waits, waits for the
+// slowest of the four counters.  A wait is bounded: a wave that gives up raises
+// IRM_FLAG_WAIT_TIMEOUT and carries on, so every wave reaches the end of the kernel.
 __device__ __forceinline__ void att_signal(uint32_t *counter, uint32_t lane)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     if (lane == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-__device__ __forceinline__ void att_wait(uint32_t *counter, uint32_t target, uint32_t lane, uint32_t *err)
-{
-    uint32_t spins = 0;
-    while ((int32_t)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) - target) < 0) {
-        __builtin_amdgcn_s_sleep(1);
-        if (++spins > (1u << 18)) {
-            if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
-            break;
-        }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-__device__ __forceinline__ void att_wait_landed(uint32_t *landed, uint32_t target, uint32_t lane, uint32_t *err)
+__device__ __forceinline__ void att_wait_all(uint32_t *counters, uint32_t target, uint32_t lane, uint32_t *err)
 {
     uint32_t spins = 0;
     for (;;) {
-        uint32_t least = __hip_atomic_load(landed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        uint32_t least = __hip_atomic_load(counters, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
         for (int w = 1; w < 4; ++w) {
-            const uint32_t v = __hip_atomic_load(landed + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            const uint32_t v = __hip_atomic_load(counters + w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             least = (int32_t)(v - least) < 0 ? v : least;
         }
         if ((int32_t)(least - target) >= 0) break;
@@ -337,9 +305,10 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     // references are -1: it reads row 0, lands zeros and counts for nothing)
     const uint32_t n_pairs = (tile1 - tile0 + 1u) >> 1;
     if (threadIdx.x == 0) {
-        sm->bar = 0;
-        sm->consumed = 0;
-        for (int w = 0; w < 4; ++w) sm->landed[w] = 0;
+        for (int w = 0; w < 4; ++w) {
+            sm->landed[w] = 0;
+            sm->consumed[w] = 0;
+        }
     }
 
     if (fetcher) {
@@ -359,12 +328,14 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             // Tile t goes into the buffer tile t - 2 was worked off from; by then the references of
             // tile t + 1 are published too.  Request t + 1 at once after landing t, so that it has a
             // whole tile's time to arrive.
-            att_wait(&sm->consumed, 4u * (t - 1u), lane, err);
+            att_wait_all(sm->consumed, t - 1u, lane, err);
             att_land_rows<F8>(r, sc, t4, hit, sm, t & 3u, t & 1u, a, cw, lane, ct);
             att_signal(&sm->landed[cw], lane);
             hit = att_load_trig(t4, sm, (t + 1u) & 3u, a, ct);
             att_issue_rows<F8>(r, sc, sm, (t + 1u) & 3u, a, cw, lane, ct);
         }
+        __syncthreads();                                    // every tile worked off
+        __syncthreads();                                    // the compute waves' merge, two steps
         __syncthreads();
         return;
     }
@@ -406,22 +377,18 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             sm->hit[slot][ref_tok] = hit < 0 ? -1 : hit;
         }
     };
-    // Q as A operands: lane holds Q[head lm][32 kk + 8 lq .. + 8] for every k-step
-    u16x8 qa[ATT_KSTEPS];
+    // Q as B operands of S^T = K Q^T: lane holds Q[head lm][32 kk + 8 lq .. + 8] for every k-step
+    u16x8 qb[ATT_KSTEPS];
     {
         const uint16_t *qrow = q + ((uint64_t)b * n_heads + group * ATT_HEADS + lm) * 576u;
 #pragma unroll
-        for (int kk = 0; kk < ATT_KSTEPS; ++kk) qa[kk] = *(const u16x8 *)(qrow + 32 * kk + 8 * lq);
+        for (int kk = 0; kk < ATT_KSTEPS; ++kk) qb[kk] = *(const u16x8 *)(qrow + 32 * kk + 8 * lq);
     }
-    f32x4 o[8];
+    // O^T: lane holds O[head lm][dim 16 blk + 4 lq + i]; everything a lane owns belongs to head lm
+    f32x4 o[32];
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt) o[nt] = f32x4{0, 0, 0, 0};
-    float m_run[4], l_part[4];                              // heads 4 lq + i
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        m_run[i] = -INFINITY;
-        l_part[i] = 0.0f;
-    }
+    for (int blk = 0; blk < 32; ++blk) o[blk] = f32x4{0, 0, 0, 0};
+    float m_run = -INFINITY, l_part = 0.0f;                 // of head lm; l over this lane's tokens only
     int32_t next_sl, ref_a_row, ref_a_hit, ref_b_row = -2, ref_b_hit = -1;
     {
         // the first four tiles' references: all slot ids first, then all rows, two round trips in all
@@ -439,112 +406,109 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     ATT_SYNC();                                             // prologue 2
 
     // one tile; req_*: register pair that takes the references of tile + 4, pub_*: the pair
-    // requested a tile ago (tile + 3), published at the end
-    uint32_t arrivals = 0;
+    // requested a tile ago (tile + 3), published in the middle
     auto tile_step = [&](uint32_t tile, int32_t &req_row, int32_t &req_hit, int32_t pub_row, int32_t pub_hit) {
         const uint32_t k = tile - tile0, cur = k & 1u;
         refs_rows(tile + 4, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
         next_sl = refs_slot(tile + 5);
-        att_wait_landed(sm->landed, k + 1u, lane, err);     // tiles 0 .. k are in place, whole
-        // S = Q K^T for this wave's 16 tokens: lane holds S[head 4 lq + i][token 16 cw + lm]
-        // (all 18 operands requested first, two accumulators: neither LDS nor MFMA latency adds up)
+        att_wait_all(sm->landed, k + 1u, lane, err);        // tiles 0 .. k are in place, whole
+        // S^T for this wave's 16 tokens: lane holds S[head lm][token 16 cw + 4 lq + i]
+        // (two accumulators, so that neither LDS nor MFMA latency adds up)
         const uint16_t *krow = sm->k[cur] + (16u * cw + lm) * ATT_KROW + 8u * lq;
-        u16x8 kb[ATT_KSTEPS];
-#pragma unroll
-        for (int kk = 0; kk < ATT_KSTEPS; ++kk) kb[kk] = *(const u16x8 *)(krow + 32 * kk);
-        __builtin_amdgcn_sched_barrier(0);
-        f32x4 s = {0, 0, 0, 0}, s2 = {0, 0, 0, 0};
+        f32x4 st = {0, 0, 0, 0}, st2 = {0, 0, 0, 0};
 #pragma unroll
         for (int kk = 0; kk < ATT_KSTEPS; kk += 2) {
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[kk]),
-                                                        __builtin_bit_cast(bf16x8, kb[kk]), s, 0, 0, 0);
-            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[kk + 1]),
-                                                         __builtin_bit_cast(bf16x8, kb[kk + 1]), s2, 0, 0, 0);
+            const u16x8 ka = *(const u16x8 *)(krow + 32 * kk), kc = *(const u16x8 *)(krow + 32 * kk + 32);
+            st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka),
+                                                         __builtin_bit_cast(bf16x8, qb[kk]), st, 0, 0, 0);
+            st2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc),
+                                                          __builtin_bit_cast(bf16x8, qb[kk + 1]), st2, 0, 0, 0);
         }
-        s += s2;
+        st += st2;
         // scores in the log2 domain; tokens that do not exist score -inf
-        const bool live = sm->row[k & 3u][16u * cw + lm] >= 0;
-        float pv[4], tmax[4], alpha[4];
+        const int32_t *live = sm->row[k & 3u] + 16u * cw + 4u * lq;
+        float pv[4];
+        float tmax = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            pv[i] = live ? s[i] * scale_log2 : -INFINITY;
-            tmax[i] = pv[i];
+            pv[i] = live[i] >= 0 ? st[i] * scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, pv[i]);
         }
-        // tile maximum per head: over the 16 lanes that share lq, then over the waves
-#pragma unroll
-        for (int d = 1; d < 16; d <<= 1)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) tmax[i] = fmaxf(tmax[i], __shfl_xor(tmax[i], d));
-        if (lm == 0)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) sm->red[cw * ATT_HEADS + 4 * lq + i] = tmax[i];
-        att_compute_barrier(sm, arrivals, lane, err);       // B: tile maxima published
+        // maximum over the wave's 16 tokens: the four lanes that share lm
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        // all -inf so far (no live token yet): keep everything at zero
+        const float alpha = m_new == -INFINITY ? 1.0f : exp2f(m_run - m_new);
+        float psum = 0.0f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t h = 4 * lq + i;
-            const float tm = fmaxf(fmaxf(sm->red[h], sm->red[ATT_HEADS + h]),
-                                   fmaxf(sm->red[2 * ATT_HEADS + h], sm->red[3 * ATT_HEADS + h]));
-            const float m_new = fmaxf(m_run[i], tm);
-            // all -inf so far (no live token yet): keep everything at zero
-            alpha[i] = m_new == -INFINITY ? 1.0f : exp2f(m_run[i] - m_new);
             pv[i] = m_new == -INFINITY ? 0.0f : exp2f(pv[i] - m_new);
-            m_run[i] = m_new;
-            l_part[i] = l_part[i] * alpha[i] + pv[i];
-            // P (bf16) to LDS as the A operand of the second product
-            sm->p[h * ATT_PROW + 16u * cw + lm] = (uint16_t)att_to_bf16(pv[i]);
+            psum += pv[i];
         }
+        m_run = m_new;
+        l_part = l_part * alpha + psum;
+        // the maximum moves on a few tiles only: scale the 128 accumulators when some lane needs it
+        if (__any(alpha != 1.0f)) {
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[nt][i] *= alpha[i];
-        att_compute_barrier(sm, arrivals, lane, err);       // C: P complete, maxima consumed
-        refs_publish((k + 3u) & 3u, pub_row, pub_hit);      // that slot held tile - 1: long done
-        // O += P V: wave owns latent dims [128 cw, 128 cw + 128)
-        // The B operand wants, per lane, 8 consecutive tokens of one latent dim: a column piece
-        // of the row-major tile, fetched by two transposing LDS reads of four tokens each.
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const u16x8 pa = *(const u16x8 *)(sm->p + lm * ATT_PROW + 32 * ks + 8 * lq);
-            const uint16_t *vsrc = sm->k[cur] + (32u * ks + 8u * lq + (lm >> 2)) * ATT_KROW + 128u * cw + 4u * (lm & 3u);
-#pragma unroll
-            for (int nt = 0; nt < 8; ++nt) {
-                const s16x4 v0 = att_lds_read_tr(vsrc + 16 * nt);
-                const s16x4 v1 = att_lds_read_tr(vsrc + 4 * ATT_KROW + 16 * nt);
-                const u16x8 vv = {(uint16_t)v0[0], (uint16_t)v0[1], (uint16_t)v0[2], (uint16_t)v0[3],
-                                  (uint16_t)v1[0], (uint16_t)v1[1], (uint16_t)v1[2], (uint16_t)v1[3]};
-                o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, pa),
-                                                                __builtin_bit_cast(bf16x8, vv), o[nt], 0, 0, 0);
-            }
+            for (int blk = 0; blk < 32; ++blk) o[blk] *= alpha;
         }
-        att_signal(&sm->consumed, lane);                    // this wave is done with tile k
+        refs_publish((k + 3u) & 3u, pub_row, pub_hit);      // that slot held tile - 1: its fetches are long done
+        // O^T += V^T P^T.  P^T (bf16) is the B operand as the lanes hold it: B[k = token 4 lq + i][n = head lm].
+        // The A operand wants, per lane, 4 consecutive tokens of one latent dim: a column piece of the
+        // row-major tile, one transposing LDS read.
+        const s16x4 pt = {(short)att_to_bf16(pv[0]), (short)att_to_bf16(pv[1]), (short)att_to_bf16(pv[2]),
+                          (short)att_to_bf16(pv[3])};
+        const uint16_t *vsrc = sm->k[cur] + (16u * cw + 4u * lq + (lm >> 2)) * ATT_KROW + 4u * (lm & 3u);
+#pragma unroll
+        for (int blk = 0; blk < 32; ++blk) {
+            const s16x4 vt = att_lds_read_tr(vsrc + 16 * blk);
+            o[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, pt, o[blk], 0, 0, 0);
+        }
+        att_signal(&sm->consumed[cw], lane);                // this wave is done with tile k
     };
     for (uint32_t pr = 0; pr < n_pairs; ++pr) {
         const uint32_t tile = tile0 + 2u * pr;
         tile_step(tile, ref_b_row, ref_b_hit, ref_a_row, ref_a_hit);
         tile_step(tile + 1, ref_a_row, ref_a_hit, ref_b_row, ref_b_hit);
     }
-    // sums over the 16 lanes that share lq, then over the compute waves (each saw its own tokens)
+    // this wave's sum per head: over the four lanes that share lm
+    l_part += __shfl_xor(l_part, 16);
+    l_part += __shfl_xor(l_part, 32);
+    if (lq == 0) {
+        sm->wmax[cw * ATT_HEADS + lm] = m_run;
+        sm->wsum[cw * ATT_HEADS + lm] = l_part;
+    }
+    __syncthreads();                                        // every tile worked off: the tile buffers are free
+    // the four waves' results meet: common maximum, weights, then the outputs summed through LDS
+    float m_all = -INFINITY, l_all = 0.0f;
 #pragma unroll
-    for (int d = 1; d < 16; d <<= 1)
+    for (uint32_t w = 0; w < 4; ++w) m_all = fmaxf(m_all, sm->wmax[w * ATT_HEADS + lm]);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) l_part[i] += __shfl_xor(l_part[i], d);
-    if (lm == 0)
+    for (uint32_t w = 0; w < 4; ++w) {
+        const float mw = sm->wmax[w * ATT_HEADS + lm];
+        l_all += mw == -INFINITY ? 0.0f : sm->wsum[w * ATT_HEADS + lm] * exp2f(mw - m_all);
+    }
+    const float mine = m_run == -INFINITY ? 0.0f : exp2f(m_run - m_all);
+    float *obuf = (float *)sm->k;                           // [4 waves][16 heads][ATT_OROW]
+    {
+        float *at = obuf + ((uint64_t)cw * ATT_HEADS + lm) * ATT_OROW + 4u * lq;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            sm->red[cw * ATT_HEADS + 4 * lq + i] = l_part[i];
-            if (cw == 0) sm->mfin[4 * lq + i] = m_run[i];   // the same in every compute wave
-        }
+        for (int blk = 0; blk < 32; ++blk) *(f32x4 *)(at + 16 * blk) = o[blk] * mine;
+    }
     __syncthreads();
     float *po = part_o + part * (ATT_HEADS * 512u);
 #pragma unroll
-    for (int nt = 0; nt < 8; ++nt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) po[(4 * lq + i) * 512u + 128u * cw + 16u * nt + lm] = o[nt][i];
-    if (threadIdx.x < ATT_HEADS) {
-        const uint32_t h = threadIdx.x;
-        const float l = sm->red[h] + sm->red[ATT_HEADS + h] + sm->red[2 * ATT_HEADS + h] + sm->red[3 * ATT_HEADS + h];
-        part_ml[part * ATT_HEADS + h] = make_float2(sm->mfin[h], l);
+    for (uint32_t e = 0; e < ATT_HEADS * 128u / 256u; ++e) {
+        const uint32_t idx = ct + 256u * e, h = idx >> 7, d4 = idx & 127u;   // head, group of four dims
+        const float *src = obuf + (uint64_t)h * ATT_OROW + 4u * d4;
+        const f32x4 acc = *(const f32x4 *)src + *(const f32x4 *)(src + ATT_HEADS * ATT_OROW) +
+                          *(const f32x4 *)(src + 2u * ATT_HEADS * ATT_OROW) +
+                          *(const f32x4 *)(src + 3u * ATT_HEADS * ATT_OROW);
+        *(f32x4 *)(po + (uint64_t)h * 512u + 4u * d4) = acc;
     }
+    if (cw == 0 && lq == 0) part_ml[part * ATT_HEADS + lm] = make_float2(m_all, l_all);
+    __syncthreads();                                        // matches the fetch waves' third
 }
 
 // grid (16 heads, head groups, requests), 512 lanes: lane d owns latent dim d of one head.
