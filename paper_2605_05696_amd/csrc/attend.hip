@@ -11,24 +11,27 @@
 //       its share of the request's tokens in tiles of 64.  Four waves fetch: the tile's 64
 //       rows (1152 B each) come from HBM into registers with 16-byte loads, k_r is rotated
 //       there (fp32, one rounding to bf16: the same values the materialising kernel writes)
-//       and the tile lands in one of two LDS buffers.  Four waves compute on the other buffer,
-//       each on its own 16 of the tile's 64 tokens and without a word to the others:
-//         S^T = K Q^T   16 tokens x 16 heads, 18 MFMA 16x16x32 (bf16 in, fp32 acc): a staged row
-//                       is an A operand as it lies, Q lives in registers as B operands
+//       and the tile lands in one of two LDS buffers.  Four waves compute on the other buffer
+//       without a word to each other; two of them share 32 of the tile's 64 tokens and split the
+//       512 latent dims of the output:
+//         S^T = K Q^T   32 tokens x 16 heads, 36 MFMA 16x16x32 (bf16 in, fp32 acc): a staged row
+//                       is an A operand as it lies, Q lives in registers as B operands (both
+//                       waves of a pair compute the same scores: cheaper than sharing them)
 //         online softmax over its tokens (the running maximum per head lives in the lanes)
-//         O^T += V^T P^T   all 512 latent dims x 16 heads, 32 MFMA 16x16x16: the softmax'd S^T
-//                       registers are the B operand as they are, V^T comes through transposing
+//         O^T += V^T P^T   256 latent dims x 16 heads over the 32 tokens, 16 MFMA: the softmax'd
+//                       S^T registers are the B operand as they are, V^T comes through transposing
 //                       LDS reads (column pieces of the row-major tile)
-//       At the end the four waves' (max, sum, O) meet once in LDS.  Every KV byte is read from
-//       HBM once per head group.
+//       At the end the two token groups' (max, sum, O) meet once in LDS.  Every KV byte is read
+//       from HBM once per head group.
 //   attend_ref_merge   combines the splits' (max, sum, O) into out and lse.
 #include "irm_internal.hpp"
 
 #define ATT_TILE 64u                   // tokens per tile
 #define ATT_KROW 584u                  // bf16 per staged row: 576 + 8 of padding (1168 B)
-#define ATT_OROW 516u                  // floats per head of a wave's partial output in LDS: 512 + 4 of padding
+#define ATT_OROW 516u                  // floats per head of a partial output in LDS: 512 + 4 of padding
 #define ATT_HEADS 16u                  // heads per workgroup
 #define ATT_KSTEPS 18                  // 576 / 32
+#define ATT_RING 8u                    // tiles whose references are kept in LDS (published five tiles ahead)
 #define ATT_LOG2E 1.4426950408889634f
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -57,10 +60,10 @@ __device__ __forceinline__ uint32_t att_to_bf16(float x)
 struct att_smem {
     uint16_t k[2][ATT_TILE * ATT_KROW]; // staged rows, k_r rotated: the tile in work and the next one;
                                         // at the end the compute waves' partial outputs (fp32)
-    float wmax[4 * ATT_HEADS];          // per compute wave and head: running maximum at the end
-    float wsum[4 * ATT_HEADS];          // ... and sum
-    int32_t row[4][ATT_TILE];           // pool row of each tile token, -1 = no token; slot = tile mod 4
-    int32_t hit[4][ATT_TILE];           // rotation of each tile token, -1 = none
+    float wmax[2 * ATT_HEADS];          // per token group (pair of compute waves) and head: running maximum at the end
+    float wsum[2 * ATT_HEADS];          // ... and sum
+    int32_t row[ATT_RING][ATT_TILE];    // pool row of each tile token, -1 = no token; slot = tile mod ATT_RING
+    int32_t hit[ATT_RING][ATT_TILE];    // rotation of each tile token, -1 = none
     uint32_t landed[4];                 // per fetch wave: tiles it has landed so far
     uint32_t consumed[4];               // per compute wave: tiles it is done with
 };
@@ -124,40 +127,74 @@ struct att_args {
 // 16 codes lie in.  10 + 8 loads per lane and tile instead of 18, for 656 bytes a row.
 #define ATT_NV(F8) ((F8) ? 10 : ATT_KSTEPS)
 
+// Where a lane's loads of one tile go: worked out from the tile's references a tile ahead of the
+// loads themselves, so that a wave whose registers have just been emptied has its next requests on
+// the way within a few instructions (measured: reading the references and forming the addresses
+// took a quarter of a tile's time, during which the wave had nothing in flight).
 template <bool F8>
-__device__ __forceinline__ void att_issue_rows(u32x4 (&vc)[ATT_NV(F8)], float (&sc)[8], const att_smem *sm,
-                                               uint32_t slot, const att_args &a, uint32_t cw, uint32_t lane,
-                                               uint32_t ct)
+struct att_addr {
+    const char *row[F8 ? 8 : 16];       // this lane's 16 bytes of each of its rows (an absent token: row 0)
+    const u32x4 *kr;                    // the k_r line of the row this lane rotates a part of
+    const f32x4 *trig;                  // that row's (cos, sin) for this lane's pairs
+    int32_t hit;
+};
+
+template <bool F8>
+__device__ __forceinline__ void att_addr_rows(att_addr<F8> &ad, const att_smem *sm, uint32_t slot,
+                                              const att_args &a, uint32_t cw, uint32_t lane, uint32_t ct)
 {
-    // an absent token reads row 0 and is zeroed when the tile lands
     if (F8) {
         const uint32_t sub = lane >> 5, vec = lane & 31u;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int32_t row = sm->row[slot][cw + 4u * (2u * (uint32_t)i + sub)];
             const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
-            const char *base = a.pool + (uint64_t)safe * a.pool_stride;
-            vc[i] = __builtin_nontemporal_load((const u32x4 *)base + vec);
-            sc[i] = *(const float *)(base + 512u + 4u * (vec >> 3));
+            ad.row[i] = a.pool + (uint64_t)safe * a.pool_stride + 16u * vec;
         }
     } else {
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int32_t row = sm->row[slot][cw + 4u * (uint32_t)j];
             const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
-            vc[j] = __builtin_nontemporal_load((const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride) + lane);
+            ad.row[j] = a.pool + (uint64_t)safe * a.pool_stride + 16u * lane;
         }
     }
-    constexpr int KA = F8 ? 8 : 16;
-    const uint32_t kr_row = ct >> 2, kj = ct & 3u;
-    const int32_t row = sm->row[slot][kr_row];
+    const int32_t row = sm->row[slot][ct >> 2];
     const uint32_t safe = row >= 0 ? (uint32_t)row : 0u;
-    const u32x4 *kr = (const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride + (F8 ? IRM_F8_CKV_BYTES : IRM_CKV_BYTES));
+    ad.kr = (const u32x4 *)(a.pool + (uint64_t)safe * a.pool_stride + (F8 ? IRM_F8_CKV_BYTES : IRM_CKV_BYTES));
+    ad.hit = sm->hit[slot][ct >> 2];
+    const uint32_t hsafe = ad.hit >= 0 ? (uint32_t)ad.hit : 0u;     // entry 0 always exists
+    ad.trig = (const f32x4 *)(a.trig + (uint64_t)hsafe * IRM_KR_PAIRS + 8u * (ct & 3u));
+}
+
+// request a tile: the (cos, sin) first (the landing needs them no later than the rows), then the rows
+template <bool F8>
+__device__ __forceinline__ int32_t att_fire_rows(u32x4 (&vc)[ATT_NV(F8)], float (&sc)[8], f32x4 (&t4)[4],
+                                                 const att_addr<F8> &ad, const att_args &a, uint32_t lane,
+                                                 uint32_t ct)
+{
+#pragma unroll
+    for (int w = 0; w < 4; ++w) t4[w] = ad.trig[w];         // (c, s, c, s) of two pairs each
+    if (F8) {
+        const uint32_t vec = lane & 31u;
+        const int32_t to_scale = 512 + 4 * (int32_t)(vec >> 3) - 16 * (int32_t)vec;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            vc[i] = __builtin_nontemporal_load((const u32x4 *)ad.row[i]);
+            sc[i] = *(const float *)(ad.row[i] + to_scale);
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) vc[j] = __builtin_nontemporal_load((const u32x4 *)ad.row[j]);
+    }
+    constexpr int KA = F8 ? 8 : 16;
+    const uint32_t kj = ct & 3u;
     // half-split: elements 8 kj .. and their partners; interleaved: pairs 8 kj .. 8 kj + 7, whole
     const uint32_t ia = a.pair_mode == IRM_PAIR_HALF_SPLIT ? kj : 2u * kj;
     const uint32_t ib = a.pair_mode == IRM_PAIR_HALF_SPLIT ? 4u + kj : 2u * kj + 1u;
-    vc[KA] = __builtin_nontemporal_load(kr + ia);
-    vc[KA + 1] = __builtin_nontemporal_load(kr + ib);
+    vc[KA] = __builtin_nontemporal_load(ad.kr + ia);
+    vc[KA + 1] = __builtin_nontemporal_load(ad.kr + ib);
+    return ad.hit;
 }
 
 // 16 E4M3 codes times their block's scale, rounded once to bf16: two 16-byte vectors
@@ -178,18 +215,6 @@ __device__ __forceinline__ void att_dequant16(u32x4 codes, float scale, u32x4 &l
     }
     lo = u32x4{o[0], o[1], o[2], o[3]};
     hi = u32x4{o[4], o[5], o[6], o[7]};
-}
-
-// the (cos, sin) a lane needs for the tile it lands next; requested BEFORE newer rows are
-__device__ __forceinline__ int32_t att_load_trig(f32x4 (&t4)[4], const att_smem *sm, uint32_t slot,
-                                                 const att_args &a, uint32_t ct)
-{
-    const int32_t hit = sm->hit[slot][ct >> 2];
-    const uint32_t safe = hit >= 0 ? (uint32_t)hit : 0u;    // entry 0 always exists
-    const f32x4 *tp = (const f32x4 *)(a.trig + (uint64_t)safe * IRM_KR_PAIRS + 8u * (ct & 3u));
-#pragma unroll
-    for (int w = 0; w < 4; ++w) t4[w] = tp[w];              // (c, s, c, s) of two pairs each
-    return hit;
 }
 
 // rotate k_r in registers (fp32, one rounding to bf16), store the tile into LDS buffer `buf`
@@ -313,26 +338,61 @@ __global__ __launch_bounds__(512) void attend_ref_split(
 
     if (fetcher) {
         const att_args a = {pool, pool_stride, trig, pair_mode};
+        constexpr uint32_t RM = ATT_RING - 1u;
         u32x4 r[ATT_NV(F8)];
         float sc[8];
         f32x4 t4[4];
-        ATT_SYNC();                                         // prologue 1: references of tiles 0..2 published
-        int32_t hit = att_load_trig(t4, sm, 0, a, ct);
-        att_issue_rows<F8>(r, sc, sm, 0, a, cw, lane, ct);
-        att_land_rows<F8>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
-        hit = att_load_trig(t4, sm, 1, a, ct);
-        att_issue_rows<F8>(r, sc, sm, 1, a, cw, lane, ct);
-        ATT_SYNC();                                         // prologue 2: counters are zero, tile0 is in place
-        att_signal(&sm->landed[cw], lane);
-        for (uint32_t t = 1; t < 2u * n_pairs; ++t) {       // t = tile - tile0
-            // Tile t goes into the buffer tile t - 2 was worked off from; by then the references of
-            // tile t + 1 are published too.  Request t + 1 at once after landing t, so that it has a
-            // whole tile's time to arrive.
-            att_wait_all(sm->consumed, t - 1u, lane, err);
-            att_land_rows<F8>(r, sc, t4, hit, sm, t & 3u, t & 1u, a, cw, lane, ct);
+        att_addr<F8> ad;
+        ATT_SYNC();                                         // prologue 1: references of tiles 0..4 published
+        att_addr_rows<F8>(ad, sm, 0, a, cw, lane, ct);
+        int32_t hit = att_fire_rows<F8>(r, sc, t4, ad, a, lane, ct);
+        att_addr_rows<F8>(ad, sm, 1, a, cw, lane, ct);
+        if (F8) {
+            // Rows of 656 bytes: one tile per wave is only 42 KB on its way per compute unit, too little
+            // for the memory latency, so a wave keeps two tiles in flight in two register sets.  Tile
+            // t + 2 is requested right after tile t has landed.
+            u32x4 r2[ATT_NV(F8)];
+            float sc2[8];
+            f32x4 t42[4];
+            int32_t hit2 = att_fire_rows<F8>(r2, sc2, t42, ad, a, lane, ct);
+            att_addr_rows<F8>(ad, sm, 2, a, cw, lane, ct);
+            att_land_rows<F8>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
+            hit = att_fire_rows<F8>(r, sc, t4, ad, a, lane, ct);
+            att_addr_rows<F8>(ad, sm, 3, a, cw, lane, ct);
+            ATT_SYNC();                                     // prologue 2: counters are zero, tile 0 is in place
             att_signal(&sm->landed[cw], lane);
-            hit = att_load_trig(t4, sm, (t + 1u) & 3u, a, ct);
-            att_issue_rows<F8>(r, sc, sm, (t + 1u) & 3u, a, cw, lane, ct);
+            uint32_t t = 1;                                 // t = tile - tile0; odd tiles use the second set
+            for (; t + 1u < 2u * n_pairs; t += 2u) {
+                att_wait_all(sm->consumed, t - 1u, lane, err);
+                att_land_rows<F8>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
+                att_signal(&sm->landed[cw], lane);
+                hit2 = att_fire_rows<F8>(r2, sc2, t42, ad, a, lane, ct);           // tile t + 2
+                att_addr_rows<F8>(ad, sm, (t + 3u) & RM, a, cw, lane, ct);
+                att_wait_all(sm->consumed, t, lane, err);
+                att_land_rows<F8>(r, sc, t4, hit, sm, (t + 1u) & RM, 0u, a, cw, lane, ct);
+                att_signal(&sm->landed[cw], lane);
+                hit = att_fire_rows<F8>(r, sc, t4, ad, a, lane, ct);               // tile t + 3
+                att_addr_rows<F8>(ad, sm, (t + 4u) & RM, a, cw, lane, ct);
+            }
+            att_wait_all(sm->consumed, t - 1u, lane, err);  // the last tile, 2 n_pairs - 1: odd
+            att_land_rows<F8>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
+            att_signal(&sm->landed[cw], lane);
+        } else {
+            att_land_rows<F8>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
+            hit = att_fire_rows<F8>(r, sc, t4, ad, a, lane, ct);                   // tile 1
+            att_addr_rows<F8>(ad, sm, 2, a, cw, lane, ct);
+            ATT_SYNC();                                     // prologue 2: counters are zero, tile 0 is in place
+            att_signal(&sm->landed[cw], lane);
+            for (uint32_t t = 1; t < 2u * n_pairs; ++t) {   // t = tile - tile0
+                // Tile t goes into the buffer tile t - 2 was worked off from.  Request t + 1 at once
+                // after landing t, so that it has a whole tile's time to arrive (more than 18 loads
+                // in flight per lane slow the stream down: measured).
+                att_wait_all(sm->consumed, t - 1u, lane, err);
+                att_land_rows<F8>(r, sc, t4, hit, sm, t & RM, t & 1u, a, cw, lane, ct);
+                att_signal(&sm->landed[cw], lane);
+                hit = att_fire_rows<F8>(r, sc, t4, ad, a, lane, ct);               // tile t + 1
+                att_addr_rows<F8>(ad, sm, (t + 2u) & RM, a, cw, lane, ct);
+            }
         }
         __syncthreads();                                    // every tile worked off
         __syncthreads();                                    // the compute waves' merge, two steps
@@ -344,10 +404,11 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     const uint32_t lm = lane & 15, lq = lane >> 4;          // MFMA coordinates of this lane
     // References (slot -> pool row, rotation): lanes 0..15 of wave cw for tokens 16 cw .. + 15 of a
     // tile.  The two dependent loads are spread over three tiles' time so that nobody waits for
-    // them: during tile i the slot ids of tile i + 5 are requested, the rows and rotations of
-    // tile i + 4 (whose slot ids came in during tile i - 1) are requested into one register
-    // pair, and those of tile i + 3, requested a tile ago into the other pair, are checked and
-    // published.  Slot = tile mod 4.
+    // them: during tile i the slot ids of tile i + 7 are requested, the rows and rotations of
+    // tile i + 6 (whose slot ids came in during tile i - 1) are requested into one register
+    // pair, and those of tile i + 5, requested a tile ago into the other pair, are checked and
+    // published: a fetch wave that has landed tile t (every compute wave is done with t - 2
+    // then) finds the references up to tile t + 3.  Slot = tile mod ATT_RING.
     const uint32_t ref_tok = 16u * cw + lane;               // meaningful for lane < 16
     auto refs_slot = [&](uint32_t tile) -> int32_t {
         if (lane >= 16u || tile >= tile1) return -1;
@@ -384,57 +445,70 @@ __global__ __launch_bounds__(512) void attend_ref_split(
 #pragma unroll
         for (int kk = 0; kk < ATT_KSTEPS; ++kk) qb[kk] = *(const u16x8 *)(qrow + 32 * kk + 8 * lq);
     }
-    // O^T: lane holds O[head lm][dim 16 blk + 4 lq + i]; everything a lane owns belongs to head lm
-    f32x4 o[32];
+    // Two waves share 32 of the tile's 64 tokens (tg) and split the latent dims (dh): both compute
+    // the scores of their 32 tokens (the same instructions on the same data: the same bits), each
+    // accumulates 256 of the 512 output dims.  O^T: lane holds O[head lm][dim 256 dh + 16 blk + 4 lq + i];
+    // everything a lane owns belongs to head lm.
+    const uint32_t tg = cw >> 1, dh = cw & 1u;
+    f32x4 o[16];
 #pragma unroll
-    for (int blk = 0; blk < 32; ++blk) o[blk] = f32x4{0, 0, 0, 0};
+    for (int blk = 0; blk < 16; ++blk) o[blk] = f32x4{0, 0, 0, 0};
     float m_run = -INFINITY, l_part = 0.0f;                 // of head lm; l over this lane's tokens only
     int32_t next_sl, ref_a_row, ref_a_hit, ref_b_row = -2, ref_b_hit = -1;
     {
-        // the first four tiles' references: all slot ids first, then all rows, two round trips in all
-        int32_t sl[4], rw[3], ht[3];
+        // the first six tiles' references: all slot ids first, then all rows, two round trips in all
+        int32_t sl[6], rw[5], ht[5];
 #pragma unroll
-        for (uint32_t k = 0; k < 4; ++k) sl[k] = refs_slot(tile0 + k);
-        next_sl = refs_slot(tile0 + 4);
+        for (uint32_t k = 0; k < 6; ++k) sl[k] = refs_slot(tile0 + k);
+        next_sl = refs_slot(tile0 + 6);
 #pragma unroll
-        for (uint32_t k = 0; k < 3; ++k) refs_rows(tile0 + k, sl[k], rw[k], ht[k]);
-        refs_rows(tile0 + 3, sl[3], ref_a_row, ref_a_hit);
+        for (uint32_t k = 0; k < 5; ++k) refs_rows(tile0 + k, sl[k], rw[k], ht[k]);
+        refs_rows(tile0 + 5, sl[5], ref_a_row, ref_a_hit);
 #pragma unroll
-        for (uint32_t k = 0; k < 3; ++k) refs_publish(k, rw[k], ht[k]);
+        for (uint32_t k = 0; k < 5; ++k) refs_publish(k, rw[k], ht[k]);
     }
     ATT_SYNC();                                             // prologue 1
     ATT_SYNC();                                             // prologue 2
 
-    // one tile; req_*: register pair that takes the references of tile + 4, pub_*: the pair
-    // requested a tile ago (tile + 3), published in the middle
+    // one tile; req_*: register pair that takes the references of tile + 6, pub_*: the pair
+    // requested a tile ago (tile + 5), published in the middle
     auto tile_step = [&](uint32_t tile, int32_t &req_row, int32_t &req_hit, int32_t pub_row, int32_t pub_hit) {
         const uint32_t k = tile - tile0, cur = k & 1u;
-        refs_rows(tile + 4, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
-        next_sl = refs_slot(tile + 5);
+        refs_rows(tile + 6, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
+        next_sl = refs_slot(tile + 7);
         att_wait_all(sm->landed, k + 1u, lane, err);        // tiles 0 .. k are in place, whole
-        // S^T for this wave's 16 tokens: lane holds S[head lm][token 16 cw + 4 lq + i]
-        // (two accumulators, so that neither LDS nor MFMA latency adds up)
-        const uint16_t *krow = sm->k[cur] + (16u * cw + lm) * ATT_KROW + 8u * lq;
-        f32x4 st = {0, 0, 0, 0}, st2 = {0, 0, 0, 0};
+        // S^T for this pair's 32 tokens, two blocks of 16: lane holds S[head lm][token 32 tg + 4 lq + i]
+        // and S[head lm][token 32 tg + 16 + 4 lq + i].  Four accumulators, so that neither LDS nor MFMA
+        // latency adds up.
+        const uint16_t *krow = sm->k[cur] + (32u * tg + lm) * ATT_KROW + 8u * lq;
+        f32x4 sa = {0, 0, 0, 0}, sa2 = {0, 0, 0, 0}, sb = {0, 0, 0, 0}, sb2 = {0, 0, 0, 0};
 #pragma unroll
         for (int kk = 0; kk < ATT_KSTEPS; kk += 2) {
-            const u16x8 ka = *(const u16x8 *)(krow + 32 * kk), kc = *(const u16x8 *)(krow + 32 * kk + 32);
-            st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka),
-                                                         __builtin_bit_cast(bf16x8, qb[kk]), st, 0, 0, 0);
-            st2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kc),
-                                                          __builtin_bit_cast(bf16x8, qb[kk + 1]), st2, 0, 0, 0);
+            const u16x8 a0 = *(const u16x8 *)(krow + 32 * kk), a1 = *(const u16x8 *)(krow + 32 * kk + 32);
+            const u16x8 b0 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk);
+            const u16x8 b1 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk + 32);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0),
+                                                         __builtin_bit_cast(bf16x8, qb[kk]), sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b0),
+                                                         __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
+            sa2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1),
+                                                          __builtin_bit_cast(bf16x8, qb[kk + 1]), sa2, 0, 0, 0);
+            sb2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b1),
+                                                          __builtin_bit_cast(bf16x8, qb[kk + 1]), sb2, 0, 0, 0);
         }
-        st += st2;
+        sa += sa2;
+        sb += sb2;
         // scores in the log2 domain; tokens that do not exist score -inf
-        const int32_t *live = sm->row[k & 3u] + 16u * cw + 4u * lq;
-        float pv[4];
+        const int32_t *live = sm->row[k & (ATT_RING - 1u)] + 32u * tg + 4u * lq;
+        float pv[8];
         float tmax = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            pv[i] = live[i] >= 0 ? st[i] * scale_log2 : -INFINITY;
-            tmax = fmaxf(tmax, pv[i]);
+            pv[i] = live[i] >= 0 ? sa[i] * scale_log2 : -INFINITY;
+            pv[4 + i] = live[16 + i] >= 0 ? sb[i] * scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, fmaxf(pv[i], pv[4 + i]));
         }
-        // maximum over the wave's 16 tokens: the four lanes that share lm
+        // maximum over the pair's 32 tokens: the four lanes that share lm
         tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float m_new = fmaxf(m_run, tmax);
@@ -442,28 +516,34 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         const float alpha = m_new == -INFINITY ? 1.0f : exp2f(m_run - m_new);
         float psum = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 8; ++i) {
             pv[i] = m_new == -INFINITY ? 0.0f : exp2f(pv[i] - m_new);
             psum += pv[i];
         }
         m_run = m_new;
         l_part = l_part * alpha + psum;
-        // the maximum moves on a few tiles only: scale the 128 accumulators when some lane needs it
+        // the maximum moves on a few tiles only: scale the accumulators when some lane needs it
         if (__any(alpha != 1.0f)) {
 #pragma unroll
-            for (int blk = 0; blk < 32; ++blk) o[blk] *= alpha;
+            for (int blk = 0; blk < 16; ++blk) o[blk] *= alpha;
         }
-        refs_publish((k + 3u) & 3u, pub_row, pub_hit);      // that slot held tile - 1: its fetches are long done
-        // O^T += V^T P^T.  P^T (bf16) is the B operand as the lanes hold it: B[k = token 4 lq + i][n = head lm].
-        // The A operand wants, per lane, 4 consecutive tokens of one latent dim: a column piece of the
-        // row-major tile, one transposing LDS read.
-        const s16x4 pt = {(short)att_to_bf16(pv[0]), (short)att_to_bf16(pv[1]), (short)att_to_bf16(pv[2]),
-                          (short)att_to_bf16(pv[3])};
-        const uint16_t *vsrc = sm->k[cur] + (16u * cw + 4u * lq + (lm >> 2)) * ATT_KROW + 4u * (lm & 3u);
+        refs_publish((k + 5u) & (ATT_RING - 1u), pub_row, pub_hit);   // that slot held tile - 3: long done with
+        // O^T += V^T P^T over the 32 tokens at once.  P^T (bf16) is the B operand as the lanes hold it,
+        // contraction slot 8 lq + i standing for token 4 lq + i (i < 4) or 16 + 4 lq + i - 4: the A
+        // operand follows the same order, four consecutive tokens of one latent dim from each block of
+        // 16, two transposing LDS reads (column pieces of the row-major tile).
+        const u16x8 pt = {(uint16_t)att_to_bf16(pv[0]), (uint16_t)att_to_bf16(pv[1]), (uint16_t)att_to_bf16(pv[2]),
+                          (uint16_t)att_to_bf16(pv[3]), (uint16_t)att_to_bf16(pv[4]), (uint16_t)att_to_bf16(pv[5]),
+                          (uint16_t)att_to_bf16(pv[6]), (uint16_t)att_to_bf16(pv[7])};
+        const uint16_t *vsrc = sm->k[cur] + (32u * tg + 4u * lq + (lm >> 2)) * ATT_KROW + 256u * dh + 4u * (lm & 3u);
 #pragma unroll
-        for (int blk = 0; blk < 32; ++blk) {
-            const s16x4 vt = att_lds_read_tr(vsrc + 16 * blk);
-            o[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vt, pt, o[blk], 0, 0, 0);
+        for (int blk = 0; blk < 16; ++blk) {
+            const s16x4 v0 = att_lds_read_tr(vsrc + 16 * blk);
+            const s16x4 v1 = att_lds_read_tr(vsrc + 16 * ATT_KROW + 16 * blk);
+            const u16x8 vt = {(uint16_t)v0[0], (uint16_t)v0[1], (uint16_t)v0[2], (uint16_t)v0[3],
+                              (uint16_t)v1[0], (uint16_t)v1[1], (uint16_t)v1[2], (uint16_t)v1[3]};
+            o[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt),
+                                                             __builtin_bit_cast(bf16x8, pt), o[blk], 0, 0, 0);
         }
         att_signal(&sm->consumed[cw], lane);                // this wave is done with tile k
     };
@@ -472,29 +552,29 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         tile_step(tile, ref_b_row, ref_b_hit, ref_a_row, ref_a_hit);
         tile_step(tile + 1, ref_a_row, ref_a_hit, ref_b_row, ref_b_hit);
     }
-    // this wave's sum per head: over the four lanes that share lm
+    // this pair's sum per head: over the four lanes that share lm
     l_part += __shfl_xor(l_part, 16);
     l_part += __shfl_xor(l_part, 32);
-    if (lq == 0) {
-        sm->wmax[cw * ATT_HEADS + lm] = m_run;
-        sm->wsum[cw * ATT_HEADS + lm] = l_part;
+    if (dh == 0 && lq == 0) {
+        sm->wmax[tg * ATT_HEADS + lm] = m_run;
+        sm->wsum[tg * ATT_HEADS + lm] = l_part;
     }
     __syncthreads();                                        // every tile worked off: the tile buffers are free
-    // the four waves' results meet: common maximum, weights, then the outputs summed through LDS
+    // the two token groups meet: common maximum, weights, then the outputs summed through LDS
     float m_all = -INFINITY, l_all = 0.0f;
 #pragma unroll
-    for (uint32_t w = 0; w < 4; ++w) m_all = fmaxf(m_all, sm->wmax[w * ATT_HEADS + lm]);
+    for (uint32_t g = 0; g < 2; ++g) m_all = fmaxf(m_all, sm->wmax[g * ATT_HEADS + lm]);
 #pragma unroll
-    for (uint32_t w = 0; w < 4; ++w) {
-        const float mw = sm->wmax[w * ATT_HEADS + lm];
-        l_all += mw == -INFINITY ? 0.0f : sm->wsum[w * ATT_HEADS + lm] * exp2f(mw - m_all);
+    for (uint32_t g = 0; g < 2; ++g) {
+        const float mg = sm->wmax[g * ATT_HEADS + lm];
+        l_all += mg == -INFINITY ? 0.0f : sm->wsum[g * ATT_HEADS + lm] * exp2f(mg - m_all);
     }
     const float mine = m_run == -INFINITY ? 0.0f : exp2f(m_run - m_all);
-    float *obuf = (float *)sm->k;                           // [4 waves][16 heads][ATT_OROW]
+    float *obuf = (float *)sm->k;                           // [2 token groups][16 heads][ATT_OROW]
     {
-        float *at = obuf + ((uint64_t)cw * ATT_HEADS + lm) * ATT_OROW + 4u * lq;
+        float *at = obuf + ((uint64_t)tg * ATT_HEADS + lm) * ATT_OROW + 256u * dh + 4u * lq;
 #pragma unroll
-        for (int blk = 0; blk < 32; ++blk) *(f32x4 *)(at + 16 * blk) = o[blk] * mine;
+        for (int blk = 0; blk < 16; ++blk) *(f32x4 *)(at + 16 * blk) = o[blk] * mine;
     }
     __syncthreads();
     float *po = part_o + part * (ATT_HEADS * 512u);
@@ -502,10 +582,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     for (uint32_t e = 0; e < ATT_HEADS * 128u / 256u; ++e) {
         const uint32_t idx = ct + 256u * e, h = idx >> 7, d4 = idx & 127u;   // head, group of four dims
         const float *src = obuf + (uint64_t)h * ATT_OROW + 4u * d4;
-        const f32x4 acc = *(const f32x4 *)src + *(const f32x4 *)(src + ATT_HEADS * ATT_OROW) +
-                          *(const f32x4 *)(src + 2u * ATT_HEADS * ATT_OROW) +
-                          *(const f32x4 *)(src + 3u * ATT_HEADS * ATT_OROW);
-        *(f32x4 *)(po + (uint64_t)h * 512u + 4u * d4) = acc;
+        *(f32x4 *)(po + (uint64_t)h * 512u + 4u * d4) = *(const f32x4 *)src + *(const f32x4 *)(src + ATT_HEADS * ATT_OROW);
     }
     if (cw == 0 && lq == 0) part_ml[part * ATT_HEADS + lm] = make_float2(m_all, l_all);
     __syncthreads();                                        // matches the fetch waves' third
