@@ -76,7 +76,7 @@ __device__ __forceinline__ void select_serial(const uint64_t *__restrict__ bitma
     uint32_t w0 = begin >> 6;
     __syncthreads();
 
-    while (__builtin_amdgcn_readfirstlane(sh_s) < end) {   // uniform: read after a barrier
+    while ((uint32_t)__builtin_amdgcn_readfirstlane(sh_s) < end) {   // uniform: read after a barrier
         const uint32_t w1 = (end_words - w0 > CDC_SEG_WORDS) ? w0 + CDC_SEG_WORDS : end_words;
         for (uint32_t w = w0 + threadIdx.x; w < w1; w += blockDim.x) seg[w - w0] = bitmap[w];
         __syncthreads();
