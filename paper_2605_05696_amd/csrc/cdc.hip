@@ -390,6 +390,7 @@ __global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ b
     __shared__ uint32_t last_sh;
 
     const uint32_t r = blockIdx.x;
+    const bool direct = n_req == 1;
     const uint32_t begin = req_offsets[r], end = req_offsets[r + 1];
     if (begin > end || (uint64_t)end > n_tokens) {     // malformed offsets: emit nothing
         if (threadIdx.x == 0) {
@@ -397,13 +398,25 @@ __global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ b
             atomicOr(err, IRM_FLAG_BAD_CHUNK);
         }
     } else {
-        const uint32_t base = begin / min_chunk + r;   // this request's staging area
+        // one request: its list is the result, written in place; no staging, no ticket, no gathering
+        const uint32_t base = direct ? 0u : begin / min_chunk + r;   // this request's staging area
+        uint32_t *out_start = direct ? chunk_start : stage_start, *out_len = direct ? chunk_len : stage_len;
+        const uint32_t out_cap = direct ? chunk_capacity : stage_cap;
         if (force_serial || !select_jump(bitmap, &sm.g, scan_lds, r, begin, end, base, min_chunk, max_chunk,
-                                         stage_start, stage_len, req_count, stage_cap, err)) {
+                                         out_start, out_len, req_count, out_cap, err)) {
             __syncthreads();
-            select_serial(bitmap, sm.seg, r, begin, end, base, min_chunk, max_chunk, stage_start, stage_len,
-                          req_count, stage_cap, err);
+            select_serial(bitmap, sm.seg, r, begin, end, base, min_chunk, max_chunk, out_start, out_len,
+                          req_count, out_cap, err);
         }
+    }
+    if (direct) {
+        if (threadIdx.x == 0) {                        // thread 0 wrote req_count[0] itself
+            const uint32_t total = req_count[0];
+            req_chunk_offsets[0] = 0;
+            req_chunk_offsets[1] = total;
+            *n_chunks = total < chunk_capacity ? total : chunk_capacity;
+        }
+        return;
     }
     // publish this request's list, then take a ticket
     __threadfence();
