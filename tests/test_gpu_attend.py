@@ -198,3 +198,53 @@ def test_attend_ref_fp8_rows_ragged_contexts():
     assert np.all(got[0] == 0) and np.all(got[5] == 0)
     # one token: the output is that token's dequantised c_KV, rounded to bf16 and no further
     assert np.abs(got[1] - want[1]).max() <= np.abs(want[1]).max() * 2.0 ** -8
+
+
+def test_no_materialise_step_captured_in_a_graph_replays_like_eager():
+    """Front end, references and the attention over them allocate nothing and record no memset nodes:
+    one decode step is captured once and replayed, with eager work in between, against the eager result."""
+    w = wl.make_workload("c2", orc.cdc_chunk, size="small")
+    from tests.gpu_util import Rig
+    rig = Rig(w)
+    try:
+        s, buf = rig.s, rig.buf
+        row = torch.zeros((w.dst_rows,), dtype=torch.int32, device=DEV)
+        hit = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.zeros((buf["cap"], 32, 2), dtype=torch.float32, device=DEV)
+        n_req, H, splits = w.n_req, 16, 3
+        q = torch.randn((n_req, H, 576), device=DEV, generator=torch.Generator(DEV).manual_seed(5)).to(torch.bfloat16)
+        out = torch.zeros((n_req, H, 512), dtype=torch.float32, device=DEV)
+        lse = torch.zeros((n_req, H), dtype=torch.float32, device=DEV)
+        ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, H, splits), dtype=torch.uint8, device=DEV)
+        pool = rig.src[0]
+        stream = torch.cuda.Stream(device=DEV)
+
+        def step():
+            s.serve_ref(rig.d_tokens, rig.d_req_offsets, rig.d_pos_base, rig.d_dst_slots, w.src_rows, row, hit, trig,
+                        buf, stream)
+            B.irm_attend_ref(s.ctx, q, pool, ROW * 2, rig.d_dst_slots, rig.d_req_offsets, row, hit, trig, SCALE,
+                             splits, ws, out, lse, stream)
+        with torch.cuda.stream(stream):
+            step()
+            stream.synchronize()
+            assert s.error_flags() == 0
+            want_out, want_lse, want_row = out.clone(), lse.clone(), row.clone()
+            assert float(want_out.abs().max()) > 0.01
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            out.fill_(7.0)                                             # eager work between the replays
+            lse.fill_(7.0)
+            row.zero_()
+            hit.fill_(-1)
+            trig.zero_()
+            ws.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert s.error_flags() == 0
+            assert torch.equal(out, want_out) and torch.equal(lse, want_lse) and torch.equal(row, want_row), rep
+    finally:
+        rig.close()
