@@ -44,8 +44,10 @@
  *     be ordered on one stream (or otherwise not overlap).
  *
  * KV row layout: 576 bf16 = [ c_KV: 512 | k_r: 64 ] = 1152 bytes
- * (paper Sec. 2 "MLA", App. C).  Rotary pair i of k_r is elements (i, i + 32)
- * (half-split, the default) or (2i, 2i + 1) (interleaved): irm_config.pair_mode.
+ * (paper Sec. 2 "MLA", App. C), or, with irm_config.row_format = IRM_ROW_FP8,
+ * 656 bytes = [ c_KV: 512 E4M3 codes | 4 fp32 block scales | k_r: 64 bf16 ].
+ * Rotary pair i of k_r is elements (i, i + 32) (half-split, the default) or
+ * (2i, 2i + 1) (interleaved): irm_config.pair_mode.
  */
 #ifndef IRM_H
 #define IRM_H
@@ -153,20 +155,21 @@ irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
 /* Tuning knobs for measurements (launch shapes only; results never change).
  * knob 0: grid.x of the re-attach row kernel = tile slots per layer (0 = one per
  *         possible tile)
- * knob 1: c_KV rows per wave and tile (1, 2, 4, 8 or 16)
+ * knob 1: c_KV rows per wave and tile (1, 2, 4, 8 or 16; fp8 rows: not 1)
  * knob 2: bit 0 = non-temporal loads, bit 1 = non-temporal stores
  * knob 3: 1 = each XCD serves a contiguous range of a layer's tiles, 0 = round-robin
- * knob 4: waves per workgroup (1, 2, 4, 8 or 16); a tile is waves x rows-per-wave rows,
- *         at least 4
+ * knob 4: waves per workgroup (1, 2, 4, 8 or 16; fp8 rows: 4 or more); a tile is
+ *         waves x rows-per-wave rows, at least 4
  * knob 5: 1 = irm_cdc_chunk always selects cuts with the serial walk (else only for
  *         requests with more than 4096 candidate positions)
  * knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; its tile is 32 times that) */
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
 /* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples
- * pairs of HIP events; while enabled, every `every`-th irm_reattach (the first
- * one included) records one pair around its row kernel on the caller's stream
- * (calls past max_samples are not sampled).  irm_ctx_profile_end waits for the stream, returns the summed
+ * pairs of HIP events; while enabled, every `every`-th irm_reattach,
+ * irm_reattach_kr, irm_reattach_ref or irm_attend_ref (the first one included)
+ * records one pair around its row kernel(s) on the caller's stream (calls past
+ * max_samples are not sampled).  irm_ctx_profile_end waits for the stream, returns the summed
  * elapsed milliseconds and the number of samples, destroys the events and
  * disables sampling.  Not for use under graph capture. */
 irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples, uint32_t every);
