@@ -323,7 +323,9 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing, does not
  * synchronise.  In an IRM_ROW_FP8 context d_pool_layer holds 656-byte rows: c_KV element d is
  * then the E4M3 value (finite-only form, largest 448) of byte d times the fp32 scale of its
- * block of 128, rounded once to bf16 while the rows are staged; everything else is the same. */
+ * block of 128.  The codes enter the products exactly (as bf16); a score's four block sums
+ * take their scales in fp32, and on the output side the scale goes into the softmax
+ * numerator before that is rounded to bf16.  Everything else is the same. */
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
 irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
                           const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,

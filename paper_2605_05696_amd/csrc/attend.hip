@@ -197,21 +197,20 @@ __device__ __forceinline__ int32_t att_fire_rows(u32x4 (&vc)[ATT_NV(F8)], float 
     return ad.hit;
 }
 
-// 16 E4M3 codes times their block's scale, rounded once to bf16: two 16-byte vectors
-typedef float att_f32x2 __attribute__((ext_vector_type(2)));
+// 16 E4M3 codes as bf16, exactly (three fraction bits fit): two 16-byte vectors.  The block scales
+// are not applied here but by the compute waves, to the score sums of a block in fp32 and to the
+// softmax numerators: one conversion per two codes is all the fetch waves spend (with the multiply
+// and the rounding here, they were what bounded the kernel).  The scaled conversion takes only the
+// exponent of its scale operand (measured), so it is used with 1.
 typedef __bf16 att_bf16x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void att_dequant16(u32x4 codes, float scale, u32x4 &lo, u32x4 &hi)
+__device__ __forceinline__ void att_codes16(u32x4 codes, u32x4 &lo, u32x4 &hi)
 {
     const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
     uint32_t o[8];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        att_f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], false);    // codes 0, 1 of the word
-        att_f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], true);     // codes 2, 3
-        a *= scale;
-        b *= scale;
-        o[2 * k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, att_bf16x2));
-        o[2 * k + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, att_bf16x2));
+        o[2 * k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)w[k], 1.0f, false));
+        o[2 * k + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)w[k], 1.0f, true));
     }
     lo = u32x4{o[0], o[1], o[2], o[3]};
     hi = u32x4{o[4], o[5], o[6], o[7]};
@@ -256,17 +255,20 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_NV(F8)], const flo
     const u32x4 zero = {0, 0, 0, 0};
     // two base addresses, the rest are immediate offsets of the LDS stores
     if (F8) {
-        // staged as bf16: the compute half sees the same tile whatever the pool holds
+        // the codes staged as bf16 in the bf16 rows' layout; the four block scales of a row go into the
+        // 16 bytes of padding behind its 576 elements
         const uint32_t sub = lane >> 5, vec = lane & 31u;
         uint16_t *at = kt + (cw + 4u * sub) * ATT_KROW + vec * 16u;
+        float *scale_at = (float *)(kt + (cw + 4u * sub) * ATT_KROW + 576u) + (vec >> 3);
         const int32_t *rows = sm->row[slot] + cw + 4u * sub;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             u32x4 w0, w1;
-            att_dequant16(vc[i], sc[i], w0, w1);
+            att_codes16(vc[i], w0, w1);
             const bool live = rows[8 * i] >= 0;
             *(u32x4 *)(at + 8 * i * ATT_KROW) = live ? w0 : zero;
             *(u32x4 *)(at + 8 * i * ATT_KROW + 8) = live ? w1 : zero;
+            if ((vec & 7u) == 0) scale_at[8 * i * (ATT_KROW / 2)] = live ? sc[i] : 0.0f;
         }
     } else {
         uint16_t *lo = kt + cw * ATT_KROW + lane * 8u, *hi = lo + 32u * ATT_KROW;
@@ -482,22 +484,61 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         // latency adds up.
         const uint16_t *krow = sm->k[cur] + (32u * tg + lm) * ATT_KROW + 8u * lq;
         f32x4 sa = {0, 0, 0, 0}, sa2 = {0, 0, 0, 0}, sb = {0, 0, 0, 0}, sb2 = {0, 0, 0, 0};
+        f32x4 sca[4], scb[4];                               // fp8 rows: the block scales of this lane's 8 tokens
+        if constexpr (F8) {
+            // codes are staged unscaled: the c_KV part of a score is summed per block of 128 dims (four
+            // k-steps) and each block sum takes its token's scale, in fp32; the k_r part has none
+            f32x4 ba[4], bb[4];
 #pragma unroll
-        for (int kk = 0; kk < ATT_KSTEPS; kk += 2) {
-            const u16x8 a0 = *(const u16x8 *)(krow + 32 * kk), a1 = *(const u16x8 *)(krow + 32 * kk + 32);
-            const u16x8 b0 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk);
-            const u16x8 b1 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk + 32);
-            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0),
-                                                         __builtin_bit_cast(bf16x8, qb[kk]), sa, 0, 0, 0);
-            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b0),
-                                                         __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
-            sa2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1),
-                                                          __builtin_bit_cast(bf16x8, qb[kk + 1]), sa2, 0, 0, 0);
-            sb2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b1),
-                                                          __builtin_bit_cast(bf16x8, qb[kk + 1]), sb2, 0, 0, 0);
+            for (int blk = 0; blk < 4; ++blk) {
+                ba[blk] = f32x4{0, 0, 0, 0};
+                bb[blk] = f32x4{0, 0, 0, 0};
+            }
+#pragma unroll
+            for (int kk = 0; kk < ATT_KSTEPS; ++kk) {
+                const u16x8 a0 = *(const u16x8 *)(krow + 32 * kk);
+                const u16x8 b0 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk);
+                if (kk < 16) {
+                    ba[kk >> 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, qb[kk]), ba[kk >> 2], 0, 0, 0);
+                    bb[kk >> 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8, b0), __builtin_bit_cast(bf16x8, qb[kk]), bb[kk >> 2], 0, 0, 0);
+                } else {
+                    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0),
+                                                                 __builtin_bit_cast(bf16x8, qb[kk]), sa, 0, 0, 0);
+                    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b0),
+                                                                 __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
+                }
+            }
+            const uint16_t *srow = sm->k[cur] + (32u * tg + 4u * lq) * ATT_KROW + 576u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                sca[i] = *(const f32x4 *)(srow + i * ATT_KROW);
+                scb[i] = *(const f32x4 *)(srow + (16 + i) * ATT_KROW);
+#pragma unroll
+                for (int blk = 0; blk < 4; ++blk) {
+                    sa[i] += ba[blk][i] * sca[i][blk];
+                    sb[i] += bb[blk][i] * scb[i][blk];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < ATT_KSTEPS; kk += 2) {
+                const u16x8 a0 = *(const u16x8 *)(krow + 32 * kk), a1 = *(const u16x8 *)(krow + 32 * kk + 32);
+                const u16x8 b0 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk);
+                const u16x8 b1 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk + 32);
+                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0),
+                                                             __builtin_bit_cast(bf16x8, qb[kk]), sa, 0, 0, 0);
+                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b0),
+                                                             __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
+                sa2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1),
+                                                              __builtin_bit_cast(bf16x8, qb[kk + 1]), sa2, 0, 0, 0);
+                sb2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b1),
+                                                              __builtin_bit_cast(bf16x8, qb[kk + 1]), sb2, 0, 0, 0);
+            }
+            sa += sa2;
+            sb += sb2;
         }
-        sa += sa2;
-        sb += sb2;
         // scores in the log2 domain; tokens that do not exist score -inf
         const int32_t *live = sm->row[k & (ATT_RING - 1u)] + 32u * tg + 4u * lq;
         float pv[8];
@@ -532,10 +573,27 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         // contraction slot 8 lq + i standing for token 4 lq + i (i < 4) or 16 + 4 lq + i - 4: the A
         // operand follows the same order, four consecutive tokens of one latent dim from each block of
         // 16, two transposing LDS reads (column pieces of the row-major tile).
-        const u16x8 pt = {(uint16_t)att_to_bf16(pv[0]), (uint16_t)att_to_bf16(pv[1]), (uint16_t)att_to_bf16(pv[2]),
-                          (uint16_t)att_to_bf16(pv[3]), (uint16_t)att_to_bf16(pv[4]), (uint16_t)att_to_bf16(pv[5]),
-                          (uint16_t)att_to_bf16(pv[6]), (uint16_t)att_to_bf16(pv[7])};
         const uint16_t *vsrc = sm->k[cur] + (32u * tg + 4u * lq + (lm >> 2)) * ATT_KROW + 256u * dh + 4u * (lm & 3u);
+        // fp8 rows: V = code x scale of the token's block, and a wave's 256 dims are two blocks: the scale
+        // goes into the numerators, one B operand per block
+        u16x8 pt[F8 ? 2 : 1];
+#pragma unroll
+        for (int h = 0; h < (F8 ? 2 : 1); ++h) {
+            float pw[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (F8) {
+                    pw[i] = pv[i] * (dh ? sca[i][2 + h] : sca[i][h]);
+                    pw[4 + i] = pv[4 + i] * (dh ? scb[i][2 + h] : scb[i][h]);
+                } else {
+                    pw[i] = pv[i];
+                    pw[4 + i] = pv[4 + i];
+                }
+            }
+            pt[h] = u16x8{(uint16_t)att_to_bf16(pw[0]), (uint16_t)att_to_bf16(pw[1]), (uint16_t)att_to_bf16(pw[2]),
+                          (uint16_t)att_to_bf16(pw[3]), (uint16_t)att_to_bf16(pw[4]), (uint16_t)att_to_bf16(pw[5]),
+                          (uint16_t)att_to_bf16(pw[6]), (uint16_t)att_to_bf16(pw[7])};
+        }
 #pragma unroll
         for (int blk = 0; blk < 16; ++blk) {
             const s16x4 v0 = att_lds_read_tr(vsrc + 16 * blk);
@@ -543,7 +601,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             const u16x8 vt = {(uint16_t)v0[0], (uint16_t)v0[1], (uint16_t)v0[2], (uint16_t)v0[3],
                               (uint16_t)v1[0], (uint16_t)v1[1], (uint16_t)v1[2], (uint16_t)v1[3]};
             o[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt),
-                                                             __builtin_bit_cast(bf16x8, pt), o[blk], 0, 0, 0);
+                                                             __builtin_bit_cast(bf16x8, pt[F8 ? blk >> 3 : 0]),
+                                                             o[blk], 0, 0, 0);
         }
         att_signal(&sm->consumed[cw], lane);                // this wave is done with tile k
     };
