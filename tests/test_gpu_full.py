@@ -404,9 +404,9 @@ def test_full_size_attend_ref_fp8_rows_c2():
         want, want_lse = orc.attend_ref(bits(q), bits(pool), w.dst_slots, w.req_offsets, row_h, hit_h, trig64, scale)
         err = np.abs(outs[0][0].cpu().numpy() - want)
         lerr = np.abs(outs[0][1].cpu().numpy() - want_lse).max()
-        # measured 3.3e-3 / 1e-4 / 1e-3: three times the bf16 rows' errors, as 512 more operands per score are
-        # rounded; a lost 64-token tile would still show (4e-3 on the lse), and so would a call that differs
-        assert err.max() < 6e-3 and err.mean() < 3e-4, (err.max(), err.mean())
-        assert lerr < 2e-3, lerr
+        # codes exact, scales in fp32 on the scores: the bf16 rows' bounds hold; a lost 64-token tile would
+        # show (4e-3 on the lse), and so would a call that differs
+        assert err.max() < 3e-3 and err.mean() < 2e-4, (err.max(), err.mean())
+        assert lerr < 6e-4, lerr
     finally:
         rig.close()
