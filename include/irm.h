@@ -309,7 +309,8 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * k_r is rotated in fp32 and rounded once to bf16 while the rows are staged on chip (the
  * values irm_reattach would have written); products in bf16 MFMA with fp32 accumulation.
  *   d_q            bf16 [n_req][n_heads][576] (latent-space query | rotary query), 16-byte aligned;
- *                  n_heads a multiple of 16, at most 128
+ *                  n_heads a multiple of 16, at most 128 (the pool rows are streamed once per
+ *                  16 heads, or once per 64 when n_heads is a multiple of 64 and the rows are bf16)
  *   d_pool_layer   one layer of the pool, rows of 576 bf16 (or fp8 rows, see below) at
  *                  pool_row_stride_bytes
  *   d_kv_slots     int32, d_kv_offsets uint32[n_req + 1]: CSR of every request's context slots

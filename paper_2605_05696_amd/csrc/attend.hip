@@ -308,7 +308,10 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_NV(F8)], const flo
 // the prologue and one at the end; in between the halves hand tiles over through LDS counters.
 // While the compute waves work on tile i in one LDS buffer, the fetch waves land tile i + 1,
 // requested a tile ago, in the other buffer as its rows arrive, and request tile i + 2 right after.
-template <bool F8, bool NT>
+// MULTI: four groups of 16 heads per workgroup, one per compute wave, each wave on all 64 tokens of a
+// tile: the tile is fetched and staged once for 64 heads (models with 64 or 128 heads), no wave needs
+// anything from another, and the kernel is bound by the LDS reads of the operands instead of HBM.
+template <bool F8, bool NT, bool MULTI>
 __global__ __launch_bounds__(512) void attend_ref_split(
     const uint16_t *__restrict__ q, uint32_t n_heads, const char *__restrict__ pool, uint64_t pool_stride,
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
@@ -319,7 +322,10 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     extern __shared__ __align__(16) unsigned char smem_raw[];
     att_smem *sm = (att_smem *)smem_raw;
     // head groups vary fastest: the workgroups that read the same rows are dispatched together
-    const uint32_t group = blockIdx.x, n_groups = gridDim.x, split = blockIdx.y, n_splits = gridDim.y;
+    const uint32_t split = blockIdx.y, n_splits = gridDim.y;
+    const uint32_t n_groups = MULTI ? 4u * gridDim.x : gridDim.x;
+    // head group of this workgroup; with MULTI, of this compute wave (read by compute waves only)
+    const uint32_t group = MULTI ? 4u * blockIdx.x + (irm_wave_id() & 3u) : blockIdx.x;
     const uint32_t b = blockIdx.z;
     const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
     const bool fetcher = wave >= 4;                         // uniform per wave
@@ -333,9 +339,12 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     const uint32_t tile1 = tile0 + per_split < n_tiles ? tile0 + per_split : n_tiles;
     const uint64_t part = ((uint64_t)b * n_groups + group) * n_splits + split;
     if (tile0 >= tile1) {                                   // nothing for this split (uniform exit)
-        float *po = part_o + part * (ATT_HEADS * 512u);
-        for (uint32_t i = threadIdx.x; i < ATT_HEADS * 512u; i += blockDim.x) po[i] = 0.0f;
-        if (threadIdx.x < ATT_HEADS) part_ml[part * ATT_HEADS + threadIdx.x] = make_float2(-INFINITY, 0.0f);
+        for (uint32_t g = 0; g < (MULTI ? 4u : 1u); ++g) {
+            const uint64_t pg = MULTI ? ((uint64_t)b * n_groups + 4u * blockIdx.x + g) * n_splits + split : part;
+            float *po = part_o + pg * (ATT_HEADS * 512u);
+            for (uint32_t i = threadIdx.x; i < ATT_HEADS * 512u; i += blockDim.x) po[i] = 0.0f;
+            if (threadIdx.x < ATT_HEADS) part_ml[pg * ATT_HEADS + threadIdx.x] = make_float2(-INFINITY, 0.0f);
+        }
         return;
     }
     // tiles are taken two at a time; an odd count is padded by a tile without tokens (its
@@ -456,6 +465,106 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         const uint16_t *qrow = q + ((uint64_t)b * n_heads + group * ATT_HEADS + lm) * 576u;
 #pragma unroll
         for (int kk = 0; kk < ATT_KSTEPS; ++kk) qb[kk] = *(const u16x8 *)(qrow + 32 * kk + 8 * lq);
+    }
+    if constexpr (MULTI) {
+        // this wave: head group `group`, all 64 tokens of every tile, all 512 output dims.
+        // O^T: lane holds O[head lm][dim 16 blk + 4 lq + i]
+        f32x4 o[32];
+#pragma unroll
+        for (int blk = 0; blk < 32; ++blk) o[blk] = f32x4{0, 0, 0, 0};
+        float m_run = -INFINITY, l_part = 0.0f;
+        int32_t next_sl, ref_a_row, ref_a_hit, ref_b_row = -2, ref_b_hit = -1;
+        {
+            int32_t sl[6], rw[5], ht[5];
+#pragma unroll
+            for (uint32_t k = 0; k < 6; ++k) sl[k] = refs_slot(tile0 + k);
+            next_sl = refs_slot(tile0 + 6);
+#pragma unroll
+            for (uint32_t k = 0; k < 5; ++k) refs_rows(tile0 + k, sl[k], rw[k], ht[k]);
+            refs_rows(tile0 + 5, sl[5], ref_a_row, ref_a_hit);
+#pragma unroll
+            for (uint32_t k = 0; k < 5; ++k) refs_publish(k, rw[k], ht[k]);
+        }
+        ATT_SYNC();                                         // prologue 1
+        ATT_SYNC();                                         // prologue 2
+        auto tile_step = [&](uint32_t tile, int32_t &req_row, int32_t &req_hit, int32_t pub_row, int32_t pub_hit) {
+            const uint32_t k = tile - tile0, cur = k & 1u;
+            refs_rows(tile + 6, next_sl, req_row, req_hit);
+            next_sl = refs_slot(tile + 7);
+            att_wait_all(sm->landed, k + 1u, lane, err);
+            // the tile in two halves of 32 tokens, each like a pair's share in the other variant: scores
+            // of two blocks of 16 tokens, one softmax step, then 32 blocks of 16 dims with 16x16x32 products
+#pragma nounroll
+            for (uint32_t th = 0; th < 2; ++th) {
+                const uint16_t *krow = sm->k[cur] + (32u * th + lm) * ATT_KROW + 8u * lq;
+                f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};     // registers are short here: one accumulator each
+#pragma unroll
+                for (int kk = 0; kk < ATT_KSTEPS; ++kk) {
+                    const u16x8 a0 = *(const u16x8 *)(krow + 32 * kk);
+                    const u16x8 b0 = *(const u16x8 *)(krow + 16 * ATT_KROW + 32 * kk);
+                    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0),
+                                                                 __builtin_bit_cast(bf16x8, qb[kk]), sa, 0, 0, 0);
+                    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b0),
+                                                                 __builtin_bit_cast(bf16x8, qb[kk]), sb, 0, 0, 0);
+                }
+                const int32_t *live = sm->row[k & (ATT_RING - 1u)] + 32u * th + 4u * lq;
+                float pv[8];
+                float tmax = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    pv[i] = live[i] >= 0 ? sa[i] * scale_log2 : -INFINITY;
+                    pv[4 + i] = live[16 + i] >= 0 ? sb[i] * scale_log2 : -INFINITY;
+                    tmax = fmaxf(tmax, fmaxf(pv[i], pv[4 + i]));
+                }
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+                tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+                const float m_new = fmaxf(m_run, tmax);
+                const float alpha = m_new == -INFINITY ? 1.0f : exp2f(m_run - m_new);
+                float psum = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    pv[i] = m_new == -INFINITY ? 0.0f : exp2f(pv[i] - m_new);
+                    psum += pv[i];
+                }
+                m_run = m_new;
+                l_part = l_part * alpha + psum;
+                if (__any(alpha != 1.0f)) {
+#pragma unroll
+                    for (int blk = 0; blk < 32; ++blk) o[blk] *= alpha;
+                }
+                if (th == 0) refs_publish((k + 5u) & (ATT_RING - 1u), pub_row, pub_hit);
+                const u16x8 pt = {(uint16_t)att_to_bf16(pv[0]), (uint16_t)att_to_bf16(pv[1]), (uint16_t)att_to_bf16(pv[2]),
+                                  (uint16_t)att_to_bf16(pv[3]), (uint16_t)att_to_bf16(pv[4]), (uint16_t)att_to_bf16(pv[5]),
+                                  (uint16_t)att_to_bf16(pv[6]), (uint16_t)att_to_bf16(pv[7])};
+                const uint16_t *vsrc = sm->k[cur] + (32u * th + 4u * lq + (lm >> 2)) * ATT_KROW + 4u * (lm & 3u);
+#pragma unroll
+                for (int blk = 0; blk < 32; ++blk) {
+                    const s16x4 v0 = att_lds_read_tr(vsrc + 16 * blk);
+                    const s16x4 v1 = att_lds_read_tr(vsrc + 16 * ATT_KROW + 16 * blk);
+                    const u16x8 vt = {(uint16_t)v0[0], (uint16_t)v0[1], (uint16_t)v0[2], (uint16_t)v0[3],
+                                      (uint16_t)v1[0], (uint16_t)v1[1], (uint16_t)v1[2], (uint16_t)v1[3]};
+                    o[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt),
+                                                                     __builtin_bit_cast(bf16x8, pt), o[blk], 0, 0, 0);
+                }
+            }
+            att_signal(&sm->consumed[cw], lane);
+        };
+        for (uint32_t pr = 0; pr < n_pairs; ++pr) {
+            const uint32_t tile = tile0 + 2u * pr;
+            tile_step(tile, ref_b_row, ref_b_hit, ref_a_row, ref_a_hit);
+            tile_step(tile + 1, ref_a_row, ref_a_hit, ref_b_row, ref_b_hit);
+        }
+        l_part += __shfl_xor(l_part, 16);
+        l_part += __shfl_xor(l_part, 32);
+        // every wave has its own heads: its partial result goes out as it is
+        float *po = part_o + part * (ATT_HEADS * 512u) + (uint64_t)lm * 512u + 4u * lq;
+#pragma unroll
+        for (int blk = 0; blk < 32; ++blk) *(f32x4 *)(po + 16 * blk) = o[blk];
+        if (lq == 0) part_ml[part * ATT_HEADS + lm] = make_float2(m_run, l_part);
+        __syncthreads();                                    // the fetch waves' three
+        __syncthreads();
+        __syncthreads();
+        return;
     }
     // Two waves share 32 of the tile's 64 tokens (tg) and split the latent dims (dh): both compute
     // the scores of their 32 tokens (the same instructions on the same data: the same bits), each
@@ -719,8 +828,12 @@ __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict_
 irm_status irm_attend_init(int device)
 {
     (void)device;
-    const void *kernels[4] = {(const void *)attend_ref_split<false, false>, (const void *)attend_ref_split<false, true>,
-                              (const void *)attend_ref_split<true, false>, (const void *)attend_ref_split<true, true>};
+    const void *kernels[6] = {(const void *)attend_ref_split<false, false, false>,
+                              (const void *)attend_ref_split<false, true, false>,
+                              (const void *)attend_ref_split<true, false, false>,
+                              (const void *)attend_ref_split<true, true, false>,
+                              (const void *)attend_ref_split<false, false, true>,
+                              (const void *)attend_ref_split<false, true, true>};
     for (const void *k : kernels)
         IRM_HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(att_smem)));
     return IRM_OK;
@@ -759,10 +872,17 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    const bool nt = n_groups == 1;                      // see att_ld
-    hipLaunchKernelGGL(f8 ? (nt ? attend_ref_split<true, true> : attend_ref_split<true, false>)
-                          : (nt ? attend_ref_split<false, true> : attend_ref_split<false, false>),
-                       dim3(n_groups, n_splits, n_req),
+    // bf16 rows and a multiple of 64 heads: four head groups per workgroup share the staged tiles
+    const bool multi = !f8 && n_groups % 4u == 0;
+    const uint32_t grid_x = multi ? n_groups / 4u : n_groups;
+    const bool nt = grid_x == 1;                        // see att_ld
+    void (*split_kernel)(const uint16_t *, uint32_t, const char *, uint64_t, uint64_t, const int32_t *,
+                         const uint32_t *, const int32_t *, const int32_t *, uint64_t, const float2 *, uint32_t,
+                         float, uint32_t, float *, float2 *, uint32_t *) =
+        multi ? (nt ? attend_ref_split<false, true, true> : attend_ref_split<false, false, true>)
+        : f8  ? (nt ? attend_ref_split<true, true, false> : attend_ref_split<true, false, false>)
+              : (nt ? attend_ref_split<false, true, false> : attend_ref_split<false, false, false>);
+    hipLaunchKernelGGL(split_kernel, dim3(grid_x, n_splits, n_req),
                        dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
                        d_kv_slots, d_kv_offsets, d_row_index, d_hit_index, dst_rows, (const float2 *)d_trig,

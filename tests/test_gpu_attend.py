@@ -96,7 +96,7 @@ def check(got, got_lse, want, want_lse, long_contexts=False, fp8=False):
 
 
 @pytest.mark.parametrize("name,n_heads,n_splits,pair_mode", [("c2", 16, 1, 0), ("c2", 16, 5, 1), ("c1", 32, 8, 0),
-                                                             ("c4", 16, 3, 0), ("c3", 128, 4, 1)])
+                                                             ("c4", 16, 3, 0), ("c3", 128, 4, 1), ("c2", 64, 3, 0)])
 def test_attend_ref_small_configs(name, n_heads, n_splits, pair_mode):
     w = wl.make_workload(name, orc.cdc_chunk, size="small")
     hits = oracle_front(w)["hits"]
@@ -113,6 +113,17 @@ def test_attend_ref_ragged_contexts_empty_and_short_requests():
     n = len(w.tokens)
     off = np.array([0, 0, 1, 64, 65, 200, 200, 4099, n], np.uint32)          # empty, 1, 63, 1, 135, empty, ...
     got, got_lse, want, want_lse = run_case(w, hits, 16, 4, 0, seed=12, kv_offsets=off)
+    check(got, got_lse, want, want_lse)
+    assert np.all(got[0] == 0) and np.all(got[5] == 0)
+
+
+def test_attend_ref_ragged_contexts_64_heads():
+    """The four-groups-per-workgroup variant on empty, short and ragged contexts."""
+    w = wl.make_workload("c2", orc.cdc_chunk, size="small")
+    hits = oracle_front(w)["hits"]
+    n = len(w.tokens)
+    off = np.array([0, 0, 1, 64, 65, 200, 200, 4099, n], np.uint32)
+    got, got_lse, want, want_lse = run_case(w, hits, 64, 4, 1, seed=14, kv_offsets=off)
     check(got, got_lse, want, want_lse)
     assert np.all(got[0] == 0) and np.all(got[5] == 0)
 
