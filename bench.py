@@ -377,8 +377,8 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
             kernel_n += n
     ctx_tokens = len(w0.tokens)                                  # every request attends over all of its tokens
     # a row is streamed once per 16 heads, or once per 64 when the library serves four head groups from one
-    # staged tile (bf16 rows, heads a multiple of 64)
-    groups = H // 64 if (H % 64 == 0 and ROW_BYTES == 1152) else H // 16
+    # staged tile (heads a multiple of 64)
+    groups = H // 64 if H % 64 == 0 else H // 16
     alg = ctx_tokens * ROW_BYTES * groups                        # per layer launch
     achieved = alg * kernel_n / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
     return {"metric": "attended context tokens/s (all layers), no-materialise scheme: front end + references + "

@@ -226,8 +226,29 @@ __device__ __forceinline__ void att_codes16(u32x4 codes, u32x4 &lo, u32x4 &hi)
     hi = u32x4{o[4], o[5], o[6], o[7]};
 }
 
-// rotate k_r in registers (fp32, one rounding to bf16), store the tile into LDS buffer `buf`
-template <bool F8>
+// 16 E4M3 codes times their block's scale, rounded once to bf16 (for the variant whose compute waves
+// are the busier half and take the tile as if it came from bf16 rows)
+typedef float att_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void att_dequant16(u32x4 codes, float scale, u32x4 &lo, u32x4 &hi)
+{
+    const uint32_t w[4] = {codes.x, codes.y, codes.z, codes.w};
+    uint32_t o[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        att_f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], false);    // codes 0, 1 of the word
+        att_f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[k], true);     // codes 2, 3
+        a *= scale;
+        b *= scale;
+        o[2 * k] = __builtin_bit_cast(uint32_t, __builtin_convertvector(a, att_bf16x2));
+        o[2 * k + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(b, att_bf16x2));
+    }
+    lo = u32x4{o[0], o[1], o[2], o[3]};
+    hi = u32x4{o[4], o[5], o[6], o[7]};
+}
+
+// rotate k_r in registers (fp32, one rounding to bf16), store the tile into LDS buffer `buf`;
+// FOLD (fp8 rows): leave the block scales to the compute waves
+template <bool F8, bool FOLD>
 __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_NV(F8)], const float (&sc)[8], const f32x4 (&t4)[4],
                                               int32_t hit, att_smem *sm, uint32_t slot, uint32_t buf,
                                               const att_args &a, uint32_t cw, uint32_t lane, uint32_t ct)
@@ -274,11 +295,12 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_NV(F8)], const flo
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             u32x4 w0, w1;
-            att_codes16(vc[i], w0, w1);
+            if (FOLD) att_codes16(vc[i], w0, w1);
+            else att_dequant16(vc[i], sc[i], w0, w1);
             const bool live = rows[8 * i] >= 0;
             *(u32x4 *)(at + 8 * i * ATT_KROW) = live ? w0 : zero;
             *(u32x4 *)(at + 8 * i * ATT_KROW + 8) = live ? w1 : zero;
-            if ((vec & 7u) == 0) scale_at[8 * i * (ATT_KROW / 2)] = live ? sc[i] : 0.0f;
+            if (FOLD && (vec & 7u) == 0) scale_at[8 * i * (ATT_KROW / 2)] = live ? sc[i] : 0.0f;
         }
     } else {
         uint16_t *lo = kt + cw * ATT_KROW + lane * 8u, *hi = lo + 32u * ATT_KROW;
@@ -377,7 +399,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             f32x4 t42[4];
             int32_t hit2 = att_fire_rows<F8, NT>(r2, sc2, t42, ad, a, lane, ct);
             att_addr_rows<F8>(ad, sm, 2, a, cw, lane, ct);
-            att_land_rows<F8>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
+            att_land_rows<F8, F8 && !MULTI>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
             hit = att_fire_rows<F8, NT>(r, sc, t4, ad, a, lane, ct);
             att_addr_rows<F8>(ad, sm, 3, a, cw, lane, ct);
             ATT_SYNC();                                     // prologue 2: counters are zero, tile 0 is in place
@@ -385,21 +407,21 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             uint32_t t = 1;                                 // t = tile - tile0; odd tiles use the second set
             for (; t + 1u < 2u * n_pairs; t += 2u) {
                 att_wait_all(sm->consumed, t - 1u, lane, err);
-                att_land_rows<F8>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
+                att_land_rows<F8, F8 && !MULTI>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
                 att_signal(&sm->landed[cw], lane);
                 hit2 = att_fire_rows<F8, NT>(r2, sc2, t42, ad, a, lane, ct);           // tile t + 2
                 att_addr_rows<F8>(ad, sm, (t + 3u) & RM, a, cw, lane, ct);
                 att_wait_all(sm->consumed, t, lane, err);
-                att_land_rows<F8>(r, sc, t4, hit, sm, (t + 1u) & RM, 0u, a, cw, lane, ct);
+                att_land_rows<F8, F8 && !MULTI>(r, sc, t4, hit, sm, (t + 1u) & RM, 0u, a, cw, lane, ct);
                 att_signal(&sm->landed[cw], lane);
                 hit = att_fire_rows<F8, NT>(r, sc, t4, ad, a, lane, ct);               // tile t + 3
                 att_addr_rows<F8>(ad, sm, (t + 4u) & RM, a, cw, lane, ct);
             }
             att_wait_all(sm->consumed, t - 1u, lane, err);  // the last tile, 2 n_pairs - 1: odd
-            att_land_rows<F8>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
+            att_land_rows<F8, F8 && !MULTI>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
             att_signal(&sm->landed[cw], lane);
         } else {
-            att_land_rows<F8>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
+            att_land_rows<F8, F8 && !MULTI>(r, sc, t4, hit, sm, 0, 0, a, cw, lane, ct);
             hit = att_fire_rows<F8, NT>(r, sc, t4, ad, a, lane, ct);                   // tile 1
             att_addr_rows<F8>(ad, sm, 2, a, cw, lane, ct);
             ATT_SYNC();                                     // prologue 2: counters are zero, tile 0 is in place
@@ -409,7 +431,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
                 // after landing t, so that it has a whole tile's time to arrive (more than 18 loads
                 // in flight per lane slow the stream down: measured).
                 att_wait_all(sm->consumed, t - 1u, lane, err);
-                att_land_rows<F8>(r, sc, t4, hit, sm, t & RM, t & 1u, a, cw, lane, ct);
+                att_land_rows<F8, F8 && !MULTI>(r, sc, t4, hit, sm, t & RM, t & 1u, a, cw, lane, ct);
                 att_signal(&sm->landed[cw], lane);
                 hit = att_fire_rows<F8, NT>(r, sc, t4, ad, a, lane, ct);               // tile t + 1
                 att_addr_rows<F8>(ad, sm, (t + 2u) & RM, a, cw, lane, ct);
@@ -828,12 +850,14 @@ __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict_
 irm_status irm_attend_init(int device)
 {
     (void)device;
-    const void *kernels[6] = {(const void *)attend_ref_split<false, false, false>,
+    const void *kernels[8] = {(const void *)attend_ref_split<false, false, false>,
                               (const void *)attend_ref_split<false, true, false>,
                               (const void *)attend_ref_split<true, false, false>,
                               (const void *)attend_ref_split<true, true, false>,
                               (const void *)attend_ref_split<false, false, true>,
-                              (const void *)attend_ref_split<false, true, true>};
+                              (const void *)attend_ref_split<false, true, true>,
+                              (const void *)attend_ref_split<true, false, true>,
+                              (const void *)attend_ref_split<true, true, true>};
     for (const void *k : kernels)
         IRM_HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(att_smem)));
     return IRM_OK;
@@ -872,16 +896,17 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    // bf16 rows and a multiple of 64 heads: four head groups per workgroup share the staged tiles
-    const bool multi = !f8 && n_groups % 4u == 0;
+    // a multiple of 64 heads: four head groups per workgroup share the staged tiles
+    const bool multi = n_groups % 4u == 0;
     const uint32_t grid_x = multi ? n_groups / 4u : n_groups;
     const bool nt = grid_x == 1;                        // see att_ld
     void (*split_kernel)(const uint16_t *, uint32_t, const char *, uint64_t, uint64_t, const int32_t *,
                          const uint32_t *, const int32_t *, const int32_t *, uint64_t, const float2 *, uint32_t,
                          float, uint32_t, float *, float2 *, uint32_t *) =
-        multi ? (nt ? attend_ref_split<false, true, true> : attend_ref_split<false, false, true>)
-        : f8  ? (nt ? attend_ref_split<true, true, false> : attend_ref_split<true, false, false>)
-              : (nt ? attend_ref_split<false, true, false> : attend_ref_split<false, false, false>);
+        multi ? (f8 ? (nt ? attend_ref_split<true, true, true> : attend_ref_split<true, false, true>)
+                    : (nt ? attend_ref_split<false, true, true> : attend_ref_split<false, false, true>))
+              : (f8 ? (nt ? attend_ref_split<true, true, false> : attend_ref_split<true, false, false>)
+                    : (nt ? attend_ref_split<false, true, false> : attend_ref_split<false, false, false>));
     hipLaunchKernelGGL(split_kernel, dim3(grid_x, n_splits, n_req),
                        dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
