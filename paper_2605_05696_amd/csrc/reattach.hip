@@ -418,7 +418,7 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
     uint64_t kr_stride, uint64_t kr_rows, const int32_t *__restrict__ dst_slots,
     const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
-    int32_t *__restrict__ ckv_index, uint32_t pair_mode, uint32_t *err)
+    int32_t *__restrict__ ckv_index, uint32_t pair_mode, uint32_t xcd_ranges, uint32_t *err)
 {
     // Lane l of a wave holds 16-byte vector v = l % 8 of row l / 8 (and of row 8 + l / 8):
     // a wave-wide access covers eight whole 128-byte rows, contiguous when the rows are.
@@ -428,8 +428,11 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
     const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
     const uint32_t v = lane & 7, jq = v & 3;
     const float sgn = v < 4 ? -1.0f : 1.0f;            // first half: a c - b s; partner: b c + a s
+    const uint32_t per_xcd = (n_tiles + 7) >> 3;       // as in reattach_rows
 #pragma nounroll
-    for (uint32_t ti = blockIdx.x; ti < n_tiles; ti += gridDim.x) {
+    for (uint32_t x = blockIdx.x; x < per_xcd * 8; x += gridDim.x) {
+        const uint32_t ti = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
+        if (ti >= n_tiles) continue;
         const irm_tile *tp = tiles + ti;
         const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
         const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
@@ -497,13 +500,14 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
     void (*kr_kernel)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t, const int32_t *,
-                      const irm_tile *, const uint32_t *, const float2 *, int32_t *, uint32_t, uint32_t *) =
+                      const irm_tile *, const uint32_t *, const float2 *, int32_t *, uint32_t, uint32_t,
+                      uint32_t *) =
         ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2>
         : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4> : reattach_kr_rows<8>;
-    hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)tile_slots, ctx->cfg.n_layers), dim3(256), 0, s,
+    hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)((tile_slots + 7) / 8 * 8), ctx->cfg.n_layers), dim3(256), 0, s,
                        d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
                        kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index,
-                       ctx->cfg.pair_mode, ctx->d_err);
+                       ctx->cfg.pair_mode, ctx->xcd_ranges, ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;
