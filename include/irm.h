@@ -320,8 +320,10 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  *   n_splits       workgroups per request and 16 heads (split of the context, merged afterwards)
  *   d_workspace    irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits) bytes, 16-byte aligned
  *   d_out          float[n_req][n_heads][512];  d_lse float[n_req][n_heads]
- * A request without context gives out = 0, lse = -inf.  A slot, row or hit index out of
- * range leaves that token out and raises IRM_FLAG_ROW_RANGE.  Allocates nothing, does not
+ * A request without context gives out = 0, lse = -inf (so does one whose offsets run
+ * backwards, which also raises IRM_FLAG_BAD_CHUNK; d_kv_slots must hold d_kv_offsets[n_req]
+ * entries).  A slot, row or hit index out of range leaves that token out and raises
+ * IRM_FLAG_ROW_RANGE.  Allocates nothing, does not
  * synchronise.  In an IRM_ROW_FP8 context d_pool_layer holds 656-byte rows: c_KV element d is
  * then the E4M3 value (finite-only form, largest 448) of byte d times the fp32 scale of its
  * block of 128.  The codes enter the products exactly (as bf16); a score's four block sums

@@ -354,7 +354,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     const uint32_t cw = wave & 3u;                          // index among the waves of its half
     const uint32_t ct = threadIdx.x & 255u;                 // lane index within its half
     const uint32_t begin = kv_offsets[b], end = kv_offsets[b + 1];
-    const uint32_t n_tok = end - begin;
+    if (end < begin && threadIdx.x == 0) atomicOr(err, IRM_FLAG_BAD_CHUNK);   // offsets that run backwards: no context
+    const uint32_t n_tok = end >= begin ? end - begin : 0u;
     const uint32_t n_tiles = (n_tok + ATT_TILE - 1) / ATT_TILE;
     const uint32_t per_split = (n_tiles + n_splits - 1) / n_splits;
     const uint32_t tile0 = split * per_split;

@@ -133,6 +133,30 @@ def test_attend_ref_ragged_contexts_64_heads():
     assert np.all(got[0] == 0) and np.all(got[5] == 0)
 
 
+def test_attend_ref_offsets_that_run_backwards_give_no_context_and_a_flag():
+    w = wl.make_workload("c2", orc.cdc_chunk, size="small")
+    s = Session.for_workload(w, DEV)
+    try:
+        pool = wl.kv_pool_torch(1, w.src_rows, 1, DEV)[0]
+        n = 300
+        slots = torch.arange(n, dtype=torch.int32, device=DEV)
+        row = torch.arange(w.dst_rows, dtype=torch.int32, device=DEV) % w.src_rows
+        hit = torch.full((w.dst_rows,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.zeros((1, 32, 2), dtype=torch.float32, device=DEV)
+        off = s.to_dev_u32(np.array([0, 200, 100, n], np.uint32))        # request 1 runs backwards
+        q = torch.randn((3, 16, 576), device=DEV, generator=torch.Generator(DEV).manual_seed(2)).to(torch.bfloat16)
+        out = torch.full((3, 16, 512), 7.0, dtype=torch.float32, device=DEV)
+        lse = torch.full((3, 16), 7.0, dtype=torch.float32, device=DEV)
+        ws = torch.empty(B.irm_attend_ref_workspace_bytes(3, 16, 2), dtype=torch.uint8, device=DEV)
+        B.irm_attend_ref(s.ctx, q, pool, ROW * 2, slots, off, row, hit, trig, SCALE, 2, ws, out, lse)
+        torch.cuda.synchronize()
+        assert s.error_flags() == B.IRM_FLAG_BAD_CHUNK
+        assert torch.all(out[1] == 0) and torch.all(torch.isneginf(lse[1]))
+        assert torch.all(torch.isfinite(lse[0])) and torch.all(torch.isfinite(lse[2])) and float(out[0].abs().max()) > 0
+    finally:
+        s.close()
+
+
 def test_attend_ref_rotation_is_applied():
     """Short contexts make the softmax peaky, so leaving the rotation out moves the result by far
     more than the tolerance: guards against a kernel that skips the rotate-on-load and a test
