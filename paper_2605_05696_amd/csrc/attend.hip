@@ -23,6 +23,11 @@
 //                       LDS reads (column pieces of the row-major tile)
 //       At the end the two token groups' (max, sum, O) meet once in LDS.  Every KV byte is read
 //       from HBM once per head group.
+//       With a multiple of 64 heads (MULTI) a workgroup serves four head groups instead, one per
+//       compute wave, each wave on all 64 tokens and all 512 dims of a tile: a row is then read
+//       from HBM once per 64 heads.
+//       Pools of fp8 rows (F8: 512 E4M3 codes | four fp32 block scales | k_r) differ in the fetch
+//       waves only, up to the block scales, which the compute waves apply (MULTI: the fetch waves).
 //   attend_ref_merge   combines the splits' (max, sum, O) into out and lse.
 #include "irm_internal.hpp"
 
