@@ -376,9 +376,9 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
             kernel_ms += ms
             kernel_n += n
     ctx_tokens = len(w0.tokens)                                  # every request attends over all of its tokens
-    # a row is streamed once per 16 heads, or once per 64 when the library serves four head groups from one
-    # staged tile (heads a multiple of 64)
-    groups = H // 64 if H % 64 == 0 else H // 16
+    # a row is streamed once per workgroup pass: 64 heads when the heads are a multiple of 64 (four head groups
+    # share every staged tile), 32 when a multiple of 32, else 16
+    groups = H // 64 if H % 64 == 0 else H // 32 if H % 32 == 0 else H // 16
     alg = ctx_tokens * ROW_BYTES * groups                        # per layer launch
     achieved = alg * kernel_n / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
     return {"metric": "attended context tokens/s (all layers), no-materialise scheme: front end + references + "

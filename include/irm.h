@@ -310,7 +310,7 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * values irm_reattach would have written); products in bf16 MFMA with fp32 accumulation.
  *   d_q            bf16 [n_req][n_heads][576] (latent-space query | rotary query), 16-byte aligned;
  *                  n_heads a multiple of 16, at most 128 (the pool rows are streamed once per
- *                  16 heads, or once per 64 when n_heads is a multiple of 64)
+ *                  16 heads, or once per 32 / 64 when n_heads is a multiple of 32 / 64)
  *   d_pool_layer   one layer of the pool, rows of 576 bf16 (or fp8 rows, see below) at
  *                  pool_row_stride_bytes
  *   d_kv_slots     int32, d_kv_offsets uint32[n_req + 1]: CSR of every request's context slots
@@ -328,7 +328,7 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * then the E4M3 value (finite-only form, largest 448) of byte d times the fp32 scale of its
  * block of 128.  The codes enter the products exactly (as bf16); a score's four block sums
  * take their scales in fp32, and on the output side the scale goes into the softmax
- * numerator before that is rounded to bf16.  (With a multiple of 64 heads the elements are
+ * numerator before that is rounded to bf16.  (With a multiple of 32 heads the elements are
  * scaled and rounded once to bf16 as the rows are staged instead.)  Everything else is the
  * same. */
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);

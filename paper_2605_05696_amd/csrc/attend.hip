@@ -23,11 +23,11 @@
 //                       LDS reads (column pieces of the row-major tile)
 //       At the end the two token groups' (max, sum, O) meet once in LDS.  Every KV byte is read
 //       from HBM once per head group.
-//       With a multiple of 64 heads (MULTI) a workgroup serves four head groups instead, one per
+//       With a multiple of 64 heads a workgroup serves four head groups instead, one per
 //       compute wave, each wave on all 64 tokens and all 512 dims of a tile: a row is then read
-//       from HBM once per 64 heads.
+//       from HBM once per 64 heads (a multiple of 32: two groups, two waves each).
 //       Pools of fp8 rows (F8: 512 E4M3 codes | four fp32 block scales | k_r) differ in the fetch
-//       waves only, up to the block scales, which the compute waves apply (MULTI: the fetch waves).
+//       waves only, up to the block scales, which the compute waves apply (several groups: the fetch waves).
 //   attend_ref_merge   combines the splits' (max, sum, O) into out and lse.
 #include "irm_internal.hpp"
 
@@ -65,8 +65,8 @@ __device__ __forceinline__ uint32_t att_to_bf16(float x)
 struct att_smem {
     uint16_t k[2][ATT_TILE * ATT_KROW]; // staged rows, k_r rotated: the tile in work and the next one;
                                         // at the end the compute waves' partial outputs (fp32)
-    float wmax[2 * ATT_HEADS];          // per token group (pair of compute waves) and head: running maximum at the end
-    float wsum[2 * ATT_HEADS];          // ... and sum
+    float wmax[4 * ATT_HEADS];          // per token group (or compute wave) and head: running maximum at the end
+    float wsum[4 * ATT_HEADS];          // ... and sum
     int32_t row[ATT_RING][ATT_TILE];    // pool row of each tile token, -1 = no token; slot = tile mod ATT_RING
     int32_t hit[ATT_RING][ATT_TILE];    // rotation of each tile token, -1 = none
     uint32_t landed[4];                 // per fetch wave: tiles it has landed so far
@@ -335,10 +335,12 @@ __device__ __forceinline__ void att_land_rows(u32x4 (&vc)[ATT_NV(F8)], const flo
 // the prologue and one at the end; in between the halves hand tiles over through LDS counters.
 // While the compute waves work on tile i in one LDS buffer, the fetch waves land tile i + 1,
 // requested a tile ago, in the other buffer as its rows arrive, and request tile i + 2 right after.
-// MULTI: four groups of 16 heads per workgroup, one per compute wave, each wave on all 64 tokens of a
-// tile: the tile is fetched and staged once for 64 heads (models with 64 or 128 heads), no wave needs
-// anything from another, and the kernel is bound by the LDS reads of the operands instead of HBM.
-template <bool F8, bool NT, bool MULTI>
+// GPW, head groups per workgroup.  1: the four compute waves share one group's tile as described above.
+// 4: one group per compute wave, each wave on all 64 tokens of a tile: the tile is fetched and staged
+// once for 64 heads (models with 64 or 128 heads), no wave needs anything from another, and the kernel is
+// bound by the LDS reads of the operands instead of HBM.  2: two waves per group, 32 tokens of the tile
+// each, their results joined at the end (32 heads per pass).
+template <bool F8, bool NT, int GPW>
 __global__ __launch_bounds__(512) void attend_ref_split(
     const uint16_t *__restrict__ q, uint32_t n_heads, const char *__restrict__ pool, uint64_t pool_stride,
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
@@ -350,9 +352,11 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     att_smem *sm = (att_smem *)smem_raw;
     // head groups vary fastest: the workgroups that read the same rows are dispatched together
     const uint32_t split = blockIdx.y, n_splits = gridDim.y;
-    const uint32_t n_groups = MULTI ? 4u * gridDim.x : gridDim.x;
-    // head group of this workgroup; with MULTI, of this compute wave (read by compute waves only)
-    const uint32_t group = MULTI ? 4u * blockIdx.x + (irm_wave_id() & 3u) : blockIdx.x;
+    constexpr bool MULTI = GPW > 1;
+    const uint32_t n_groups = (uint32_t)GPW * gridDim.x;
+    // head group of this workgroup; with several, of this compute wave (read by compute waves only)
+    const uint32_t group = GPW == 4 ? 4u * blockIdx.x + (irm_wave_id() & 3u)
+                           : GPW == 2 ? 2u * blockIdx.x + ((irm_wave_id() & 3u) >> 1) : blockIdx.x;
     const uint32_t b = blockIdx.z;
     const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
     const bool fetcher = wave >= 4;                         // uniform per wave
@@ -367,8 +371,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     const uint32_t tile1 = tile0 + per_split < n_tiles ? tile0 + per_split : n_tiles;
     const uint64_t part = ((uint64_t)b * n_groups + group) * n_splits + split;
     if (tile0 >= tile1) {                                   // nothing for this split (uniform exit)
-        for (uint32_t g = 0; g < (MULTI ? 4u : 1u); ++g) {
-            const uint64_t pg = MULTI ? ((uint64_t)b * n_groups + 4u * blockIdx.x + g) * n_splits + split : part;
+        for (uint32_t g = 0; g < (uint32_t)GPW; ++g) {
+            const uint64_t pg = ((uint64_t)b * n_groups + (uint32_t)GPW * blockIdx.x + g) * n_splits + split;
             float *po = part_o + pg * (ATT_HEADS * 512u);
             for (uint32_t i = threadIdx.x; i < ATT_HEADS * 512u; i += blockDim.x) po[i] = 0.0f;
             if (threadIdx.x < ATT_HEADS) part_ml[pg * ATT_HEADS + threadIdx.x] = make_float2(-INFINITY, 0.0f);
@@ -523,7 +527,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             // the tile in two halves of 32 tokens, each like a pair's share in the other variant: scores
             // of two blocks of 16 tokens, one softmax step, then 32 blocks of 16 dims with 16x16x32 products
 #pragma nounroll
-            for (uint32_t th = 0; th < 2; ++th) {
+            for (uint32_t th = (GPW == 2 ? cw & 1u : 0u); th < (GPW == 2 ? (cw & 1u) + 1u : 2u); ++th) {
                 const uint16_t *krow = sm->k[cur] + (32u * th + lm) * ATT_KROW + 8u * lq;
                 f32x4 sa = {0, 0, 0, 0}, sb = {0, 0, 0, 0};     // registers are short here: one accumulator each
 #pragma unroll
@@ -560,7 +564,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
 #pragma unroll
                     for (int blk = 0; blk < 32; ++blk) o[blk] *= alpha;
                 }
-                if (th == 0) refs_publish((k + 5u) & (ATT_RING - 1u), pub_row, pub_hit);
+                if (GPW == 2 || th == 0) refs_publish((k + 5u) & (ATT_RING - 1u), pub_row, pub_hit);
                 const u16x8 pt = {(uint16_t)att_to_bf16(pv[0]), (uint16_t)att_to_bf16(pv[1]), (uint16_t)att_to_bf16(pv[2]),
                                   (uint16_t)att_to_bf16(pv[3]), (uint16_t)att_to_bf16(pv[4]), (uint16_t)att_to_bf16(pv[5]),
                                   (uint16_t)att_to_bf16(pv[6]), (uint16_t)att_to_bf16(pv[7])};
@@ -584,14 +588,46 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         }
         l_part += __shfl_xor(l_part, 16);
         l_part += __shfl_xor(l_part, 32);
-        // every wave has its own heads: its partial result goes out as it is
-        float *po = part_o + part * (ATT_HEADS * 512u) + (uint64_t)lm * 512u + 4u * lq;
+        if constexpr (GPW == 4) {
+            // every wave has its own heads: its partial result goes out as it is
+            float *po = part_o + part * (ATT_HEADS * 512u) + (uint64_t)lm * 512u + 4u * lq;
 #pragma unroll
-        for (int blk = 0; blk < 32; ++blk) *(f32x4 *)(po + 16 * blk) = o[blk];
-        if (lq == 0) part_ml[part * ATT_HEADS + lm] = make_float2(m_run, l_part);
-        __syncthreads();                                    // the fetch waves' three
-        __syncthreads();
-        __syncthreads();
+            for (int blk = 0; blk < 32; ++blk) *(f32x4 *)(po + 16 * blk) = o[blk];
+            if (lq == 0) part_ml[part * ATT_HEADS + lm] = make_float2(m_run, l_part);
+            __syncthreads();                                // the fetch waves' three
+            __syncthreads();
+            __syncthreads();
+        } else {
+            // two waves per head group, one per half of every tile: join them through LDS
+            const uint32_t gl = cw >> 1, th = cw & 1u;      // group within the workgroup, token half
+            if (lq == 0) {
+                sm->wmax[cw * ATT_HEADS + lm] = m_run;
+                sm->wsum[cw * ATT_HEADS + lm] = l_part;
+            }
+            __syncthreads();                                // every tile worked off: the tile buffers are free
+            const float m0 = sm->wmax[(2u * gl) * ATT_HEADS + lm], m1 = sm->wmax[(2u * gl + 1u) * ATT_HEADS + lm];
+            const float m_all = fmaxf(m0, m1);
+            const float l_all = (m0 == -INFINITY ? 0.0f : sm->wsum[(2u * gl) * ATT_HEADS + lm] * exp2f(m0 - m_all)) +
+                                (m1 == -INFINITY ? 0.0f : sm->wsum[(2u * gl + 1u) * ATT_HEADS + lm] * exp2f(m1 - m_all));
+            const float mine = m_run == -INFINITY ? 0.0f : exp2f(m_run - m_all);
+            float *obuf = (float *)sm->k;                   // [4 waves][16 heads][ATT_OROW]
+            {
+                float *at = obuf + ((uint64_t)cw * ATT_HEADS + lm) * ATT_OROW + 4u * lq;
+#pragma unroll
+                for (int blk = 0; blk < 32; ++blk) *(f32x4 *)(at + 16 * blk) = o[blk] * mine;
+            }
+            __syncthreads();
+            // the two waves of a group sum its two halves: 16 heads x 128 groups of four dims, 128 lanes
+            float *po = part_o + part * (ATT_HEADS * 512u);
+            const uint32_t t128 = 64u * th + lane;
+#pragma unroll
+            for (uint32_t e = 0; e < ATT_HEADS; ++e) {
+                const float *src = obuf + ((uint64_t)(2u * gl) * ATT_HEADS + e) * ATT_OROW + 4u * t128;
+                *(f32x4 *)(po + (uint64_t)e * 512u + 4u * t128) = *(const f32x4 *)src + *(const f32x4 *)(src + ATT_HEADS * ATT_OROW);
+            }
+            if (th == 0 && lq == 0) part_ml[part * ATT_HEADS + lm] = make_float2(m_all, l_all);
+            __syncthreads();                                // matches the fetch waves' third
+        }
         return;
     }
     // Two waves share 32 of the tile's 64 tokens (tg) and split the latent dims (dh): both compute
@@ -856,14 +892,13 @@ __global__ __launch_bounds__(512) void attend_ref_merge(const float *__restrict_
 irm_status irm_attend_init(int device)
 {
     (void)device;
-    const void *kernels[8] = {(const void *)attend_ref_split<false, false, false>,
-                              (const void *)attend_ref_split<false, true, false>,
-                              (const void *)attend_ref_split<true, false, false>,
-                              (const void *)attend_ref_split<true, true, false>,
-                              (const void *)attend_ref_split<false, false, true>,
-                              (const void *)attend_ref_split<false, true, true>,
-                              (const void *)attend_ref_split<true, false, true>,
-                              (const void *)attend_ref_split<true, true, true>};
+    const void *kernels[12] = {
+        (const void *)attend_ref_split<false, false, 1>, (const void *)attend_ref_split<false, true, 1>,
+        (const void *)attend_ref_split<true, false, 1>,  (const void *)attend_ref_split<true, true, 1>,
+        (const void *)attend_ref_split<false, false, 2>, (const void *)attend_ref_split<false, true, 2>,
+        (const void *)attend_ref_split<true, false, 2>,  (const void *)attend_ref_split<true, true, 2>,
+        (const void *)attend_ref_split<false, false, 4>, (const void *)attend_ref_split<false, true, 4>,
+        (const void *)attend_ref_split<true, false, 4>,  (const void *)attend_ref_split<true, true, 4>};
     for (const void *k : kernels)
         IRM_HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(att_smem)));
     return IRM_OK;
@@ -902,17 +937,22 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    // a multiple of 64 heads: four head groups per workgroup share the staged tiles
-    const bool multi = n_groups % 4u == 0;
-    const uint32_t grid_x = multi ? n_groups / 4u : n_groups;
+    // head groups per workgroup (they share the staged tiles): 4 with a multiple of 64 heads, else 2 with a
+    // multiple of 32, else 1
+    const uint32_t gpw = n_groups % 4u == 0 ? 4u : n_groups % 2u == 0 ? 2u : 1u;
+    const uint32_t grid_x = n_groups / gpw;
     const bool nt = grid_x == 1;                        // see att_ld
-    void (*split_kernel)(const uint16_t *, uint32_t, const char *, uint64_t, uint64_t, const int32_t *,
-                         const uint32_t *, const int32_t *, const int32_t *, uint64_t, const float2 *, uint32_t,
-                         float, uint32_t, float *, float2 *, uint32_t *) =
-        multi ? (f8 ? (nt ? attend_ref_split<true, true, true> : attend_ref_split<true, false, true>)
-                    : (nt ? attend_ref_split<false, true, true> : attend_ref_split<false, false, true>))
-              : (f8 ? (nt ? attend_ref_split<true, true, false> : attend_ref_split<true, false, false>)
-                    : (nt ? attend_ref_split<false, true, false> : attend_ref_split<false, false, false>));
+    typedef void (*split_kernel_t)(const uint16_t *, uint32_t, const char *, uint64_t, uint64_t, const int32_t *,
+                                   const uint32_t *, const int32_t *, const int32_t *, uint64_t, const float2 *,
+                                   uint32_t, float, uint32_t, float *, float2 *, uint32_t *);
+    static const split_kernel_t table[3][2][2] = {      // [groups per workgroup][fp8][streaming loads]
+        {{attend_ref_split<false, false, 1>, attend_ref_split<false, true, 1>},
+         {attend_ref_split<true, false, 1>, attend_ref_split<true, true, 1>}},
+        {{attend_ref_split<false, false, 2>, attend_ref_split<false, true, 2>},
+         {attend_ref_split<true, false, 2>, attend_ref_split<true, true, 2>}},
+        {{attend_ref_split<false, false, 4>, attend_ref_split<false, true, 4>},
+         {attend_ref_split<true, false, 4>, attend_ref_split<true, true, 4>}}};
+    const split_kernel_t split_kernel = table[gpw == 4 ? 2 : gpw == 2 ? 1 : 0][f8 ? 1 : 0][nt ? 1 : 0];
     hipLaunchKernelGGL(split_kernel, dim3(grid_x, n_splits, n_req),
                        dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
