@@ -52,6 +52,9 @@ def main() -> int:
                     help="row format of the pools: bf16 = 1152-byte rows (the headline); fp8 = 656-byte rows, c_KV "
                          "as 512 e4m3 bytes and four fp32 scales moved bit for bit, k_r in bf16 rotated as usual "
                          "(hit stage with --reattach full or kr, admit stage, attend stage: c_KV dequantised on load)")
+    ap.add_argument("--row-stride", type=int, default=0, metavar="BYTES",
+                    help="hit stage, --reattach full: row stride of both pools in bytes, a multiple of 16 "
+                         "(0 = packed rows; 768 puts every fp8 row on its own 128-byte lines)")
     ap.add_argument("--heads", type=int, default=16, help="attend stage: query heads (multiple of 16)")
     ap.add_argument("--linear-rows", action="store_true",
                     help="attend stage: every slot refers to the pool row of the same number (no rotation), i.e. "
@@ -135,13 +138,23 @@ def main() -> int:
                                    codes="quantised" if args.stage == "attend" else "random")
     else:
         src = wl.kv_pool_torch(L, w0.src_rows, wl.kv_seed(name), dev)
+    STRIDE = ROW_BYTES
+    if args.row_stride:
+        assert args.stage == "hit" and args.reattach == "full", "--row-stride: hit stage with --reattach full"
+        assert args.row_stride % 16 == 0 and args.row_stride >= ROW_BYTES, "--row-stride: a multiple of 16, >= the row"
+        STRIDE = args.row_stride
+        padded = torch.zeros((L, w0.src_rows, STRIDE // 2), dtype=src.dtype, device=dev)
+        padded[:, :, :ROW_BYTES // 2].copy_(src)
+        src = padded[:, :, :ROW_BYTES // 2]
+        del padded
     src_ptrs = B.layer_pointers(src)
     n_streams = max(1, args.streams)
     if n_streams > 1:
         assert args.reattach == "full" and args.stage != "admit" and n_var % n_streams == 0, \
             "--streams needs --reattach full, the hit or s1 stage, and --variants divisible by it"
     if args.reattach == "full":
-        dsts = [wl.sentinel_pool_torch(L, w0.dst_rows, dev, ROW_BYTES // 2) for _ in range(n_streams)]
+        dsts = [wl.sentinel_pool_torch(L, w0.dst_rows, dev, STRIDE // 2)[:, :, :ROW_BYTES // 2]
+                for _ in range(n_streams)]
         dst_ptrs_of = [B.layer_pointers(d) for d in dsts]
         dst, dst_ptrs = dsts[0], dst_ptrs_of[0]
         bytes_per_token_layer = 2 * ROW_BYTES                        # one row read, one written
@@ -207,11 +220,11 @@ def main() -> int:
         s, d = sessions[v], dev_in[v]
         if args.reattach == "full":
             st, dp = streams[v % n_streams], dst_ptrs_of[v % n_streams]   # a context stays on one stream
-            s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
-                    w0.src_rows, dp, ROW_BYTES, w0.dst_rows, d["buf"], st)
+            s.serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, STRIDE,
+                    w0.src_rows, dp, STRIDE, w0.dst_rows, d["buf"], st)
             if s1:
-                s.s1_serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, ROW_BYTES,
-                           w0.src_rows, dp, ROW_BYTES, w0.dst_rows, d["buf"], d["wbuf"], B.S1_ANCHOR_END, st)
+                s.s1_serve(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], src_ptrs, STRIDE,
+                           w0.src_rows, dp, STRIDE, w0.dst_rows, d["buf"], d["wbuf"], B.S1_ANCHOR_END, st)
         elif args.reattach == "ref":
             s.serve_ref(d["tokens"], d["req_offsets"], d["pos_base"], d["dst_slots"], w0.src_rows, row_index,
                         hit_index, d["trig"], d["buf"], stream)
@@ -282,7 +295,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}"
-                               + (", fp8 rows (656 B: e4m3 c_KV + scales copied, bf16 k_r rotated)" if fp8 else ""),
+                               + (", fp8 rows (656 B: e4m3 c_KV + scales copied, bf16 k_r rotated)" if fp8 else "")
+                               + (f", row stride {STRIDE} B" if STRIDE != ROW_BYTES else ""),
                    "variants": n_var, "streams": n_streams, "hip_graph": bool(args.graph), "hit_tokens_per_step": float(np.mean(hit_tokens)),
                    "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s %s"
                              % ({"full": "", "ref": "_ref"}.get(args.reattach, "_kr"),
