@@ -217,7 +217,8 @@ def test_attend_ref_bad_arguments_and_indices():
 # ------------------------------------------------------------------ fp8 rows --
 
 @pytest.mark.parametrize("name,n_heads,n_splits,pair_mode", [("c2", 16, 1, 0), ("c2", 16, 5, 1), ("c1", 32, 8, 0),
-                                                             ("c3", 128, 4, 1), ("c2", 64, 3, 0)])
+                                                             ("c3", 128, 4, 1), ("c2", 64, 3, 0),
+                                                             ("c2", 48, 2, 1), ("c2", 96, 2, 0)])
 def test_attend_ref_fp8_rows_small_configs(name, n_heads, n_splits, pair_mode):
     """Pools of 656-byte rows: c_KV = E4M3 code times block scale, the codes staged exactly and the scales
     applied on the compute side."""
