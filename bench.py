@@ -55,7 +55,8 @@ def main() -> int:
     ap.add_argument("--row-stride", type=int, default=0, metavar="BYTES",
                     help="hit stage, --reattach full: row stride of both pools in bytes, a multiple of 16 "
                          "(0 = packed rows; 768 puts every fp8 row on its own 128-byte lines)")
-    ap.add_argument("--heads", type=int, default=16, help="attend stage: query heads (multiple of 16)")
+    ap.add_argument("--heads", type=int, default=16, help="attend stage: query rows per request, a multiple of 16 "
+                                                              "(heads, or new tokens x heads over a cached prefix)")
     ap.add_argument("--linear-rows", action="store_true",
                     help="attend stage: every slot refers to the pool row of the same number (no rotation), i.e. "
                          "purely sequential reads: the yardstick for what the gather pattern costs")
@@ -408,7 +409,11 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
             "roofline": {"bound": "hbm", "kernel": "attend_ref_split+attend_ref_merge", "achieved": achieved,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                          "bytes_per_token_layer": ROW_BYTES * groups, "launches": kernel_n,
-                         "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3}}
+                         "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3,
+                         # the two products: 576 + 512 multiply-adds per token and query row
+                         "mfma_tflops": (2.0 * (576 + 512) * H * ctx_tokens * kernel_n / (kernel_ms * 1e-3) / 1e12
+                                         if kernel_ms > 0 else 0.0),
+                         "mfma_peak_tflops": 2500.0}}
 
 
 def calibrate(n, dev, stream):

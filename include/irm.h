@@ -309,8 +309,13 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * k_r is rotated in fp32 and rounded once to bf16 while the rows are staged on chip (the
  * values irm_reattach would have written); products in bf16 MFMA with fp32 accumulation.
  *   d_q            bf16 [n_req][n_heads][576] (latent-space query | rotary query), 16-byte aligned;
- *                  n_heads a multiple of 16, at most 128 (the pool rows are streamed once per
- *                  16 heads, or once per 32 / 64 when n_heads is a multiple of 32 / 64)
+ *                  n_heads a multiple of 16, at most IRM_ATTEND_MAX_QUERY_ROWS (the pool rows are
+ *                  streamed once per 16 heads, or once per 32 / 64 when n_heads is a multiple of
+ *                  32 / 64).  In the latent form every (query token, head) pair is one more query
+ *                  row over the same keys, so a step with several query tokens per request whose
+ *                  context lies wholly before them (new tokens over a re-attached prefix) passes
+ *                  n_heads = tokens * heads, rows ordered [token][head]; attention among the new
+ *                  tokens themselves is the caller's, joined through d_lse
  *   d_pool_layer   one layer of the pool, rows of 576 bf16 (or fp8 rows, see below) at
  *                  pool_row_stride_bytes
  *   d_kv_slots     int32, d_kv_offsets uint32[n_req + 1]: CSR of every request's context slots
@@ -331,6 +336,7 @@ irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t *d_row_inde
  * numerator before that is rounded to bf16.  (With a multiple of 32 heads the elements are
  * scaled and rounded once to bf16 as the rows are staged instead.)  Everything else is the
  * same. */
+#define IRM_ATTEND_MAX_QUERY_ROWS 8192u
 uint64_t irm_attend_ref_workspace_bytes(uint32_t n_req, uint32_t n_heads, uint32_t n_splits);
 irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_req, uint32_t n_heads,
                           const void *d_pool_layer, uint64_t pool_row_stride_bytes, uint64_t pool_rows,

@@ -920,7 +920,7 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     if (!ctx || !d_q || !d_pool_layer || !d_kv_slots || !d_kv_offsets || !d_row_index || !d_hit_index ||
         !d_trig || !d_workspace || !d_out || !d_lse)
         return IRM_ERR_INVALID_ARG;
-    if (n_req < 1 || n_heads < ATT_HEADS || n_heads % ATT_HEADS || n_heads > 128 || n_splits < 1 ||
+    if (n_req < 1 || n_heads < ATT_HEADS || n_heads % ATT_HEADS || n_heads > IRM_ATTEND_MAX_QUERY_ROWS || n_splits < 1 ||
         n_splits > 1024 || n_req > 65535)
         return IRM_ERR_INVALID_ARG;
     const bool f8 = ctx->cfg.row_format == IRM_ROW_FP8;

@@ -102,7 +102,8 @@ def check(got, got_lse, want, want_lse, long_contexts=False, fp8=False):
 
 @pytest.mark.parametrize("name,n_heads,n_splits,pair_mode", [("c2", 16, 1, 0), ("c2", 16, 5, 1), ("c1", 32, 8, 0),
                                                              ("c4", 16, 3, 0), ("c3", 128, 4, 1), ("c2", 64, 3, 0),
-                                                             ("c2", 48, 2, 1), ("c2", 96, 2, 0)])
+                                                             ("c2", 48, 2, 1), ("c2", 96, 2, 0),
+                                                             ("c1", 272, 3, 1), ("c2", 512, 2, 0)])
 def test_attend_ref_small_configs(name, n_heads, n_splits, pair_mode):
     w = wl.make_workload(name, orc.cdc_chunk, size="small")
     hits = oracle_front(w)["hits"]
@@ -218,7 +219,8 @@ def test_attend_ref_bad_arguments_and_indices():
 
 @pytest.mark.parametrize("name,n_heads,n_splits,pair_mode", [("c2", 16, 1, 0), ("c2", 16, 5, 1), ("c1", 32, 8, 0),
                                                              ("c3", 128, 4, 1), ("c2", 64, 3, 0),
-                                                             ("c2", 48, 2, 1), ("c2", 96, 2, 0)])
+                                                             ("c2", 48, 2, 1), ("c2", 96, 2, 0),
+                                                             ("c1", 256, 2, 0)])
 def test_attend_ref_fp8_rows_small_configs(name, n_heads, n_splits, pair_mode):
     """Pools of 656-byte rows: c_KV = E4M3 code times block scale, the codes staged exactly and the scales
     applied on the compute side."""
