@@ -390,6 +390,7 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
             ms, n = B.irm_ctx_profile_end(s.ctx, stream)
             kernel_ms += ms
             kernel_n += n
+            assert s.error_flags() == 0, "the timed steps raised an error flag"
     ctx_tokens = len(w0.tokens)                                  # every request attends over all of its tokens
     # a row is streamed once per workgroup pass: 64 heads when the heads are a multiple of 64 (four head groups
     # share every staged tile), 32 when a multiple of 32, else 16
