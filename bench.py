@@ -28,18 +28,25 @@ if ROOT not in sys.path:
 
 ROW_BYTES = 1152                                     # bf16 rows; main() takes the format's own size
 HBM_PEAK_GBS = 8000.0
-PROFILE_TRAFFIC = {"bf16": os.path.join(ROOT, "profiles", "reattach_rows_c1_traffic.json"),
-                   "fp8": os.path.join(ROOT, "profiles", "reattach_rows_fp8_c1_traffic.json")}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c1", help="c0..c4 (the headline is c1)")
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: per workload, see DEFAULTS)")
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c4",
+                    help="c0..c4; the headline is c4, the largest configuration that fits one GPU (61 layers, "
+                         "32 x 65,536 tokens, the whole serve path on one stream)")
     ap.add_argument("--size", default="full", choices=["full", "small"])
-    ap.add_argument("--variants", type=int, default=8, help="request batches cycled through")
+    ap.add_argument("--variants", type=int, default=None, help="request batches cycled through (default: per workload)")
+    ap.add_argument("--cdc", default="config", choices=["config", "paper"],
+                    help="CDC rule: config = the measured configurations' (mask 0xFF, chunks of 64..1024 tokens); "
+                         "paper = the paper's own (Sec. 7.2, App. B: mask 0x7F, chunks of 32..512 tokens)")
+    ap.add_argument("--secondary", default=None,
+                    help="comma-separated workloads measured after the headline in the same process and reported in "
+                         "the 'secondary' block of the JSON line, each as name or name:paper (default with the c4 "
+                         "headline: c1,c2,c3,c1:paper; '' = none)")
     ap.add_argument("--slots", default="contiguous", choices=["contiguous", "permuted"])
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the row kernel (0 = library default)")
     ap.add_argument("--reattach", default="full", choices=["full", "kr", "kr-dense", "ref"],
@@ -93,6 +100,46 @@ def main() -> int:
               "(it would shard by layer or by request, with no exchange step)", file=sys.stderr)
         return 2
 
+    plain = (args.stage == "hit" and args.reattach == "full" and args.rows == "bf16" and args.streams == 1
+             and not args.graph and not args.row_stride and args.size == "full")
+    if args.secondary is None:
+        args.secondary = "c1,c2,c3,c1:paper" if plain and args.workload == "c4" and args.cdc == "config" else ""
+    out = run(with_defaults(args, args.workload, args.cdc, args.steps, args.warmup, args.variants))
+    if args.secondary:
+        assert plain, "--secondary goes with the plain hit path (bf16 rows, one stream)"
+        out["secondary"] = []
+        for item in filter(None, args.secondary.split(",")):
+            name, _, cdc = item.partition(":")
+            sub = run(with_defaults(args, name, cdc or "config", None, None, None, cpu=False))
+            out["secondary"].append({"workload": sub["config"]["workload"], "steps": sub["steps"],
+                                     "ms_per_step": sub["ms_per_step"], "value": sub["value"], "unit": sub["unit"],
+                                     "hit_tokens_per_step": sub["config"]["hit_tokens_per_step"],
+                                     "hits_per_step": sub["config"]["hits_per_step"],
+                                     "roofline": sub["roofline"]})
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+# per workload: timed steps, warm-up steps, request batches cycled (sized so that every run takes seconds)
+DEFAULTS = {"c0": (200, 20, 1), "c1": (200, 20, 8), "c2": (12, 3, 2), "c3": (60, 6, 2), "c4": (20, 5, 1)}
+
+
+def with_defaults(args, name, cdc, steps, warmup, variants, cpu=True):
+    import copy
+    a = copy.copy(args)
+    d = DEFAULTS[name]
+    a.workload, a.cdc = name, cdc
+    a.steps = d[0] if steps is None else steps
+    a.warmup = d[1] if warmup is None else warmup
+    a.variants = d[2] if variants is None else variants
+    if not cpu:
+        a.no_cpu_baseline = True
+    return a
+
+
+def run(args) -> dict:
+    """One workload through the stage the flags name; returns the result record."""
+    import gc
     import torch
     from paper_2605_05696_amd import binding as B
     from paper_2605_05696_amd import workloads as wl
@@ -101,22 +148,26 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    gc.collect()
+    torch.cuda.empty_cache()
     name = args.workload
     dims = wl.CONFIGS[name][args.size]
+    mask, min_chunk, max_chunk = wl.CDC_RULES[args.cdc]
 
     # ---- inputs: chunked and fingerprinted by the library itself -------------
     max_stream = max(dims["pool"], dims.get("n_req", 1) * dims.get("req_len", dims["pool"]) * 2 + 16384)
     gear = wl.gear_table()
-    front = Session(gear, 0xFF, 64, 1024, 32, 1, wl.inv_freq_plain(), max_stream, 1, dev)
+    front = Session(gear, mask, min_chunk, max_chunk, 32, 1, wl.inv_freq_plain(), max_stream, 1, dev)
 
-    def gpu_chunker(tokens, req_offsets, gear_, mask, lo, hi):
+    def gpu_chunker(tokens, req_offsets, gear_, mask_, lo, hi):
+        assert (mask_, lo, hi) == (mask, min_chunk, max_chunk)
         st, ln, rco, _ = front.chunk_host(tokens, req_offsets)
         return st, ln, rco
 
     n_var = 1 if name == "c0" else max(1, args.variants)
     s1 = args.stage == "s1"
     works = [wl.make_workload(name, gpu_chunker, size=args.size, variant=v, slots=args.slots,
-                              assembly="unaligned" if s1 else "aligned", s1_window=128 if s1 else 0)
+                              assembly="unaligned" if s1 else "aligned", s1_window=128 if s1 else 0, cdc=args.cdc)
              for v in range(n_var)]
     w0 = works[0]
     _, _, _, pool_hash = front.chunk_host(w0.pool_tokens, np.array([0, len(w0.pool_tokens)], np.uint32))
@@ -206,16 +257,14 @@ def main() -> int:
         out = bench_attend(args, works, sessions, dev_in, src, stream)
         for s in sessions:
             s.close()
-        print(json.dumps(out), flush=True)
-        return 0
+        return out
     if args.stage == "admit":
         with torch.cuda.stream(stream):
             calibrate(args.calibrate, dev, stream)
         out = bench_admit(args, works, sessions, dev_in, src, stream)
         for s in sessions:
             s.close()
-        print(json.dumps(out), flush=True)
-        return 0
+        return out
 
     def step(v):
         s, d = sessions[v], dev_in[v]
@@ -235,10 +284,11 @@ def main() -> int:
 
     with torch.cuda.stream(stream):
         # one pass per variant: learn the hit counts, check the error words
-        hit_tokens, window_tokens = [], []
+        hit_tokens, window_tokens, n_hits = [], [], []
         for v in range(n_var):
             step(v)
             torch.cuda.synchronize()
+            n_hits.append(int(dev_in[v]["buf"]["n_hits"].item()))
             hit_tokens.append(int(dev_in[v]["buf"]["hit_tokens"].item())
                               + (int(dev_in[v]["wbuf"]["hit_tokens"].item()) if s1 else 0))
             if s1:
@@ -284,10 +334,16 @@ def main() -> int:
     value = total_tokens / elapsed
     alg_bytes = kernel_tokens * L * bytes_per_token_layer
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9 if kernel_ms > 0 else 0.0
-    traffic = None
-    if (name == "c1" and args.size == "full" and args.reattach == "full" and args.stage == "hit"
-            and args.slots == "contiguous" and os.path.exists(PROFILE_TRAFFIC[args.rows])):
-        traffic = json.load(open(PROFILE_TRAFFIC[args.rows])).get("hbm_bytes_per_launch")
+    # HBM bytes per launch as counted by rocprofv3 (FETCH_SIZE, WRITE_SIZE, scaled by a plain copy): a STORED
+    # profile of this workload and kernel, not a measurement of this run
+    traffic, traffic_source = None, None
+    tfile = os.path.join(ROOT, "profiles", f"reattach_rows_{'fp8_' if fp8 else ''}{name}"
+                                           f"{'_paper' if args.cdc == 'paper' else ''}_traffic.json")
+    if (args.size == "full" and args.reattach == "full" and args.stage == "hit" and args.slots == "contiguous"
+            and not args.row_stride and os.path.exists(tfile)):
+        stored = json.load(open(tfile))
+        traffic = stored.get("hbm_bytes_per_launch")
+        traffic_source = f"stored: profiles/{os.path.basename(tfile)} ({stored.get('kernel', 'reattach_rows')})"
 
     out = {
         "metric": "re-attached KV tokens/s (all layers), whole hot path, 1 MI355X",
@@ -296,9 +352,12 @@ def main() -> int:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{name}-{args.size}: {w0.n_req} request(s) x {dims.get('req_len', dims['pool'])} tokens, "
                                f"{L} layers, pool {w0.src_rows} tokens, slots {args.slots}"
+                               + (", paper-native CDC rule" if args.cdc == "paper" else "")
                                + (", fp8 rows (656 B: e4m3 c_KV + scales copied, bf16 k_r rotated)" if fp8 else "")
                                + (f", row stride {STRIDE} B" if STRIDE != ROW_BYTES else ""),
-                   "variants": n_var, "streams": n_streams, "hip_graph": bool(args.graph), "hit_tokens_per_step": float(np.mean(hit_tokens)),
+                   "cdc_rule": f"mask {mask:#x}, chunks of {min_chunk}..{max_chunk} tokens",
+                   "variants": n_var, "streams": n_streams, "hip_graph": bool(args.graph),
+                   "hit_tokens_per_step": float(np.mean(hit_tokens)), "hits_per_step": float(np.mean(n_hits)),
                    "stages": "irm_cdc_chunk+irm_chunk_hash+irm_lookup+irm_reattach%s %s"
                              % ({"full": "", "ref": "_ref"}.get(args.reattach, "_kr"),
                                 "on one stream" if n_streams == 1 else
@@ -307,6 +366,8 @@ def main() -> int:
                                 "the missed chunks" if s1 else "")},
         "roofline": {"bound": "hbm", "kernel": {"full": "reattach_rows", "ref": "reattach_ref_rows"}.get(args.reattach, "reattach_kr_rows"), "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": alg_bytes / max(kernel_n, 1),
                      "bytes_per_token_layer": bytes_per_token_layer, "launches": kernel_n,
                      "avg_launch_us": kernel_ms / max(kernel_n, 1) * 1e3,
                      "kernel_tokens_per_s": kernel_tokens / (kernel_ms * 1e-3) if kernel_ms > 0 else 0.0},
@@ -321,8 +382,7 @@ def main() -> int:
 
     for s in sessions:
         s.close()
-    print(json.dumps(out), flush=True)
-    return 0
+    return out
 
 
 def bench_attend(args, works, sessions, dev_in, pool, stream):
@@ -545,7 +605,7 @@ def cpu_baseline(works, src, budget_s):
     # the same oracle calls fanned out over (layer, group of hits) on the host's cores, last sample
     # (ctypes releases the interpreter lock during a call; the integer stages stay on one thread)
     from concurrent.futures import ThreadPoolExecutor
-    cores = max(1, min(16, os.cpu_count() or 1))
+    cores = max(1, min(16, os.cpu_count() or 1))     # a one-GPU machine's share of the host is 16 threads
     slots = np.arange(off[-1], dtype=np.int32)
     groups = np.array_split(np.arange(keep), max(1, min(keep, -(-4 * cores // L))))
     def one(task):
@@ -557,10 +617,11 @@ def cpu_baseline(works, src, budget_s):
     with ThreadPoolExecutor(cores) as pool:
         list(pool.map(one, tasks))
     mt_s = time.perf_counter() - t2 + front_s * share
-    return {"value": tokens / spent, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+    return {"value": tokens / spent, "unit": "tokens/s", "cores": 1, "host_cores": os.cpu_count(), "kind": "oracle",
             "sample": f"{tokens} re-attached tokens x {L} layers from {batches} batch pass(es) over the same workload "
                       f"(chunk+hash+lookup+re-attach, single thread), {spent:.1f} s of CPU time",
             "all_cores": {"value": int(off[-1]) / mt_s, "unit": "tokens/s", "cores": cores,
+                          "host_cores": os.cpu_count(),
                           "sample": f"the last pass's {int(off[-1])} tokens x {L} layers, re-attach fanned out over "
                                     f"{len(tasks)} (layer, hit group) tasks on {cores} threads"}}
 

@@ -152,35 +152,6 @@ irm_status irm_ctx_destroy(irm_ctx *ctx);
  * and clears it. */
 irm_status irm_ctx_error_flags(irm_ctx *ctx, void *stream, uint32_t *flags);
 
-/* Tuning knobs for measurements (launch shapes only; results never change).
- * knob 0: grid.x of the re-attach row kernel = tile slots per layer (0 = one per
- *         possible tile)
- * knob 1: c_KV rows per wave and tile (1, 2, 4, 8 or 16; fp8 rows: not 1)
- * knob 2: bit 0 = non-temporal loads, bit 1 = non-temporal stores
- * knob 3: 1 = each XCD serves a contiguous range of a layer's tiles, 0 = round-robin
- * knob 4: waves per workgroup (1, 2, 4, 8 or 16; fp8 rows: 4 or more); a tile is
- *         waves x rows-per-wave rows, at least 4
- * knob 5: 1 = irm_cdc_chunk always selects cuts with the serial walk (else only for
- *         requests with more than 4096 candidate positions)
- * knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; its tile is 32 times that) */
-irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
-
-/* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples
- * pairs of HIP events; while enabled, every `every`-th irm_reattach,
- * irm_reattach_kr, irm_reattach_ref or irm_attend_ref (the first one included)
- * records one pair around its row kernel(s) on the caller's stream (calls past
- * max_samples are not sampled).  irm_ctx_profile_end waits for the stream, returns the summed
- * elapsed milliseconds and the number of samples, destroys the events and
- * disables sampling.  Not for use under graph capture. */
-irm_status irm_ctx_profile_begin(irm_ctx *ctx, uint32_t max_samples, uint32_t every);
-irm_status irm_ctx_profile_end(irm_ctx *ctx, void *stream, float *total_ms, uint32_t *n_samples);
-
-/* Measurement aid: a plain copy of `bytes` (multiple of 16) from d_src to d_dst
- * with 16-byte accesses, `grid` workgroups of 256 lanes (0 = default).  Its HBM
- * traffic is known exactly (bytes read + bytes written), which calibrates
- * hardware counters and gives the copy bandwidth the machine can reach. */
-irm_status irm_calibrate_copy(void *d_dst, const void *d_src, uint64_t bytes, uint32_t grid, void *stream);
-
 /* Registry R: hash -> entry (Alg. 1 "Require", steps 7 and 13), an
  * open-addressing table of n_slots slots in device memory owned by the table. */
 irm_status irm_table_create(irm_ctx *ctx, uint64_t n_slots, irm_table **out);

@@ -80,7 +80,6 @@ def lib():
                                      vp, vp]
         L.irm_reattach_ref.argtypes = [vp, u64, vp, vp, u64, vp, vp, u64, vp, vp, u32, vp]
         L.irm_attend_ref_workspace_bytes.argtypes = [u32, u32, u32]
-        L.irm_attend_ref_workspace_bytes.restype = u64
         L.irm_attend_ref.argtypes = [vp, vp, u32, u32, vp, u64, u64, vp, vp, vp, vp, u64, vp, u32, ctypes.c_float, u32,
                                      vp, u64, vp, vp, vp]
         L.irm_admit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, u64, u64, vp, u64, vp,
@@ -88,6 +87,7 @@ def lib():
         L.irm_reattach_kr.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, vp, u64, vp, vp, u32, vp]
         for name in SYMBOLS:
             getattr(L, name).restype = ctypes.c_int
+        L.irm_attend_ref_workspace_bytes.restype = u64       # the one call that returns a size, not a status
         _lib = L
     return _lib
 

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "irm.h"
+#include "irm_measure.h"
 
 #define IRM_ROW_BYTES 1152u     // bf16 rows: 576 bf16
 #define IRM_CKV_BYTES 1024u     // bf16 rows: 512 bf16

@@ -220,6 +220,10 @@ CONFIGS = {
 CONFIG_NAMES = tuple(CONFIGS)
 LOAD_FACTOR = 0.7
 
+# CDC rule -> (mask, min_chunk, max_chunk).  "config": the rule the five measured configurations
+# state; "paper": the paper's own (Sec. 7.2 "CDC boundary rule", App. B): low 7 bits, 32..512 tokens.
+CDC_RULES = {"config": (0xFF, 64, 1024), "paper": (0x7F, 32, 512)}
+
 
 def _seeds(name, variant):
     k = CONFIG_NAMES.index(name)
@@ -231,7 +235,8 @@ def kv_seed(name: str) -> int:
 
 
 def make_workload(name: str, chunker: Chunker, size: str = "full", variant: int = 0,
-                  slots: str = "contiguous", assembly: str = "aligned", s1_window: int = 0) -> Workload:
+                  slots: str = "contiguous", assembly: str = "aligned", s1_window: int = 0,
+                  cdc: str = "config") -> Workload:
     """Build configuration ``name`` ("c0".."c4").
 
     ``assembly`` "aligned" (default): every piece of a request ends on a cut, so the request
@@ -239,6 +244,8 @@ def make_workload(name: str, chunker: Chunker, size: str = "full", variant: int 
     trailing tokens, so the pool chunk that follows it starts off a cut and its first chunk
     drifts (traffic whose assembly the operator does not control).  ``s1_window`` > 0 sizes the
     table for the pool's fixed windows as well (``window_registry``).
+
+    ``cdc`` picks the chunking rule from ``CDC_RULES`` (same seeds, so the same token streams).
 
     ``variant`` re-draws the request batch against the same pool (used to cycle
     through several batches while timing).  ``slots`` is "contiguous" (request
@@ -248,7 +255,7 @@ def make_workload(name: str, chunker: Chunker, size: str = "full", variant: int 
     dims = spec[size]
     pool_seed, req_seed, _ = _seeds(name, variant)
     gear = gear_table()
-    mask, min_chunk, max_chunk, carve_out = 0xFF, 64, 1024, 32
+    (mask, min_chunk, max_chunk), carve_out = CDC_RULES[cdc], 32
     rng_pool = np.random.default_rng(pool_seed)
     rng = np.random.default_rng(req_seed)
 

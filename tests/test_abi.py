@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "irm.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("irm.h", "irm_measure.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"^(?:irm_status|uint64_t)\s+(irm_\w+)\s*\(", text, flags=re.M)))
 
@@ -98,6 +98,11 @@ def test_null_arguments_are_rejected():
     assert L.irm_attend_ref(*([None] * 2), 1, 16, None, 1152, 1, *([None] * 4), 1, None, 0, ctypes.c_float(1.0), 1, None, 0,
                             None, None, None) == B.IRM_ERR_INVALID_ARG
     assert L.irm_attend_ref_workspace_bytes(2, 16, 3) == 2 * 16 * 3 * 514 * 4
+    # a size beyond 32 bits must come back whole, through the raw symbol and through the binding
+    big = 65535 * 8192 * 4 * 514 * 4
+    assert big > 1 << 32
+    assert L.irm_attend_ref_workspace_bytes(65535, 8192, 4) == big
+    assert B.irm_attend_ref_workspace_bytes(65535, 8192, 4) == big
     flags = ctypes.c_uint32()
     assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG
