@@ -76,8 +76,6 @@ def lib():
         L.irm_lookup.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
         L.irm_reattach.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, u64, vp, vp, u32, vp]
         L.irm_table_insert_counted.argtypes = [vp, vp, vp, vp, u32, vp]
-        L.irm_s1_windows.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, u32,
-                                     vp, vp]
         L.irm_reattach_ref.argtypes = [vp, u64, vp, vp, u64, vp, vp, u64, vp, vp, u32, vp]
         L.irm_attend_ref_workspace_bytes.argtypes = [u32, u32, u32]
         L.irm_attend_ref.argtypes = [vp, vp, u32, u32, vp, u64, u64, vp, vp, vp, vp, u64, vp, u32, ctypes.c_float, u32,

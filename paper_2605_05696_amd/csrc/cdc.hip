@@ -28,9 +28,9 @@ __device__ __forceinline__ uint64_t rfl64(uint64_t v)
 // Bits of tokens closer than k-1 to the start of the array use the terms that
 // exist; bits within k-1 of a request start mix in the previous request's
 // tail, which is harmless: such positions are never eligible (min_chunk >= k).
-__global__ __launch_bounds__(256) void cdc_candidates(const int32_t *__restrict__ tokens, uint64_t n_tokens,
-                                                      const uint32_t *__restrict__ gear, uint32_t mask,
-                                                      uint32_t k_bits, uint64_t *__restrict__ bitmap)
+__device__ __forceinline__ void candidates_block(const int32_t *__restrict__ tokens, uint64_t n_tokens,
+                                                 const uint32_t *__restrict__ gear, uint32_t mask,
+                                                 uint32_t k_bits, uint64_t *__restrict__ bitmap)
 {
     __shared__ uint32_t g[256 + 32];
     const uint64_t block0 = (uint64_t)blockIdx.x * 256;
@@ -49,6 +49,13 @@ __global__ __launch_bounds__(256) void cdc_candidates(const int32_t *__restrict_
     const bool cand = (i < n_tokens) && ((acc & mask) == 0);
     const uint64_t word = __ballot(cand);
     if ((tid & 63) == 0 && i < n_tokens) bitmap[i >> 6] = word;   // i is a multiple of 64 here
+}
+
+__global__ __launch_bounds__(256) void cdc_candidates(const int32_t *__restrict__ tokens, uint64_t n_tokens,
+                                                      const uint32_t *__restrict__ gear, uint32_t mask,
+                                                      uint32_t k_bits, uint64_t *__restrict__ bitmap)
+{
+    candidates_block(tokens, n_tokens, gear, mask, k_bits, bitmap);
 }
 
 // ---- kernel 2, serial path: one wave walks the bitmap, one step per chunk ----
@@ -371,6 +378,53 @@ __device__ __forceinline__ void cdc_compact(const uint32_t *__restrict__ req_off
 // ---- kernel 2: greedy cut selection, one workgroup per request -------------
 // The workgroup that finishes last (ticket counter in the context, left at zero again)
 // gathers the per-request lists into the caller's CSR arrays.
+struct cdc_select_mem {
+    union {
+        uint64_t seg[CDC_SEG_WORDS];
+        cdc_jump_mem g;
+    } sm;
+    uint32_t scan_lds[17];
+};
+
+// cuts of request r.  `direct` (a batch of one request): its list is the result, written in
+// place, no staging and nothing to gather afterwards.
+__device__ __forceinline__ void select_request(cdc_select_mem *m, const uint64_t *__restrict__ bitmap,
+                                               const uint32_t *__restrict__ req_offsets, uint32_t r, bool direct,
+                                               uint64_t n_tokens, uint32_t min_chunk, uint32_t max_chunk,
+                                               uint32_t *stage_start, uint32_t *stage_len, uint32_t *req_count,
+                                               uint32_t stage_cap, uint32_t force_serial,
+                                               uint32_t *__restrict__ chunk_start, uint32_t *__restrict__ chunk_len,
+                                               uint32_t *__restrict__ req_chunk_offsets,
+                                               uint32_t *__restrict__ n_chunks, uint32_t chunk_capacity, uint32_t *err)
+{
+    const uint32_t begin = req_offsets[r], end = req_offsets[r + 1];
+    if (begin > end || (uint64_t)end > n_tokens) {     // malformed offsets: emit nothing
+        if (threadIdx.x == 0) {
+            req_count[r] = 0;
+            atomicOr(err, IRM_FLAG_BAD_CHUNK);
+        }
+    } else {
+        const uint32_t base = direct ? 0u : begin / min_chunk + r;   // this request's staging area
+        uint32_t *out_start = direct ? chunk_start : stage_start, *out_len = direct ? chunk_len : stage_len;
+        const uint32_t out_cap = direct ? chunk_capacity : stage_cap;
+        if (force_serial || !select_jump(bitmap, &m->sm.g, m->scan_lds, r, begin, end, base, min_chunk, max_chunk,
+                                         out_start, out_len, req_count, out_cap, err)) {
+            __syncthreads();
+            select_serial(bitmap, m->sm.seg, r, begin, end, base, min_chunk, max_chunk, out_start, out_len,
+                          req_count, out_cap, err);
+        }
+    }
+    if (direct && threadIdx.x == 0) {                  // thread 0 wrote req_count[0] itself
+        const uint32_t total = req_count[0];
+        req_chunk_offsets[0] = 0;
+        req_chunk_offsets[1] = total;
+        *n_chunks = total < chunk_capacity ? total : chunk_capacity;
+    }
+}
+
+// ---- kernel 2: greedy cut selection, one workgroup per request -------------
+// The workgroup that finishes last (ticket counter in the context, left at zero again)
+// gathers the per-request lists into the caller's CSR arrays.
 __global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ bitmap,
                                                   const uint32_t *__restrict__ req_offsets, uint32_t n_req,
                                                   uint64_t n_tokens, uint32_t min_chunk, uint32_t max_chunk,
@@ -382,42 +436,13 @@ __global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ b
                                                   uint32_t *__restrict__ n_chunks, uint32_t chunk_capacity,
                                                   uint32_t *tickets, uint32_t *err)
 {
-    __shared__ union {
-        uint64_t seg[CDC_SEG_WORDS];
-        cdc_jump_mem g;
-    } sm;
-    __shared__ uint32_t scan_lds[17];
+    __shared__ cdc_select_mem m;
     __shared__ uint32_t last_sh;
-
-    const uint32_t r = blockIdx.x;
     const bool direct = n_req == 1;
-    const uint32_t begin = req_offsets[r], end = req_offsets[r + 1];
-    if (begin > end || (uint64_t)end > n_tokens) {     // malformed offsets: emit nothing
-        if (threadIdx.x == 0) {
-            req_count[r] = 0;
-            atomicOr(err, IRM_FLAG_BAD_CHUNK);
-        }
-    } else {
-        // one request: its list is the result, written in place; no staging, no ticket, no gathering
-        const uint32_t base = direct ? 0u : begin / min_chunk + r;   // this request's staging area
-        uint32_t *out_start = direct ? chunk_start : stage_start, *out_len = direct ? chunk_len : stage_len;
-        const uint32_t out_cap = direct ? chunk_capacity : stage_cap;
-        if (force_serial || !select_jump(bitmap, &sm.g, scan_lds, r, begin, end, base, min_chunk, max_chunk,
-                                         out_start, out_len, req_count, out_cap, err)) {
-            __syncthreads();
-            select_serial(bitmap, sm.seg, r, begin, end, base, min_chunk, max_chunk, out_start, out_len,
-                          req_count, out_cap, err);
-        }
-    }
-    if (direct) {
-        if (threadIdx.x == 0) {                        // thread 0 wrote req_count[0] itself
-            const uint32_t total = req_count[0];
-            req_chunk_offsets[0] = 0;
-            req_chunk_offsets[1] = total;
-            *n_chunks = total < chunk_capacity ? total : chunk_capacity;
-        }
-        return;
-    }
+    select_request(&m, bitmap, req_offsets, blockIdx.x, direct, n_tokens, min_chunk, max_chunk, stage_start,
+                   stage_len, req_count, stage_cap, force_serial, chunk_start, chunk_len, req_chunk_offsets,
+                   n_chunks, chunk_capacity, err);
+    if (direct) return;
     // publish this request's list, then take a ticket
     __threadfence();
     __syncthreads();
@@ -426,7 +451,7 @@ __global__ __launch_bounds__(256) void cdc_select(const uint64_t *__restrict__ b
     if (!last_sh) return;
     __threadfence();                                   // see every other workgroup's list
     cdc_compact(req_offsets, n_req, min_chunk, stage_start, stage_len, req_count, stage_cap, chunk_start,
-                chunk_len, req_chunk_offsets, n_chunks, chunk_capacity, scan_lds, err);
+                chunk_len, req_chunk_offsets, n_chunks, chunk_capacity, m.scan_lds, err);
     if (threadIdx.x == 0) *tickets = 0;
 }
 

@@ -62,7 +62,7 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     const uint64_t o_tiles = take((uint64_t)c->tile_cap * sizeof(irm_tile));
     const uint64_t o_trig = take((uint64_t)c->chunk_cap * IRM_KR_PAIRS * sizeof(float2));
     const uint64_t o_so = take((uint64_t)c->chunk_cap * 4);
-    const uint64_t o_plan = take(16);
+    const uint64_t o_plan = take(IRM_PLAN_WORDS * 4);
     if (hipMalloc(&c->slab, off) != hipSuccess) {
         (void)hipGetLastError();
         delete c;

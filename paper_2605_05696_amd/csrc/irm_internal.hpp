@@ -14,6 +14,7 @@
 #define IRM_KR_BYTES 128u       // 64 bf16
 #define IRM_TILE_ROWS_MIN 4u    // smallest tile of the re-attach row kernel (sizes the tile list)
 #define IRM_WAVE 64
+#define IRM_PLAN_WORDS 16u
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -52,7 +53,7 @@ struct irm_ctx {
     irm_tile *d_tiles;      // [tile_cap]
     float2 *d_trig;         // [chunk_cap][32] (cos, sin) per hit and pair
     uint32_t *d_slot_of;    // [chunk_cap] table slot a chunk claimed while being admitted
-    uint32_t *d_plan;       // [4]: n_tiles, then the ticket counters of cdc, lookup and admit
+    uint32_t *d_plan;       // [IRM_PLAN_WORDS]: n_tiles, then the ticket counters of cdc, lookup and admit
     // optional timing of the row kernel
     hipEvent_t *prof_events; // [2 * prof_cap]
     uint32_t prof_cap, prof_n, prof_every, prof_calls;

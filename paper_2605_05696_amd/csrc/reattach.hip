@@ -34,13 +34,11 @@ __device__ __forceinline__ uint32_t hit_tiles(const irm_hit &hit, uint64_t src_r
 // One lane per (hit, pair): 8 hits per workgroup.  Each workgroup sums the tile counts
 // of all hits in front of its own (independent loads, a block reduction), so the tile
 // list is written by all workgroups at once, 32 lanes per hit.
-__global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__ hits,
-                                                     const uint32_t *__restrict__ n_hits_p,
-                                                     uint32_t hit_capacity, const float *__restrict__ inv_freq,
-                                                     uint64_t src_rows, uint64_t n_slot_tokens,
-                                                     float2 *__restrict__ trig, irm_tile *__restrict__ tiles,
-                                                     uint32_t tile_cap, uint32_t tile_rows, uint32_t pair_mode,
-                                                     uint32_t *__restrict__ plan, uint32_t *err)
+__device__ __forceinline__ void plan_body(const irm_hit *__restrict__ hits, const uint32_t *__restrict__ n_hits_p,
+                                          uint32_t hit_capacity, const float *inv_freq, uint64_t src_rows,
+                                          uint64_t n_slot_tokens, float2 *__restrict__ trig,
+                                          irm_tile *__restrict__ tiles, uint32_t tile_cap, uint32_t tile_rows,
+                                          uint32_t pair_mode, uint32_t *__restrict__ plan, uint32_t *err)
 {
     __shared__ uint32_t lds[17];
     __shared__ uint32_t local_nt[8];
@@ -102,6 +100,18 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
         }
         if (h == n_hits - 1 && i == 0) plan[0] = t0 + nt < tile_cap ? t0 + nt : tile_cap;
     }
+}
+
+__global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__ hits,
+                                                     const uint32_t *__restrict__ n_hits_p,
+                                                     uint32_t hit_capacity, const float *__restrict__ inv_freq,
+                                                     uint64_t src_rows, uint64_t n_slot_tokens,
+                                                     float2 *__restrict__ trig, irm_tile *__restrict__ tiles,
+                                                     uint32_t tile_cap, uint32_t tile_rows, uint32_t pair_mode,
+                                                     uint32_t *__restrict__ plan, uint32_t *err)
+{
+    plan_body(hits, n_hits_p, hit_capacity, inv_freq, src_rows, n_slot_tokens, trig, tiles, tile_cap, tile_rows,
+              pair_mode, plan, err);
 }
 
 // ---- rows ----------------------------------------------------------------------
@@ -317,35 +327,48 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = irm_wave_id();
     const uint32_t per_xcd = (n_tiles + 7) >> 3;
+    const char *const src_layer = (const char *)src_ptrs[layer];
+    char *const dbase = (char *)dst_ptrs[layer];
+    // With fewer workgroups than tiles (a grid set by the caller) a workgroup walks several
+    // tiles; the record of the next one is requested before the current tile's rows, so
+    // that its latency hides behind them.
+    const uint32_t limit = per_xcd * 8;
+    auto tile_of = [&](uint32_t x) { return xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x; };
+    uint32_t x = blockIdx.x;
+    irm_tile cur = {0u, 0u, 0u, 0u};
+    if (x < limit && tile_of(x) < n_tiles) cur = tiles[tile_of(x)];
 #pragma nounroll
-    for (uint32_t x = blockIdx.x; x < per_xcd * 8; x += gridDim.x) {
-        const uint32_t ti = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
-        if (ti >= n_tiles) continue;
-        const irm_tile *tp = tiles + ti;
-        const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
-        const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
-        const uint32_t n_rows = __builtin_amdgcn_readfirstlane(tp->n_rows);
-        const uint32_t hit = __builtin_amdgcn_readfirstlane(tp->hit);
-        const char *sbase = (const char *)src_ptrs[layer] + (uint64_t)src_row0 * src_stride;
-        char *dbase = (char *)dst_ptrs[layer];
-        int32_t slot[NQ];                               // -1: row absent or its slot unusable
+    while (x < limit) {
+        const uint32_t xn = x + gridDim.x;
+        irm_tile nxt = {0u, 0u, 0u, 0u};
+        if (xn < limit && tile_of(xn) < n_tiles) nxt = tiles[tile_of(xn)];
+        const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(cur.src_row0);
+        const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(cur.dst_tok0);
+        const uint32_t n_rows = __builtin_amdgcn_readfirstlane(cur.n_rows);
+        const uint32_t hit = __builtin_amdgcn_readfirstlane(cur.hit);
+        if (n_rows != 0) {                              // 0: no tile behind this slot
+            const char *sbase = src_layer + (uint64_t)src_row0 * src_stride;
+            int32_t slot[NQ];                           // -1: row absent or its slot unusable
 #pragma unroll
-        for (uint32_t q = 0; q < NQ; ++q) {
-            const uint32_t r = 64 * q + lane;
-            slot[q] = -1;
-            if (r < n_rows) {
-                const int32_t sl = dst_slots[(uint64_t)dst_tok0 + r];
-                if (sl < 0 || (uint64_t)(uint32_t)sl >= dst_rows) atomicOr(err, IRM_FLAG_ROW_RANGE);
-                else slot[q] = sl;
+            for (uint32_t q = 0; q < NQ; ++q) {
+                const uint32_t r = 64 * q + lane;
+                slot[q] = -1;
+                if (r < n_rows) {
+                    const int32_t sl = dst_slots[(uint64_t)dst_tok0 + r];
+                    if (sl < 0 || (uint64_t)(uint32_t)sl >= dst_rows) atomicOr(err, IRM_FLAG_ROW_RANGE);
+                    else slot[q] = sl;
+                }
             }
+            const float2 *trig_hit = trig + (uint64_t)hit * IRM_KR_PAIRS;
+            if (n_rows == TILE)
+                reattach_tile<WAVES, RPW, true, NT_LD, NT_ST, F8>(sbase, src_stride, dbase, dst_stride, slot,
+                                                                  n_rows, trig_hit, wave, lane, il);
+            else
+                reattach_tile<WAVES, RPW, false, NT_LD, NT_ST, F8>(sbase, src_stride, dbase, dst_stride, slot,
+                                                                   n_rows, trig_hit, wave, lane, il);
         }
-        const float2 *trig_hit = trig + (uint64_t)hit * IRM_KR_PAIRS;
-        if (n_rows == TILE)
-            reattach_tile<WAVES, RPW, true, NT_LD, NT_ST, F8>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
-                                                              trig_hit, wave, lane, il);
-        else
-            reattach_tile<WAVES, RPW, false, NT_LD, NT_ST, F8>(sbase, src_stride, dbase, dst_stride, slot, n_rows,
-                                                               trig_hit, wave, lane, il);
+        cur = nxt;
+        x = xn;
     }
 }
 
@@ -571,16 +594,24 @@ extern "C" irm_status irm_reattach_ref(irm_ctx *ctx, uint64_t src_rows, int32_t 
     return irm_launch_status();
 }
 
-extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
-                                   uint64_t src_row_stride_bytes, uint64_t src_rows,
-                                   void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,
-                                   uint64_t dst_rows, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
-                                   const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
-                                   void *stream)
+// launch shape of the row kernel and where its plan lives
+struct rows_launch {
+    uint32_t waves, rows_per_wave, mem_mode, xcd_ranges, grid, pair_mode, row_format, n_layers;
+    float2 *d_trig;
+    irm_tile *d_tiles;
+    uint32_t tile_cap;
+    uint32_t *d_plan, *d_err;
+};
+
+// host-side checks both entry points share
+static irm_status reattach_check(uint32_t row_format, const void *const *d_src_layer_ptrs,
+                                 uint64_t src_row_stride_bytes, uint64_t src_rows, void *const *d_dst_layer_ptrs,
+                                 uint64_t dst_row_stride_bytes, uint64_t dst_rows, const int32_t *d_dst_slots,
+                                 uint64_t n_slot_tokens, const irm_hit *d_hits, const uint32_t *d_n_hits,
+                                 uint32_t hit_capacity)
 {
-    if (!ctx || !d_src_layer_ptrs || !d_dst_layer_ptrs || !d_dst_slots || !d_hits || !d_n_hits)
-        return IRM_ERR_INVALID_ARG;
-    const uint32_t row_bytes = irm_row_bytes(ctx->cfg.row_format);
+    if (!d_src_layer_ptrs || !d_dst_layer_ptrs || !d_dst_slots || !d_hits || !d_n_hits) return IRM_ERR_INVALID_ARG;
+    const uint32_t row_bytes = irm_row_bytes(row_format);
     if (src_row_stride_bytes < row_bytes || dst_row_stride_bytes < row_bytes ||
         (src_row_stride_bytes & 15) || (dst_row_stride_bytes & 15))
         return IRM_ERR_INVALID_ARG;
@@ -588,28 +619,52 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
         n_slot_tokens < 1)
         return IRM_ERR_INVALID_ARG;
     if (hit_capacity < 1) return IRM_ERR_INVALID_ARG;
-    if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
-    hipStream_t s = (hipStream_t)stream;
-    const uint32_t tile_rows = ctx->block_waves * ctx->rows_per_wave;
-    const uint32_t plan_blocks = (hit_capacity + 7) / 8;
-    hipLaunchKernelGGL(reattach_plan, dim3(plan_blocks), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
-                       ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles, ctx->tile_cap,
-                       tile_rows, ctx->cfg.pair_mode, ctx->d_plan, ctx->d_err);
-    // one workgroup per tile slot and layer: the hardware dispatcher balances the load
-    // (measured faster than a persistent grid of resident size); the slot count can only
-    // be bounded on the host, surplus workgroups exit on their first compare
+    return IRM_OK;
+}
+
+// one workgroup per tile slot and layer: the hardware dispatcher balances the load
+// (measured faster than a persistent grid of resident size); the slot count can only
+// be bounded on the host, surplus workgroups exit on their first compare
+static void rows_enqueue(const rows_launch &k, const void *const *d_src_layer_ptrs, uint64_t src_row_stride_bytes,
+                         void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes, uint64_t dst_rows,
+                         const int32_t *d_dst_slots, uint64_t n_slot_tokens, uint32_t hit_capacity, hipStream_t s)
+{
+    const uint32_t tile_rows = k.waves * k.rows_per_wave;
     uint64_t tile_slots = n_slot_tokens / tile_rows + hit_capacity;
-    if (ctx->reattach_grid) tile_slots = ctx->reattach_grid;
+    if (k.grid) tile_slots = k.grid;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
     const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8);
+    hipLaunchKernelGGL(pick_kernel(k.waves, k.rows_per_wave, k.mem_mode, k.row_format), dim3(grid_x, k.n_layers),
+                       dim3(k.waves * 64), 0, s, d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs,
+                       dst_row_stride_bytes, dst_rows, d_dst_slots, k.d_tiles, k.d_plan, k.d_trig, k.xcd_ranges,
+                       k.pair_mode, k.d_err);
+}
+
+extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
+                                   uint64_t src_row_stride_bytes, uint64_t src_rows,
+                                   void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,
+                                   uint64_t dst_rows, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
+                                   const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
+                                   void *stream)
+{
+    if (!ctx) return IRM_ERR_INVALID_ARG;
+    const irm_status st = reattach_check(ctx->cfg.row_format, d_src_layer_ptrs, src_row_stride_bytes, src_rows,
+                                         d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows, d_dst_slots,
+                                         n_slot_tokens, d_hits, d_n_hits, hit_capacity);
+    if (st != IRM_OK) return st;
+    if (hit_capacity > ctx->chunk_cap || n_slot_tokens > ctx->cfg.max_tokens) return IRM_ERR_CAPACITY;
+    hipStream_t s = (hipStream_t)stream;
+    const rows_launch k = {ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode, ctx->xcd_ranges, ctx->reattach_grid,
+                           ctx->cfg.pair_mode, ctx->cfg.row_format, ctx->cfg.n_layers,
+                           ctx->d_trig, ctx->d_tiles, ctx->tile_cap, ctx->d_plan, ctx->d_err};
+    hipLaunchKernelGGL(reattach_plan, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits, hit_capacity,
+                       ctx->d_inv_freq, src_rows, n_slot_tokens, k.d_trig, k.d_tiles, k.tile_cap,
+                       k.waves * k.rows_per_wave, k.pair_mode, k.d_plan, k.d_err);
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
-    hipLaunchKernelGGL(pick_kernel(ctx->block_waves, ctx->rows_per_wave, ctx->mem_mode, ctx->cfg.row_format),
-                       dim3(grid_x, ctx->cfg.n_layers), dim3(ctx->block_waves * 64), 0, s,
-                       d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
-                       d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, ctx->xcd_ranges, ctx->cfg.pair_mode,
-                       ctx->d_err);
+    rows_enqueue(k, d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
+                 d_dst_slots, n_slot_tokens, hit_capacity, s);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;

@@ -5,10 +5,11 @@ chained on one stream).
 Integer stages are compared bit for bit on every token and chunk.  Re-attached
 rows are recomputed by the oracle: all of them for c0, c1 and c3; for c2 and c4
 (tens to hundreds of GB) a seeded sample -- every layer of 256 random hits and
-three layers of every hit's first and last row -- plus checks that hold at any
-size: c_KV of every re-attached row equals its source row bit for bit, pair
-norms of k_r survive the rotation to bf16 rounding, and rows no hit covers keep
-the sentinel.
+every layer of every hit's first and last row -- plus checks that hold at any
+size and run on EVERY layer: c_KV of every re-attached row equals its source row
+bit for bit, pair norms of k_r survive the rotation to bf16 rounding, and rows no
+hit covers keep the sentinel.  The paper's own chunking rule (mask 0x7F, chunks of
+32..512 tokens) runs the same checks at the c1 and c2 sizes.
 """
 import numpy as np
 import pytest
@@ -109,16 +110,54 @@ def test_full_size_sampled(name):
         sample = np.sort(rng.choice(len(hits), size=256, replace=False))
         stats = verify_reattach(w, hits, rig.src, rig.dst, hit_sel=sample, what=f"{w.name} sample")
         assert stats["rows"] == int(hits.len[sample].sum()) * L
-        # first and last row of every hit, three layers
+        # first and last row of every hit, every layer (a few layers at a time)
         ends = orc.Hits(np.concatenate([hits.src_row, hits.src_row + hits.len - 1]),
                         np.concatenate([hits.dst_tok, hits.dst_tok + hits.len - 1]),
                         np.ones(2 * len(hits), np.uint32), np.concatenate([hits.delta, hits.delta]))
-        verify_reattach(w, ends, rig.src, rig.dst, layers=[0, L // 2, L - 1], what=f"{w.name} ends")
-        check_properties(rig, [0, L // 2, L - 1] if name == "c4" else range(0, L, 4))
+        for l0 in range(0, L, 16):
+            verify_reattach(w, ends, rig.src, rig.dst, layers=range(l0, min(L, l0 + 16)), what=f"{w.name} ends")
+        check_properties(rig, range(L))
         if name == "c4":
             assert len(rig.o["reg"]["hash"]) == 4194304 and w.table_slots == int(np.ceil(4194304 / 0.7))
         if name == "c2":
             assert np.abs(hits.delta).max() < 16384 and w.n_req == 64
+    finally:
+        rig.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_full_size_paper_native_rule(name):
+    """The paper's own CDC rule (Sec. 7.2 "CDC boundary rule", App. B: low 7 bits, chunks of 32..512
+    tokens, about 2.4 times as many and as short hits) end to end at full size: front end bit for bit,
+    all re-attached rows of c1 and a sample of c2 against the oracle, the size-independent checks on
+    every layer."""
+    w = wl.make_workload(name, orc.cdc_chunk, size="full", cdc="paper")
+    assert (w.mask, w.min_chunk, w.max_chunk) == (0x7F, 32, 512)
+    rig = Rig(w)
+    try:
+        rig.serve()
+        assert rig.s.error_flags() == 0
+        check_front(rig)
+        hits = rig.o["hits"]
+        L = w.n_layers
+        assert 100 < hits.len.mean() < 190 and hits.len.max() <= 512 and hits.len.min() >= 32
+        if name == "c1":
+            total = 0
+            for l0 in range(0, L, 9):
+                total += verify_reattach(w, hits, rig.src, rig.dst, layers=range(l0, min(L, l0 + 9)),
+                                         what=f"{w.name} paper rule")["rows"]
+            assert total == rig.o["hit_tokens"] * L
+        else:
+            rng = np.random.default_rng(4100)
+            sample = np.sort(rng.choice(len(hits), size=256, replace=False))
+            verify_reattach(w, hits, rig.src, rig.dst, hit_sel=sample, what=f"{w.name} paper rule, sample")
+            ends = orc.Hits(np.concatenate([hits.src_row, hits.src_row + hits.len - 1]),
+                            np.concatenate([hits.dst_tok, hits.dst_tok + hits.len - 1]),
+                            np.ones(2 * len(hits), np.uint32), np.concatenate([hits.delta, hits.delta]))
+            for l0 in range(0, L, 9):
+                verify_reattach(w, ends, rig.src, rig.dst, layers=range(l0, min(L, l0 + 9)),
+                                what=f"{w.name} paper rule, ends")
+        check_properties(rig, range(L))
     finally:
         rig.close()
 

@@ -263,6 +263,32 @@ def test_reattach_special_deltas_and_tile_tails():
         s.close()
 
 
+@pytest.mark.parametrize("waves,rpw,grid", [(8, 2, 0), (8, 2, 8), (8, 2, 64), (8, 4, 0), (4, 4, 16), (16, 2, 0),
+                                            (4, 8, 24), (16, 4, 8)])
+@pytest.mark.parametrize("name,slots", [("c2", "permuted"), ("c4", "contiguous")])
+def test_reattach_launch_shapes(name, slots, waves, rpw, grid):
+    """Every launch shape of the row kernel writes the same rows: tile shapes, and grids smaller
+    than the tile count, where a workgroup walks several tiles.  All rows against the oracle; rows
+    no hit covers keep the sentinel."""
+    w = small(name, slots=slots)
+    rig = Rig(w)
+    try:
+        for knob, value in ((4, 16), (1, rpw), (4, waves), (0, grid)):
+            B.irm_ctx_tune(rig.s.ctx, knob, value)
+        hits = rig.o["hits"]
+        d_hits, d_n = hits_to_dev(hits, rig.buf["cap"])
+        for _ in range(2):
+            rig.dst.view(torch.int16).fill_(wl.SENTINEL_BF16 - 0x10000 if wl.SENTINEL_BF16 >= 0x8000 else wl.SENTINEL_BF16)
+            rig.reattach(d_hits, d_n)
+            assert rig.s.error_flags() == 0
+            stats = verify_reattach(w, hits, rig.src, rig.dst, what=f"{w.name} {waves}x{rpw} g{grid}")
+            assert stats["rows"] == rig.o["hit_tokens"] * w.n_layers
+            untouched = ~covered_rows(w, hits)
+            assert np.all(bits(rig.dst)[:, untouched] == wl.SENTINEL_BF16)
+    finally:
+        rig.close()
+
+
 def test_reattach_no_hits_and_bad_indices_are_skipped_and_flagged():
     L, rows = 1, 256
     s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, L, wl.inv_freq_plain(), 1024, 1, DEV)

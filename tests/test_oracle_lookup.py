@@ -120,12 +120,15 @@ def test_length_guard_and_first_wins():
     assert hits.src_row.tolist() == [1, 3]
 
 
+@pytest.mark.parametrize("cdc", ["config", "paper"])
 @pytest.mark.parametrize("name", wl.CONFIG_NAMES)
-def test_planted_requests_are_recovered(name):
+def test_planted_requests_are_recovered(name, cdc):
     """End-to-end closed form: chunk + fingerprint + lookup of an assembled request
     returns exactly the planted pool chunks (position independence of the whole
-    front end), each with delta = new position - stored position."""
-    w = wl.make_workload(name, orc.cdc_chunk, size="small")
+    front end), each with delta = new position - stored position.  Under the measured
+    configurations' rule and under the paper's own (Sec. 7.2, App. B: 7 bits, 32..512)."""
+    w = wl.make_workload(name, orc.cdc_chunk, size="small", cdc=cdc)
+    assert (w.mask, w.min_chunk, w.max_chunk) == ((0xFF, 64, 1024) if cdc == "config" else (0x7F, 32, 512))
     st, ln, rco = orc.cdc_chunk(w.tokens, w.req_offsets, w.gear, w.mask, w.min_chunk, w.max_chunk)
     assert st.astype(np.int64).tolist() == w.piece_start.tolist()
     assert ln.astype(np.int64).tolist() == w.piece_len.tolist()
