@@ -231,6 +231,29 @@ irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
                         const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
                         void *stream);
 
+/* irm_reattach for callers that cannot allocate device memory and hold no context: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arithmetic, kernels, preconditions and results as irm_reattach; what a context would
+ * supply comes as arguments (inv_freq: HOST array of the 32 fp32 inverse frequencies;
+ * n_layers, pair_mode, row_format as in irm_config), and the call's scratch (tile list,
+ * per-hit rotation table) lives in a fixed array inside the library's device image, about
+ * 1.5 MB on every GPU the library runs on, held until the process ends.  The call
+ * allocates nothing, frees nothing and does not synchronise.
+ *   n_slot_tokens  <= IRM_REATTACH_STATIC_MAX_TOKENS, hit_capacity <= IRM_REATTACH_STATIC_MAX_HITS
+ *                  (else IRM_ERR_CAPACITY, nothing is launched)
+ *   d_error_flags  optional device word the kernels OR the IRM_FLAG_* bits into (the
+ *                  caller clears and reads it); NULL: the bits are dropped
+ * All calls on one GPU share that GPU's array: calls that overlap in time on the same GPU
+ * (two streams, two threads) race on it and must be ordered by the caller. */
+#define IRM_REATTACH_STATIC_MAX_TOKENS 131072u
+#define IRM_REATTACH_STATIC_MAX_HITS 4096u
+irm_status irm_reattach_static(const float *inv_freq, uint32_t n_layers, uint32_t pair_mode, uint32_t row_format,
+                               const void *const *d_src_layer_ptrs, uint64_t src_row_stride_bytes,
+                               uint64_t src_rows, void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,
+                               uint64_t dst_rows, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
+                               const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
+                               uint32_t *d_error_flags, void *stream);
+
 /* Split-pool variant of irm_reattach (App. C "Split TokenToKVPool"): the shared,
  * content-addressed pool keeps the position-free c_KV, which is only referenced; the
  * 64-dim k_r slice alone is materialised per request.  For every hit h, j < len,

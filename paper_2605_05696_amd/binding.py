@@ -25,7 +25,8 @@ IRM_ROW_BF16, IRM_ROW_FP8 = 0, 1
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
            "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
-           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows", "irm_reattach_ref", "irm_attend_ref", "irm_attend_ref_workspace_bytes")
+           "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows", "irm_reattach_ref", "irm_attend_ref", "irm_attend_ref_workspace_bytes",
+           "irm_reattach_static")
 
 
 class IrmError(RuntimeError):
@@ -76,6 +77,10 @@ def lib():
         L.irm_lookup.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, vp, vp, vp, vp]
         L.irm_reattach.argtypes = [vp, vp, u64, u64, vp, u64, u64, vp, u64, vp, vp, u32, vp]
         L.irm_table_insert_counted.argtypes = [vp, vp, vp, vp, u32, vp]
+        L.irm_reattach_static.argtypes = [ctypes.POINTER(ctypes.c_float), u32, u32, u32, vp, u64, u64, vp, u64, u64,
+                                          vp, u64, vp, vp, u32, vp, vp]
+        L.irm_s1_windows.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, u32, u32, vp, vp, vp, vp, vp, vp, vp, u32,
+                                     vp, vp]
         L.irm_reattach_ref.argtypes = [vp, u64, vp, vp, u64, vp, vp, u64, vp, vp, u32, vp]
         L.irm_attend_ref_workspace_bytes.argtypes = [u32, u32, u32]
         L.irm_attend_ref.argtypes = [vp, vp, u32, u32, vp, u64, u64, vp, vp, vp, vp, u64, vp, u32, ctypes.c_float, u32,
@@ -301,6 +306,30 @@ def irm_reattach(ctx, d_src_layer_ptrs, src_row_stride_bytes, src_rows, d_dst_la
         _dev(d_dst_layer_ptrs, i64, "d_dst_layer_ptrs"), dst_row_stride_bytes, dst_rows,
         _dev(d_dst_slots, i32, "d_dst_slots"), d_dst_slots.numel(), _dev(d_hits, i32, "d_hits"),
         _dev(d_n_hits, i32, "d_n_hits"), d_hits.shape[0], _stream(stream)))
+
+
+REATTACH_STATIC_MAX_TOKENS, REATTACH_STATIC_MAX_HITS = 131072, 4096
+
+
+def irm_reattach_static(inv_freq, n_layers, pair_mode, row_format, d_src_layer_ptrs, src_row_stride_bytes, src_rows,
+                        d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows, d_dst_slots, d_hits, d_n_hits,
+                        d_error_flags=None, stream=None) -> None:
+    """irm_reattach without a context: inv_freq is a host array of 32 floats; d_error_flags an
+    optional int32 device tensor of one element the kernels OR their flags into."""
+    import torch
+    i32, i64 = torch.int32, torch.int64
+    if d_hits.dim() != 2 or d_hits.shape[1] != 4:
+        raise TypeError("d_hits: need shape [capacity, 4]")
+    f = np.ascontiguousarray(inv_freq, np.float32)
+    if f.shape != (32,):
+        raise TypeError("inv_freq: need 32 floats")
+    _check("irm_reattach_static", lib().irm_reattach_static(
+        f.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), n_layers, pair_mode, row_format,
+        _dev(d_src_layer_ptrs, i64, "d_src_layer_ptrs"), src_row_stride_bytes, src_rows,
+        _dev(d_dst_layer_ptrs, i64, "d_dst_layer_ptrs"), dst_row_stride_bytes, dst_rows,
+        _dev(d_dst_slots, i32, "d_dst_slots"), d_dst_slots.numel(), _dev(d_hits, i32, "d_hits"),
+        _dev(d_n_hits, i32, "d_n_hits"), d_hits.shape[0],
+        None if d_error_flags is None else _dev(d_error_flags, i32, "d_error_flags"), _stream(stream)))
 
 
 def kr_slice_pointers(pool):

@@ -114,6 +114,28 @@ __global__ __launch_bounds__(256) void reattach_plan(const irm_hit *__restrict__
               pair_mode, plan, err);
 }
 
+// the same with the 32 frequencies passed by value (a caller without a context has no device copy)
+struct irm_freq32 {
+    float v[IRM_KR_PAIRS];
+};
+
+__global__ __launch_bounds__(256) void reattach_plan_byval(const irm_hit *__restrict__ hits,
+                                                           const uint32_t *__restrict__ n_hits_p,
+                                                           uint32_t hit_capacity, irm_freq32 freq, uint64_t src_rows,
+                                                           uint64_t n_slot_tokens, float2 *__restrict__ trig,
+                                                           irm_tile *__restrict__ tiles, uint32_t tile_cap,
+                                                           uint32_t tile_rows, uint32_t pair_mode,
+                                                           uint32_t *__restrict__ plan, uint32_t *err)
+{
+    __shared__ float f[IRM_KR_PAIRS];
+#pragma unroll
+    for (int i = 0; i < IRM_KR_PAIRS; ++i)             // constant indices: the values come straight from the argument block
+        if (threadIdx.x == (uint32_t)i) f[i] = freq.v[i];
+    __syncthreads();
+    plan_body(hits, n_hits_p, hit_capacity, f, src_rows, n_slot_tokens, trig, tiles, tile_cap, tile_rows, pair_mode,
+              plan, err);
+}
+
 // ---- rows ----------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
@@ -669,5 +691,83 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;
     }
+    return irm_launch_status();
+}
+
+// ---- irm_reattach for callers that cannot allocate ----------------------------------------
+// Same kernels; the plan (tile list, per-hit rotation table, tile count) lives in a static
+// device array instead of a context's slab.  Every GPU holds its own copy of the array at
+// its own address: the address is looked up once per device, with that device current, and
+// host code only ever uses that pointer (the array's name is not a device address on the
+// host side).  Nothing in the array has to start at zero: the plan kernel writes the tile
+// count, the tiles and the table before the row kernel reads them.
+#define IRM_STATIC_TILE_ROWS 16u     // 8 waves x 2 rows, the row kernel's default shape
+#define IRM_STATIC_TILE_CAP (IRM_REATTACH_STATIC_MAX_TOKENS / IRM_STATIC_TILE_ROWS + IRM_REATTACH_STATIC_MAX_HITS)
+#define IRM_STATIC_HEAD_BYTES 256u   // word 0: tile count; word 16: error word of callers that pass none
+#define IRM_STATIC_TILES_BYTES (IRM_STATIC_TILE_CAP * 16u)
+#define IRM_STATIC_TRIG_BYTES (IRM_REATTACH_STATIC_MAX_HITS * IRM_KR_PAIRS * 8u)
+#define IRM_STATIC_BYTES (IRM_STATIC_HEAD_BYTES + IRM_STATIC_TILES_BYTES + IRM_STATIC_TRIG_BYTES)
+#define IRM_STATIC_MAX_DEVICES 64
+
+static __device__ __align__(256) unsigned char scratch[IRM_STATIC_BYTES];
+
+#include <mutex>
+static std::mutex g_static_lock;
+static unsigned char *g_static_ptr[IRM_STATIC_MAX_DEVICES];   // per device: where `scratch` lives there
+
+// device address of this device's copy of `scratch` (first call on a device looks it up)
+static irm_status static_scratch(unsigned char **out)
+{
+    int device = -1;
+    IRM_HIP_TRY(hipGetDevice(&device));
+    if (device < 0 || device >= IRM_STATIC_MAX_DEVICES) return IRM_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_static_lock);
+    if (!g_static_ptr[device]) {
+        unsigned char *ptr = nullptr;
+        IRM_HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return IRM_ERR_DEVICE;
+        g_static_ptr[device] = ptr;
+    }
+    *out = g_static_ptr[device];
+    return IRM_OK;
+}
+
+extern "C" irm_status irm_reattach_static(const float *inv_freq, uint32_t n_layers, uint32_t pair_mode,
+                                          uint32_t row_format, const void *const *d_src_layer_ptrs,
+                                          uint64_t src_row_stride_bytes, uint64_t src_rows,
+                                          void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes,
+                                          uint64_t dst_rows, const int32_t *d_dst_slots, uint64_t n_slot_tokens,
+                                          const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
+                                          uint32_t *d_error_flags, void *stream)
+{
+    if (!inv_freq) return IRM_ERR_INVALID_ARG;
+    if (pair_mode > IRM_PAIR_INTERLEAVED || row_format > IRM_ROW_FP8) return IRM_ERR_UNSUPPORTED;
+    if (n_layers < 1 || n_layers > 4096) return IRM_ERR_INVALID_ARG;
+    irm_freq32 freq;
+    for (int i = 0; i < IRM_KR_PAIRS; ++i) {
+        if (!(inv_freq[i] == inv_freq[i]) || inv_freq[i] - inv_freq[i] != 0.0f) return IRM_ERR_INVALID_ARG;
+        freq.v[i] = inv_freq[i];
+    }
+    const irm_status st = reattach_check(row_format, d_src_layer_ptrs, src_row_stride_bytes, src_rows,
+                                         d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows, d_dst_slots,
+                                         n_slot_tokens, d_hits, d_n_hits, hit_capacity);
+    if (st != IRM_OK) return st;
+    if (n_slot_tokens > IRM_REATTACH_STATIC_MAX_TOKENS || hit_capacity > IRM_REATTACH_STATIC_MAX_HITS)
+        return IRM_ERR_CAPACITY;                        // beyond what the static array was sized for
+    unsigned char *base = nullptr;
+    const irm_status got = static_scratch(&base);
+    if (got != IRM_OK) return got;
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t *plan = (uint32_t *)base;
+    uint32_t *err = d_error_flags ? d_error_flags : (uint32_t *)base + 16;
+    // fp8 rows share 128-byte lines with their neighbours: cached accesses (as in a context)
+    const rows_launch k = {8u, 2u, row_format == IRM_ROW_FP8 ? 0u : 3u, 1u, 0u, pair_mode, row_format, n_layers,
+                           (float2 *)(base + IRM_STATIC_HEAD_BYTES + IRM_STATIC_TILES_BYTES),
+                           (irm_tile *)(base + IRM_STATIC_HEAD_BYTES), IRM_STATIC_TILE_CAP, plan, err};
+    hipLaunchKernelGGL(reattach_plan_byval, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,
+                       hit_capacity, freq, src_rows, n_slot_tokens, k.d_trig, k.d_tiles, k.tile_cap,
+                       IRM_STATIC_TILE_ROWS, pair_mode, k.d_plan, k.d_err);
+    rows_enqueue(k, d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
+                 d_dst_slots, n_slot_tokens, hit_capacity, s);
     return irm_launch_status();
 }

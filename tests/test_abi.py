@@ -103,6 +103,14 @@ def test_null_arguments_are_rejected():
     assert big > 1 << 32
     assert L.irm_attend_ref_workspace_bytes(65535, 8192, 4) == big
     assert B.irm_attend_ref_workspace_bytes(65535, 8192, 4) == big
+    # the entry point without a context: sizes beyond its static scratch are refused before any device call
+    f32 = (ctypes.c_float * 32)(*([1.0] * 32))
+    one = ctypes.c_void_p(16)
+    assert L.irm_reattach_static(None, 1, 0, 0, one, 1152, 1, one, 1152, 1, one, 1, one, one, 1, None, None) == B.IRM_ERR_INVALID_ARG
+    assert L.irm_reattach_static(f32, 1, 0, 0, one, 1152, 1, one, 1152, 1, one, B.REATTACH_STATIC_MAX_TOKENS + 1, one, one,
+                                 1, None, None) == B.IRM_ERR_CAPACITY
+    assert L.irm_reattach_static(f32, 1, 0, 0, one, 1152, 1, one, 1152, 1, one, 1, one, one,
+                                 B.REATTACH_STATIC_MAX_HITS + 1, None, None) == B.IRM_ERR_CAPACITY
     flags = ctypes.c_uint32()
     assert L.irm_ctx_error_flags(None, None, ctypes.byref(flags)) == B.IRM_ERR_INVALID_ARG
     assert L.irm_ctx_tune(None, 0, 0) == B.IRM_ERR_INVALID_ARG
