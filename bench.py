@@ -62,20 +62,25 @@ def main() -> int:
     ap.add_argument("--row-stride", type=int, default=0, metavar="BYTES",
                     help="hit stage, --reattach full: row stride of both pools in bytes, a multiple of 16 "
                          "(0 = packed rows; 768 puts every fp8 row on its own 128-byte lines)")
+    ap.add_argument("--layer-pad", type=int, default=0, metavar="ROWS",
+                    help="--reattach kr / kr-dense: rows of padding behind every layer of the k_r pools, so that the "
+                         "layer stride is not a power of two")
     ap.add_argument("--heads", type=int, default=16, help="attend stage: query rows per request, a multiple of 16 "
                                                               "(heads, or new tokens x heads over a cached prefix)")
     ap.add_argument("--linear-rows", action="store_true",
                     help="attend stage: every slot refers to the pool row of the same number (no rotation), i.e. "
                          "purely sequential reads: the yardstick for what the gather pattern costs")
     ap.add_argument("--splits", type=int, default=8, help="attend stage: workgroups per request and 16 heads")
-    ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1", "attend"],
+    ap.add_argument("--stage", default="hit", choices=["hit", "admit", "s1", "attend", "yardstick"],
                     help="hit = the cache-hit path (the headline); admit = the miss path on a cold registry: "
                          "every chunk of the batch is copied from the request pool into the shared pool and "
                          "registered (irm_admit alone is timed, with events on its stream); s1 = the hit path "
                          "on UNALIGNED batches followed by the S1 fallback (128-token windows inside the chunks "
                          "that missed, end-anchored): eight calls per step; attend = the no-materialise scheme end to end: "
                          "front end + irm_reattach_ref once, then irm_attend_ref (decode attention over the "
-                         "references, k_r rotated on load) on every layer")
+                         "references, k_r rotated on load) on every layer; yardstick = no part of the path: plain read-only, "
+                         "write-only and copy streams over 9 GiB in a sweep of launch shapes (irm_yardstick), the "
+                         "bandwidth this machine gives a kernel that only moves bytes")
     ap.add_argument("--streams", type=int, default=1,
                     help="batches in flight: step k runs on stream k mod S with its own context and destination "
                          "pool, so the front end of one batch overlaps the row kernel of another (hit and s1 "
@@ -89,10 +94,15 @@ def main() -> int:
     ap.add_argument("--calibrate", type=int, default=0, metavar="N",
                     help="also run N plain 1 GiB copies (irm_calibrate_copy) before the timed loop: the "
                          "known-traffic yardstick for hardware counters")
-    ap.add_argument("--kernel-timing", type=int, default=4, metavar="E",
+    ap.add_argument("--kernel-timing", type=int, default=None, metavar="E",
                     help="HIP events around every E-th row-kernel launch of each batch variant inside the "
-                         "timed region (0 = none, no roofline)")
+                         "timed region (0 = none, no roofline; default: every 4th on c0 and c1, whose launches "
+                         "take a fraction of a millisecond, every launch on the larger workloads)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU budget of the oracle baseline")
+    ap.add_argument("--extras", default=None,
+                    help="'all' or '': after the headline and the secondary workloads, also run the path's other "
+                         "variants (split pool, fp8 rows, miss path, S1 fallback, rotate-on-load attention) and "
+                         "report them in the 'other_paths' block (default with the c4 headline: all)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -100,6 +110,9 @@ def main() -> int:
               "(it would shard by layer or by request, with no exchange step)", file=sys.stderr)
         return 2
 
+    if args.stage == "yardstick":
+        print(json.dumps(bench_yardstick(args)), flush=True)
+        return 0
     plain = (args.stage == "hit" and args.reattach == "full" and args.rows == "bf16" and args.streams == 1
              and not args.graph and not args.row_stride and args.size == "full")
     if args.secondary is None:
@@ -116,8 +129,35 @@ def main() -> int:
                                      "hit_tokens_per_step": sub["config"]["hit_tokens_per_step"],
                                      "hits_per_step": sub["config"]["hits_per_step"],
                                      "roofline": sub["roofline"]})
+    if args.extras is None:
+        args.extras = "all" if plain and args.workload == "c4" and args.cdc == "config" and args.secondary else ""
+    if args.extras:
+        out["other_paths"] = []
+        for flags in EXTRAS:
+            a = with_defaults(args, flags.get("workload", "c2"), "config", flags.get("steps"), flags.get("warmup"),
+                              flags.get("variants"), cpu=False)
+            for k, v in flags.items():
+                setattr(a, k, v)
+            sub = run(a)
+            out["other_paths"].append({"what": flags["what"], "metric": sub["metric"], "workload": sub["config"]["workload"],
+                                       "steps": sub["steps"], "ms_per_step": sub["ms_per_step"], "value": sub["value"],
+                                       "unit": sub["unit"], "roofline": sub["roofline"]})
     print(json.dumps(out), flush=True)
     return 0
+
+
+# the path's other variants, each a set of flags of this script (one short run each)
+EXTRAS = [
+    dict(what="split pool, k_r only, packed source rows", workload="c2", reattach="kr", steps=24, warmup=4),
+    dict(what="split pool, k_r only, dense k_r_base source", workload="c2", reattach="kr-dense", steps=24, warmup=4),
+    dict(what="no-materialise variant: references and rotation table only", workload="c2", reattach="ref", steps=40, warmup=5),
+    dict(what="fp8 pool rows (656 B)", workload="c2", rows="fp8"),
+    dict(what="fp8 pool rows (656 B), 32 K-token request", workload="c1", rows="fp8"),
+    dict(what="miss path, irm_admit alone", workload="c2", stage="admit", steps=8, warmup=2),
+    dict(what="hit path + S1 window fallback on unaligned batches", workload="c1", stage="s1"),
+    dict(what="rotate-on-load decode attention over the references, 16 heads", workload="c2", stage="attend",
+         splits=4, steps=6, warmup=2),
+]
 
 
 # per workload: timed steps, warm-up steps, request batches cycled (sized so that every run takes seconds)
@@ -132,6 +172,8 @@ def with_defaults(args, name, cdc, steps, warmup, variants, cpu=True):
     a.steps = d[0] if steps is None else steps
     a.warmup = d[1] if warmup is None else warmup
     a.variants = d[2] if variants is None else variants
+    if a.kernel_timing is None:
+        a.kernel_timing = 4 if name in ("c0", "c1") else 1
     if not cpu:
         a.no_cpu_baseline = True
     return a
@@ -215,12 +257,13 @@ def run(args) -> dict:
         hit_index = torch.full((w0.dst_rows,), -1, dtype=torch.int32, device=dev)
         bytes_per_token_layer = 12.0 / L                            # 4 B slot read, 8 B written, per token
     else:
-        dst = torch.zeros((L, w0.dst_rows, 64), dtype=torch.bfloat16, device=dev)
+        dst = torch.zeros((L, w0.dst_rows + args.layer_pad, 64), dtype=torch.bfloat16, device=dev)[:, :w0.dst_rows]
         dst_ptrs = B.kr_layer_pointers(dst)
         if args.reattach == "kr":
             kr_src_ptrs, kr_src_stride = B.kr_slice_pointers(src), ROW_BYTES
         else:
-            kr_base = torch.empty((L, w0.src_rows, 64), dtype=torch.bfloat16, device=dev)
+            kr_base = torch.empty((L, w0.src_rows + args.layer_pad, 64), dtype=torch.bfloat16,
+                                  device=dev)[:, :w0.src_rows]
             for l in range(L):
                 kr_base[l].copy_(src[l, :, 512:])
             kr_src_ptrs, kr_src_stride = B.kr_layer_pointers(kr_base), 128
@@ -475,6 +518,46 @@ def bench_attend(args, works, sessions, dev_in, pool, stream):
                          "mfma_tflops": (2.0 * (576 + 512) * H * ctx_tokens * kernel_n / (kernel_ms * 1e-3) / 1e12
                                          if kernel_ms > 0 else 0.0),
                          "mfma_peak_tflops": 2500.0}}
+
+
+def bench_yardstick(args):
+    """Read-only, write-only and copy streams in a sweep of launch shapes: what the memory system gives
+    a kernel that does nothing but move bytes (the ceiling of the row kernels)."""
+    import torch
+    from paper_2605_05696_amd import binding as B
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    n = 9 << 30                                                  # divisible by every grid x lanes x vectors x 16 below
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
+    dst = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 256)
+    stream = torch.cuda.Stream(device=dev)
+    rows = []
+    reps = max(1, args.steps or 5)
+    with torch.cuda.stream(stream):
+        for mode, mname in ((B.YARDSTICK_READ, "read"), (B.YARDSTICK_WRITE, "write"), (B.YARDSTICK_COPY, "copy")):
+            for grid in (2048, 4096, 8192, 16384, 65536):
+                for lanes, vec in ((256, 2), (256, 4), (256, 9), (256, 18), (256, 36), (512, 4), (512, 9), (1024, 2),
+                                   (1024, 4)):
+                    if n % (grid * lanes * vec * 16):
+                        continue                                 # ranges must be whole steps
+                    B.irm_yardstick(dst, src, mode, grid, lanes, vec, stream)          # warm-up
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(stream)
+                    for _ in range(reps):
+                        B.irm_yardstick(dst, src, mode, grid, lanes, vec, stream)
+                    b.record(stream)
+                    b.synchronize()
+                    ms = a.elapsed_time(b) / reps
+                    moved = n * (2 if mode == B.YARDSTICK_COPY else 1)
+                    rows.append({"mode": mname, "grid": grid, "lanes": lanes, "vectors_per_lane": vec,
+                                 "ms": ms, "gbs": moved / (ms * 1e-3) / 1e9})
+    best = {m: max((r for r in rows if r["mode"] == m), key=lambda r: r["gbs"]) for m in ("read", "write", "copy")}
+    median = {m: float(np.median([r["gbs"] for r in rows if r["mode"] == m])) for m in ("read", "write", "copy")}
+    # a copy whose reads and writes take turns on the memory bus at their own best rates
+    serial = 2.0 / (1.0 / best["read"]["gbs"] + 1.0 / best["write"]["gbs"])
+    return {"metric": "plain streams over 9 GiB, HBM GB/s by launch shape, 1 MI355X", "unit": "GB/s",
+            "value": best["copy"]["gbs"], "best": best, "median": median,
+            "copy_if_reads_and_writes_took_turns": serial, "peak": HBM_PEAK_GBS, "reps": reps, "shapes": rows}
 
 
 def calibrate(n, dev, stream):

@@ -218,8 +218,10 @@ irm_status irm_lookup(irm_ctx *ctx, const irm_table *table, const uint64_t *d_ch
  *   d_src_layer_ptrs / d_dst_layer_ptrs  device arrays of n_layers device pointers
  *                                        to row 0 of each layer (16-byte aligned)
  *   *_row_stride_bytes                   >= irm_row_bytes(row_format), multiple of 16
- *   src_rows / dst_rows                  rows per layer (bounds; rows outside are skipped
- *                                        and raise IRM_FLAG_ROW_RANGE)
+ *   src_rows / dst_rows                  rows per layer (bounds: a hit that reaches outside the
+ *                                        source pool or past d_dst_slots, and a row whose slot
+ *                                        lies outside the destination pool, are skipped and
+ *                                        raise IRM_FLAG_ROW_RANGE)
  *   d_dst_slots                          int32[n_slots_tokens]: destination row per batch token
  *   d_hits, d_n_hits                     as written by irm_lookup; *d_n_hits <= hit_capacity
  * Destination rows of different hits must not overlap; src and dst pools must
@@ -276,9 +278,9 @@ irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_layer_ptrs,
                            const irm_hit *d_hits, const uint32_t *d_n_hits, uint32_t hit_capacity,
                            void *stream);
 
-/* No-materialise variant of the re-attachment (Sec. 7.2: the rotation is "fuseable into
- * the attention kernel's load path"; App. C: keep k_r_base in HBM so that the rotated
- * tensor never materialises).  No KV is moved.  For every hit h, j < len and
+/* No-materialise variant of the re-attachment (Sec. 7.2 and App. C propose to apply the
+ * rotation inside the attention kernel while it loads the keys, leaving k_r_base in HBM as
+ * it was stored and writing no rotated copy).  No KV is moved.  For every hit h, j < len and
  * slot = d_dst_slots[dst_tok + j]:
  *   d_row_index[slot] = src_row + j   pool row that holds the slot's (c_KV, k_r_base)
  *   d_hit_index[slot] = h             which rotation the load path applies to that row

@@ -24,7 +24,12 @@ extern "C" {
  *         waves x rows-per-wave rows, at least 4
  * knob 5: 1 = irm_cdc_chunk always selects cuts with the serial walk (else only for
  *         requests with more than 4096 candidate positions)
- * knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; its tile is 32 times that) */
+ * knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; its tile is 32 times that)
+ * knob 7: layers a workgroup of the k_r-only kernel keeps its tile for (0 = chosen by batch size)
+ * knob 8: polls one in-kernel wait of irm_attend_ref may take before the wave gives up and raises
+ *         IRM_FLAG_WAIT_TIMEOUT (default 2^18; 0 makes every wait that is not met at once give up:
+ *         for tests of that path, the results of such a call are not to be used)
+ * knob 9: layers of rows a wave of the k_r-only kernel has on their way (2 or 4) */
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
 /* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples
@@ -42,6 +47,20 @@ irm_status irm_ctx_profile_end(irm_ctx *ctx, void *stream, float *total_ms, uint
  * traffic is known exactly (bytes read + bytes written), which calibrates
  * hardware counters and gives the copy bandwidth the machine can reach. */
 irm_status irm_calibrate_copy(void *d_dst, const void *d_src, uint64_t bytes, uint32_t grid, void *stream);
+
+/* Measurement aid: a shaped stream over `bytes` of d_src and/or d_dst.  `grid` workgroups of
+ * `lanes` lanes (a multiple of 64, at most 1024) each own a contiguous range and walk it in
+ * steps of lanes x vectors_per_lane 16-byte vectors (1, 2, 4, 9, 18 or 36 per lane): all loads
+ * of a step are issued before its stores.  IRM_YARDSTICK_COPY reads d_src and writes d_dst
+ * (traffic 2 x bytes), IRM_YARDSTICK_READ only reads d_src (the data must not be the one
+ * pattern that would make it store; any random fill is fine), IRM_YARDSTICK_WRITE only
+ * writes d_dst.  bytes must be a multiple of grid x lanes x vectors_per_lane x 16.  What these
+ * reach bounds what a kernel that moves rows can reach. */
+#define IRM_YARDSTICK_COPY 0u
+#define IRM_YARDSTICK_READ 1u
+#define IRM_YARDSTICK_WRITE 2u
+irm_status irm_yardstick(void *d_dst, const void *d_src, uint64_t bytes, uint32_t mode, uint32_t grid,
+                         uint32_t lanes, uint32_t vectors_per_lane, void *stream);
 
 #ifdef __cplusplus
 }

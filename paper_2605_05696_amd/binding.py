@@ -23,7 +23,7 @@ IRM_FLAG_WAIT_TIMEOUT = 16
 IRM_ROW_BF16, IRM_ROW_FP8 = 0, 1
 
 SYMBOLS = ("irm_ctx_create", "irm_ctx_destroy", "irm_ctx_error_flags", "irm_ctx_tune",
-           "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy",
+           "irm_ctx_profile_begin", "irm_ctx_profile_end", "irm_calibrate_copy", "irm_yardstick",
            "irm_table_create", "irm_table_destroy", "irm_table_insert",
            "irm_cdc_chunk", "irm_chunk_hash", "irm_lookup", "irm_reattach", "irm_reattach_kr", "irm_admit", "irm_table_insert_counted", "irm_s1_windows", "irm_reattach_ref", "irm_attend_ref", "irm_attend_ref_workspace_bytes",
            "irm_reattach_static")
@@ -69,6 +69,7 @@ def lib():
         L.irm_ctx_profile_begin.argtypes = [vp, u32, u32]
         L.irm_ctx_profile_end.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(u32)]
         L.irm_calibrate_copy.argtypes = [vp, vp, u64, u32, vp]
+        L.irm_yardstick.argtypes = [vp, vp, u64, u32, u32, u32, u32, vp]
         L.irm_table_create.argtypes = [vp, u64, ctypes.POINTER(vp)]
         L.irm_table_destroy.argtypes = [vp]
         L.irm_table_insert.argtypes = [vp, vp, vp, u32, vp]
@@ -168,6 +169,19 @@ def irm_calibrate_copy(d_dst, d_src, grid: int = 0, stream=None) -> None:
         raise TypeError("irm_calibrate_copy: need two contiguous device tensors of equal byte size")
     _check("irm_calibrate_copy", lib().irm_calibrate_copy(
         ctypes.c_void_p(d_dst.data_ptr()), ctypes.c_void_p(d_src.data_ptr()), n, grid, _stream(stream)))
+
+
+YARDSTICK_COPY, YARDSTICK_READ, YARDSTICK_WRITE = 0, 1, 2
+
+
+def irm_yardstick(d_dst, d_src, mode: int, grid: int, lanes: int, vectors_per_lane: int, stream=None) -> None:
+    """A shaped read, write or copy stream over two byte tensors of equal size (see irm_measure.h)."""
+    n = d_src.numel() * d_src.element_size()
+    if d_dst.numel() * d_dst.element_size() != n or not d_src.is_contiguous() or not d_dst.is_contiguous():
+        raise TypeError("irm_yardstick: need two contiguous device tensors of equal byte size")
+    _check("irm_yardstick", lib().irm_yardstick(
+        ctypes.c_void_p(d_dst.data_ptr()), ctypes.c_void_p(d_src.data_ptr()), n, mode, grid, lanes,
+        vectors_per_lane, _stream(stream)))
 
 
 def irm_table_create(ctx, n_slots: int) -> ctypes.c_void_p:

@@ -88,13 +88,17 @@ struct att_smem {
 // for each other at all.  Waves of one half may therefore be a tile or more apart, so a sum over
 // them would not say that a tile is whole (or wholly worked off): whoever waits, waits for the
 // slowest of the four counters.  A wait is bounded: a wave that gives up raises
-// IRM_FLAG_WAIT_TIMEOUT and carries on, so every wave reaches the end of the kernel.
+// IRM_FLAG_WAIT_TIMEOUT and carries on, so every wave reaches the end of the kernel.  Whatever
+// a wave then finds in LDS is harmless to follow: every reference slot of the ring holds checked
+// values from the prologue on (a row inside the pool or "no token"), tile data is only ever
+// multiplied, and every global address comes from a checked reference.
 __device__ __forceinline__ void att_signal(uint32_t *counter, uint32_t lane)
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     if (lane == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-__device__ __forceinline__ void att_wait_all(uint32_t *counters, uint32_t target, uint32_t lane, uint32_t *err)
+__device__ __forceinline__ void att_wait_all(uint32_t *counters, uint32_t target, uint32_t lane, uint32_t *err,
+                                             uint32_t spin_limit)
 {
     uint32_t spins = 0;
     for (;;) {
@@ -106,7 +110,7 @@ __device__ __forceinline__ void att_wait_all(uint32_t *counters, uint32_t target
         }
         if ((int32_t)(least - target) >= 0) break;
         __builtin_amdgcn_s_sleep(1);
-        if (++spins > (1u << 18)) {
+        if (++spins > spin_limit) {
             if (lane == 0) atomicOr(err, IRM_FLAG_WAIT_TIMEOUT);
             break;
         }
@@ -346,7 +350,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
     uint64_t pool_rows, const int32_t *__restrict__ kv_slots, const uint32_t *__restrict__ kv_offsets,
     const int32_t *__restrict__ row_index, const int32_t *__restrict__ hit_index, uint64_t dst_rows,
     const float2 *__restrict__ trig, uint32_t trig_hits, float scale_log2, uint32_t pair_mode,
-    float *__restrict__ part_o, float2 *__restrict__ part_ml, uint32_t *err)
+    float *__restrict__ part_o, float2 *__restrict__ part_ml, uint32_t spin_limit, uint32_t *err)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     att_smem *sm = (att_smem *)smem_raw;
@@ -416,18 +420,18 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             att_signal(&sm->landed[cw], lane);
             uint32_t t = 1;                                 // t = tile - tile0; odd tiles use the second set
             for (; t + 1u < 2u * n_pairs; t += 2u) {
-                att_wait_all(sm->consumed, t - 1u, lane, err);
+                att_wait_all(sm->consumed, t - 1u, lane, err, spin_limit);
                 att_land_rows<F8, F8 && !MULTI>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
                 att_signal(&sm->landed[cw], lane);
                 hit2 = att_fire_rows<F8, NT>(r2, sc2, t42, ad, a, lane, ct);           // tile t + 2
                 att_addr_rows<F8>(ad, sm, (t + 3u) & RM, a, cw, lane, ct);
-                att_wait_all(sm->consumed, t, lane, err);
+                att_wait_all(sm->consumed, t, lane, err, spin_limit);
                 att_land_rows<F8, F8 && !MULTI>(r, sc, t4, hit, sm, (t + 1u) & RM, 0u, a, cw, lane, ct);
                 att_signal(&sm->landed[cw], lane);
                 hit = att_fire_rows<F8, NT>(r, sc, t4, ad, a, lane, ct);               // tile t + 3
                 att_addr_rows<F8>(ad, sm, (t + 4u) & RM, a, cw, lane, ct);
             }
-            att_wait_all(sm->consumed, t - 1u, lane, err);  // the last tile, 2 n_pairs - 1: odd
+            att_wait_all(sm->consumed, t - 1u, lane, err, spin_limit);  // the last tile, 2 n_pairs - 1: odd
             att_land_rows<F8, F8 && !MULTI>(r2, sc2, t42, hit2, sm, t & RM, 1u, a, cw, lane, ct);
             att_signal(&sm->landed[cw], lane);
         } else {
@@ -440,7 +444,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
                 // Tile t goes into the buffer tile t - 2 was worked off from.  Request t + 1 at once
                 // after landing t, so that it has a whole tile's time to arrive (more than 18 loads
                 // in flight per lane slow the stream down: measured).
-                att_wait_all(sm->consumed, t - 1u, lane, err);
+                att_wait_all(sm->consumed, t - 1u, lane, err, spin_limit);
                 att_land_rows<F8, F8 && !MULTI>(r, sc, t4, hit, sm, t & RM, t & 1u, a, cw, lane, ct);
                 att_signal(&sm->landed[cw], lane);
                 hit = att_fire_rows<F8, NT>(r, sc, t4, ad, a, lane, ct);               // tile t + 1
@@ -516,6 +520,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             refs_rows(tile0 + 5, sl[5], ref_a_row, ref_a_hit);
 #pragma unroll
             for (uint32_t k = 0; k < 5; ++k) refs_publish(k, rw[k], ht[k]);
+#pragma unroll
+            for (uint32_t k = 5; k < ATT_RING; ++k) refs_publish(k, -2, -1);   // not looked up yet: no token
         }
         ATT_SYNC();                                         // prologue 1
         ATT_SYNC();                                         // prologue 2
@@ -523,7 +529,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
             const uint32_t k = tile - tile0, cur = k & 1u;
             refs_rows(tile + 6, next_sl, req_row, req_hit);
             next_sl = refs_slot(tile + 7);
-            att_wait_all(sm->landed, k + 1u, lane, err);
+            att_wait_all(sm->landed, k + 1u, lane, err, spin_limit);
             // the tile in two halves of 32 tokens, each like a pair's share in the other variant: scores
             // of two blocks of 16 tokens, one softmax step, then 32 blocks of 16 dims with 16x16x32 products
 #pragma nounroll
@@ -651,6 +657,8 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         refs_rows(tile0 + 5, sl[5], ref_a_row, ref_a_hit);
 #pragma unroll
         for (uint32_t k = 0; k < 5; ++k) refs_publish(k, rw[k], ht[k]);
+#pragma unroll
+        for (uint32_t k = 5; k < ATT_RING; ++k) refs_publish(k, -2, -1);       // not looked up yet: no token
     }
     ATT_SYNC();                                             // prologue 1
     ATT_SYNC();                                             // prologue 2
@@ -661,7 +669,7 @@ __global__ __launch_bounds__(512) void attend_ref_split(
         const uint32_t k = tile - tile0, cur = k & 1u;
         refs_rows(tile + 6, next_sl, req_row, req_hit);     // slot ids arrived during the last tile
         next_sl = refs_slot(tile + 7);
-        att_wait_all(sm->landed, k + 1u, lane, err);        // tiles 0 .. k are in place, whole
+        att_wait_all(sm->landed, k + 1u, lane, err, spin_limit);        // tiles 0 .. k are in place, whole
         // S^T for this pair's 32 tokens, two blocks of 16: lane holds S[head lm][token 32 tg + 4 lq + i]
         // and S[head lm][token 32 tg + 16 + 4 lq + i].  Four accumulators, so that neither LDS nor MFMA
         // latency adds up.
@@ -944,7 +952,7 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
     const bool nt = grid_x == 1;                        // see att_ld
     typedef void (*split_kernel_t)(const uint16_t *, uint32_t, const char *, uint64_t, uint64_t, const int32_t *,
                                    const uint32_t *, const int32_t *, const int32_t *, uint64_t, const float2 *,
-                                   uint32_t, float, uint32_t, float *, float2 *, uint32_t *);
+                                   uint32_t, float, uint32_t, float *, float2 *, uint32_t, uint32_t *);
     static const split_kernel_t table[3][2][2] = {      // [groups per workgroup][fp8][streaming loads]
         {{attend_ref_split<false, false, 1>, attend_ref_split<false, true, 1>},
          {attend_ref_split<true, false, 1>, attend_ref_split<true, true, 1>}},
@@ -957,7 +965,7 @@ extern "C" irm_status irm_attend_ref(irm_ctx *ctx, const void *d_q, uint32_t n_r
                        dim3(512), sizeof(att_smem), s,
                        (const uint16_t *)d_q, n_heads, (const char *)d_pool_layer, pool_row_stride_bytes, pool_rows,
                        d_kv_slots, d_kv_offsets, d_row_index, d_hit_index, dst_rows, (const float2 *)d_trig,
-                       trig_hits, scale * ATT_LOG2E, ctx->cfg.pair_mode, part_o, part_ml, ctx->d_err);
+                       trig_hits, scale * ATT_LOG2E, ctx->cfg.pair_mode, part_o, part_ml, ctx->att_spin_limit, ctx->d_err);
     hipLaunchKernelGGL(attend_ref_merge, dim3(ATT_HEADS, n_groups, n_req), dim3(512), 0, s, part_o, part_ml, n_splits, n_heads,
                        d_out, d_lse);
     if (sample) {

@@ -39,6 +39,9 @@ struct irm_ctx {
     uint32_t mem_mode;      // knob 2: bit 0 non-temporal loads, bit 1 non-temporal stores
     uint32_t cdc_serial;    // knob 5: 1 = always use the serial cut selection
     uint32_t kr_rows_per_lane; // knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; tile = 32x that)
+    uint32_t kr_layers_per_wg; // knob 7: layers a workgroup of the k_r-only kernel keeps its tile for (0 = by batch size)
+    uint32_t kr_depth;      // knob 9: layers of rows a wave of the k_r-only kernel has on their way (2 or 4)
+    uint32_t att_spin_limit; // knob 8: polls a wave of the attention kernel spends in one wait before it gives up
     uint32_t xcd_ranges;    // knob 3: 1 = each XCD serves a contiguous range of a layer's tiles
     uint32_t n_cu;
     // one device slab, carved up below
@@ -122,6 +125,39 @@ __device__ __forceinline__ int64_t irm_chunk_pos(const uint32_t *__restrict__ re
         if (req_chunk_offsets[mid] <= c) lo = mid; else hi = mid;
     }
     return (int64_t)pos_base[lo] + ((int64_t)start - (int64_t)req_offsets[lo]);
+}
+
+// (cos, sin) of delta * inv_freq, the angle as an fp64 product with fp64 range reduction
+// (|delta| reaches 1e5: an fp32 angle would already cost half a bf16 ulp); delta == 0 is the
+// exact identity.
+__device__ __forceinline__ float2 irm_hit_trig(int32_t delta, float inv_freq)
+{
+    if (delta == 0) return make_float2(1.0f, 0.0f);
+    const double phi = (double)delta * (double)inv_freq;
+    double sn, cn;
+    sincos(phi, &sn, &cn);
+    return make_float2((float)cn, (float)sn);
+}
+
+// Where pair i of a hit sits in its 32-entry table.  Half-split: entry i is pair i.
+// Interleaved: the lane that holds the 16-byte vectors j and 4+j of a row owns pairs 4j+w and
+// 16+4j+w (w < 4); they are stored side by side at entries 8j+2w and 8j+2w+1, where the
+// half-split kernel code finds the (cos, sin) of the two halves of word w.
+__device__ __forceinline__ uint32_t irm_trig_slot(uint32_t pair_mode, uint32_t i)
+{
+    return pair_mode ? 8u * ((i & 15u) >> 2) + 2u * (i & 3u) + (i >> 4) : i;
+}
+
+// tile k of a hit that is cut into tiles of tile_rows rows
+__device__ __forceinline__ irm_tile irm_tile_of(const irm_hit &hit, uint32_t h, uint32_t k, uint32_t tile_rows)
+{
+    const uint32_t done = k * tile_rows;
+    irm_tile tile;
+    tile.src_row0 = hit.src_row + done;
+    tile.dst_tok0 = hit.dst_tok + done;
+    tile.n_rows = hit.len - done < tile_rows ? hit.len - done : tile_rows;
+    tile.hit = h;
+    return tile;
 }
 
 __device__ __forceinline__ uint32_t irm_wave_id()

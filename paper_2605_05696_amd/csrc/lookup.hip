@@ -61,6 +61,13 @@ __global__ __launch_bounds__(256) void lookup_probe(const uint64_t *__restrict__
     if (n_chunks > chunk_capacity) n_chunks = chunk_capacity;
     if (c < n_chunks) probe_one(keys, vals, n_slots, chunk_hash, chunk_start, chunk_len, req_chunk_offsets,
                                 req_offsets, pos_base, n_req, carve_out, c, chunk_entry, hit_tmp);
+    if (gridDim.x == 1) {
+        // the only workgroup reads back what it wrote itself: no device-wide fence, no ticket
+        __threadfence_block();
+        __syncthreads();
+        lookup_compact(hit_tmp, n_chunks, hits, n_hits, hit_tokens);
+        return;
+    }
     // publish, take a ticket; the last workgroup compacts and leaves the counter at zero
     __threadfence();
     __syncthreads();

@@ -58,20 +58,7 @@ __device__ __forceinline__ void plan_body(const irm_hit *__restrict__ hits, cons
     if (h < n_hits) {
         hit = hits[h];
         nt = hit_tiles(hit, src_rows, n_slot_tokens, tile_rows);
-        // (cos, sin) of delta * inv_freq[i]
-        float2 cs = make_float2(1.0f, 0.0f);            // delta == 0: exact identity
-        if (hit.delta != 0) {
-            const double phi = (double)hit.delta * (double)inv_freq[i];
-            double sn, cn;
-            sincos(phi, &sn, &cn);
-            cs = make_float2((float)cn, (float)sn);
-        }
-        // Table order.  Half-split: entry i is pair i.  Interleaved: the lane that holds the
-        // 16-byte vectors j and 4+j of a row owns pairs 4j+w and 16+4j+w (w < 4); they are
-        // stored side by side at entries 8j+2w and 8j+2w+1, where the half-split kernel
-        // code finds the (cos, sin) of the two halves of word w.
-        const uint32_t at = pair_mode ? 8u * ((i & 15u) >> 2) + 2u * (i & 3u) + (i >> 4) : i;
-        trig[(uint64_t)h * IRM_KR_PAIRS + at] = cs;
+        trig[(uint64_t)h * IRM_KR_PAIRS + irm_trig_slot(pair_mode, i)] = irm_hit_trig(hit.delta, inv_freq[i]);
         if (i == 0 && nt == 0 && hit.len != 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
     }
     if (i == 0) local_nt[threadIdx.x >> 5] = nt;
@@ -90,13 +77,7 @@ __device__ __forceinline__ void plan_body(const irm_hit *__restrict__ hits, cons
                 atomicOr(err, IRM_FLAG_CHUNK_OVERFLOW);
                 break;
             }
-            const uint32_t done = k * tile_rows;
-            irm_tile tile;
-            tile.src_row0 = hit.src_row + done;
-            tile.dst_tok0 = hit.dst_tok + done;
-            tile.n_rows = hit.len - done < tile_rows ? hit.len - done : tile_rows;
-            tile.hit = h;
-            tiles[t] = tile;
+            tiles[t] = irm_tile_of(hit, h, k, tile_rows);
         }
         if (h == n_hits - 1 && i == 0) plan[0] = t0 + nt < tile_cap ? t0 + nt : tile_cap;
     }
@@ -458,18 +439,24 @@ static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode, ui
 // pool row each destination row refers to (once, by the layer-0 workgroups).
 // A lane keeps its (cos, sin) values for Q rows: the table read is as large as two rows'
 // worth of data, so a tile is 32 * Q rows.
-template <int Q>
+// Grid (tile slots, layer groups): a row's k_r is only 128 bytes, so one tile and layer is a
+// few KB, too little for a workgroup of its own (the dispatcher, not the memory, then sets
+// the pace: 0.63 of peak).  A workgroup therefore keeps its tile for `lpw` layers: the tile
+// record, the slots and the (cos, sin) values are fetched once, the rows of the next layer
+// are requested before the current ones are rotated and stored (D layers on their way).
+template <int Q, int D>
 __global__ __launch_bounds__(256) void reattach_kr_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
     uint64_t kr_stride, uint64_t kr_rows, const int32_t *__restrict__ dst_slots,
     const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
-    int32_t *__restrict__ ckv_index, uint32_t pair_mode, uint32_t xcd_ranges, uint32_t *err)
+    int32_t *__restrict__ ckv_index, uint32_t n_layers, uint32_t lpw, uint32_t pair_mode, uint32_t xcd_ranges,
+    uint32_t *err)
 {
     // Lane l of a wave holds 16-byte vector v = l % 8 of row l / 8 (and of row 8 + l / 8):
     // a wave-wide access covers eight whole 128-byte rows, contiguous when the rows are.
     // Vectors 0..3 are the first halves of the pairs, 4..7 their partners, four lanes on.
     const uint32_t n_tiles = plan[0];
-    const uint32_t layer = blockIdx.y;
+    const uint32_t l0 = blockIdx.y * lpw, l1 = l0 + lpw < n_layers ? l0 + lpw : n_layers;
     const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
     const uint32_t v = lane & 7, jq = v & 3;
     const float sgn = v < 4 ? -1.0f : 1.0f;            // first half: a c - b s; partner: b c + a s
@@ -485,34 +472,55 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
         const uint32_t hit = __builtin_amdgcn_readfirstlane(tp->hit);
         const f32x4 *tq = (const f32x4 *)(trig + (uint64_t)hit * IRM_KR_PAIRS + 8 * jq);
         const f32x4 t0 = tq[0], t1 = tq[1], t2 = tq[2], t3 = tq[3];
-        u32x4 mine[Q];
         int32_t slot[Q];
+        bool on[Q];
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             const uint32_t r = (wave * Q + q) * 8 + (lane >> 3);
             slot[q] = -1;
-            mine[q] = u32x4{0, 0, 0, 0};
-            if (r < n_rows) {
+            on[q] = r < n_rows;
+            if (on[q]) {
                 const int32_t sl = dst_slots[(uint64_t)dst_tok0 + r];
                 if (sl < 0 || (uint64_t)(uint32_t)sl >= kr_rows) {
-                    if (v == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
+                    if (v == 0 && l0 == 0) atomicOr(err, IRM_FLAG_ROW_RANGE);
                 } else {
                     slot[q] = sl;
+                    if (l0 == 0 && v == 0) ckv_index[sl] = (int32_t)(src_row0 + r);
                 }
-                mine[q] = __builtin_nontemporal_load(
-                    (const u32x4 *)((const char *)src_ptrs[layer] + (uint64_t)(src_row0 + r) * src_stride) + v);
             }
         }
+        // D layers' rows are on their way at any time
+        u32x4 buf[D][Q];
+        auto fetch = [&](u32x4 (&into)[Q], uint32_t layer) {
+            const char *base = (const char *)src_ptrs[layer];
 #pragma unroll
-        for (int q = 0; q < Q; ++q) {
-            const uint32_t r = (wave * Q + q) * 8 + (lane >> 3);
-            const u32x4 other = partner_vector(mine[q]);          // every lane takes part
-            if (slot[q] < 0) continue;
-            const u32x4 out = pair_mode ? rotate_vector_pairs(mine[q], t0, t1, t2, t3, v >= 4)
-                                        : rotate_vector(mine[q], other, t0, t1, t2, t3, sgn);
-            __builtin_nontemporal_store(
-                out, (u32x4 *)((char *)kr_ptrs[layer] + (uint64_t)(uint32_t)slot[q] * kr_stride) + v);
-            if (layer == 0 && v == 0) ckv_index[slot[q]] = (int32_t)(src_row0 + r);
+            for (int q = 0; q < Q; ++q) {
+                const uint32_t r = (wave * Q + q) * 8 + (lane >> 3);
+                into[q] = u32x4{0, 0, 0, 0};
+                if (on[q])
+                    into[q] = __builtin_nontemporal_load((const u32x4 *)(base + (uint64_t)(src_row0 + r) * src_stride) + v);
+            }
+        };
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+            if (l0 + d < l1) fetch(buf[d], l0 + d);
+#pragma nounroll
+        for (uint32_t layer = l0; layer < l1; layer += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (layer + d >= l1) break;
+                char *out_base = (char *)kr_ptrs[layer + d];
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const u32x4 other = partner_vector(buf[d][q]);    // every lane takes part
+                    if (slot[q] >= 0) {
+                        const u32x4 out = pair_mode ? rotate_vector_pairs(buf[d][q], t0, t1, t2, t3, v >= 4)
+                                                    : rotate_vector(buf[d][q], other, t0, t1, t2, t3, sgn);
+                        __builtin_nontemporal_store(out, (u32x4 *)(out_base + (uint64_t)(uint32_t)slot[q] * kr_stride) + v);
+                    }
+                }
+                if (layer + d + D < l1) fetch(buf[d], layer + d + D);
+            }
         }
     }
 }
@@ -539,19 +547,32 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     hipLaunchKernelGGL(reattach_plan, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,
                        hit_capacity, ctx->d_inv_freq, src_rows, n_slot_tokens, ctx->d_trig, ctx->d_tiles,
                        ctx->tile_cap, kr_tile_rows, ctx->cfg.pair_mode, ctx->d_plan, ctx->d_err);
-    uint64_t tile_slots = n_slot_tokens / kr_tile_rows + hit_capacity;
+    // as for the row kernel: slots for the tiles n_slot_tokens rows can fill, the overflow in a second pass
+    uint64_t tile_slots = (n_slot_tokens + kr_tile_rows - 1) / kr_tile_rows;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
+    // layers per workgroup: all of them for a large batch, fewer while that leaves too few workgroups to fill
+    // the chip (about 16 per compute unit)
+    const uint32_t L = ctx->cfg.n_layers;
+    uint32_t lpw = ctx->kr_layers_per_wg;
+    if (!lpw) {
+        const uint64_t want = 16ull * ctx->n_cu;
+        lpw = tile_slots >= want ? L : (uint32_t)((tile_slots * L + want - 1) / want);
+    }
+    if (lpw < 1) lpw = 1;
+    if (lpw > L) lpw = L;
     const bool sample = ctx->prof_events && ctx->prof_n < ctx->prof_cap &&
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
     void (*kr_kernel)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t, const int32_t *,
-                      const irm_tile *, const uint32_t *, const float2 *, int32_t *, uint32_t, uint32_t,
-                      uint32_t *) =
-        ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2>
-        : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4> : reattach_kr_rows<8>;
-    hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)((tile_slots + 7) / 8 * 8), ctx->cfg.n_layers), dim3(256), 0, s,
+                      const irm_tile *, const uint32_t *, const float2 *, int32_t *, uint32_t, uint32_t, uint32_t,
+                      uint32_t, uint32_t *) =
+        ctx->kr_depth == 4 ? (ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2, 4>
+                              : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4, 4> : reattach_kr_rows<8, 4>)
+                           : (ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2, 2>
+                              : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4, 2> : reattach_kr_rows<8, 2>);
+    hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)((tile_slots + 7) / 8 * 8), (L + lpw - 1) / lpw), dim3(256), 0, s,
                        d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
-                       kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index,
+                       kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index, L, lpw,
                        ctx->cfg.pair_mode, ctx->xcd_ranges, ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
@@ -644,15 +665,20 @@ static irm_status reattach_check(uint32_t row_format, const void *const *d_src_l
     return IRM_OK;
 }
 
-// one workgroup per tile slot and layer: the hardware dispatcher balances the load
-// (measured faster than a persistent grid of resident size); the slot count can only
-// be bounded on the host, surplus workgroups exit on their first compare
+// One workgroup per tile slot and layer: the hardware dispatcher balances the load (measured
+// faster than a grid of resident size, whether it strides over the tiles or draws them from a
+// device counter).  The tile count is only known on the device.  Workgroups without a tile
+// leave on their first compare, but dispatching them is not free (about 0.7 ns each, in a run
+// at the end of every layer during which nothing new starts: 10 us of a 276 us launch on the
+// 32 K-token configuration with one slot per possible tile), so the grid covers the tiles
+// that n_slot_tokens rows can fill; the ragged last tiles of the hits, if they overflow it,
+// are taken by the first workgroups of the layer in a second pass.
 static void rows_enqueue(const rows_launch &k, const void *const *d_src_layer_ptrs, uint64_t src_row_stride_bytes,
                          void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes, uint64_t dst_rows,
-                         const int32_t *d_dst_slots, uint64_t n_slot_tokens, uint32_t hit_capacity, hipStream_t s)
+                         const int32_t *d_dst_slots, uint64_t n_slot_tokens, hipStream_t s)
 {
     const uint32_t tile_rows = k.waves * k.rows_per_wave;
-    uint64_t tile_slots = n_slot_tokens / tile_rows + hit_capacity;
+    uint64_t tile_slots = (n_slot_tokens + tile_rows - 1) / tile_rows;
     if (k.grid) tile_slots = k.grid;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
     const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8);
@@ -686,7 +712,7 @@ extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_
                         (ctx->prof_calls++ % ctx->prof_every) == 0;
     if (sample) IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n], s));
     rows_enqueue(k, d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
-                 d_dst_slots, n_slot_tokens, hit_capacity, s);
+                 d_dst_slots, n_slot_tokens, s);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;
@@ -768,6 +794,6 @@ extern "C" irm_status irm_reattach_static(const float *inv_freq, uint32_t n_laye
                        hit_capacity, freq, src_rows, n_slot_tokens, k.d_trig, k.d_tiles, k.tile_cap,
                        IRM_STATIC_TILE_ROWS, pair_mode, k.d_plan, k.d_err);
     rows_enqueue(k, d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
-                 d_dst_slots, n_slot_tokens, hit_capacity, s);
+                 d_dst_slots, n_slot_tokens, s);
     return irm_launch_status();
 }

@@ -36,8 +36,10 @@ def _need_gpu():
 SCALE = 1.0 / np.sqrt(192.0)
 
 
-def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None, fp8=False):
-    """references by the library, attention by the library; expectation by the oracle alone"""
+def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None, fp8=False, give_up_first=False):
+    """references by the library, attention by the library; expectation by the oracle alone.
+    give_up_first: before the call that is checked, the same call with a wait limit of zero polls,
+    so that every in-kernel wait that is not met at once gives up."""
     rng = np.random.default_rng(seed)
     s = Session.for_workload(w, DEV, pair_mode=pair_mode, row_format=B.IRM_ROW_FP8 if fp8 else B.IRM_ROW_BF16)
     try:
@@ -65,6 +67,15 @@ def run_case(w, hits, n_heads, n_splits, pair_mode, seed, kv_offsets=None, fp8=F
         out = torch.full((n_req, n_heads, 512), 7.0, dtype=torch.float32, device=DEV)
         lse = torch.full((n_req, n_heads), 7.0, dtype=torch.float32, device=DEV)
         ws = torch.empty(B.irm_attend_ref_workspace_bytes(n_req, n_heads, n_splits), dtype=torch.uint8, device=DEV)
+        if give_up_first:
+            B.irm_ctx_tune(s.ctx, 8, 0)
+            B.irm_attend_ref(s.ctx, q, pool, pool.shape[1] * 2, d_slots, s.to_dev_u32(off), row, hit, trig, SCALE,
+                             n_splits, ws, out, lse)
+            torch.cuda.synchronize()                                  # the call returns: every wave reached the end
+            assert s.error_flags() & B.IRM_FLAG_WAIT_TIMEOUT        # and says that its results are not to be used
+            B.irm_ctx_tune(s.ctx, 8, 1 << 18)
+            out.fill_(7.0)
+            lse.fill_(7.0)
         B.irm_attend_ref(s.ctx, q, pool, pool.shape[1] * 2, d_slots, s.to_dev_u32(off), row, hit, trig, SCALE,
                          n_splits, ws, out, lse)
         torch.cuda.synchronize()
@@ -112,6 +123,18 @@ def test_attend_ref_small_configs(name, n_heads, n_splits, pair_mode):
     check(got, got_lse, want, want_lse, long_contexts=True)
     again, again_lse, _, _ = run_case(w, hits, n_heads, n_splits, pair_mode, seed=11)
     assert np.array_equal(got, again) and np.array_equal(got_lse, again_lse)
+
+
+@pytest.mark.parametrize("fp8,n_heads", [(False, 16), (True, 16), (False, 64)])
+def test_attend_ref_waits_that_give_up_end_the_kernel_and_raise_the_flag(fp8, n_heads):
+    """The in-kernel waits are bounded.  With a limit of zero polls the waves do not wait for each
+    other at all: the call must still return (every wave reaches the closing barriers; every address
+    it forms comes from a checked reference) and raise IRM_FLAG_WAIT_TIMEOUT; the next call, with the
+    default limit, is clean and matches the oracle."""
+    w = wl.make_workload("c2", orc.cdc_chunk, size="small")
+    o = oracle_front(w)
+    got, got_lse, want, want_lse = run_case(w, o["hits"], n_heads, 1, 0, 11, fp8=fp8, give_up_first=True)
+    check(got, got_lse, want, want_lse, long_contexts=True, fp8=("64 heads" if n_heads == 64 else True) if fp8 else False)
 
 
 def test_attend_ref_ragged_contexts_empty_and_short_requests():
