@@ -62,9 +62,6 @@ def main() -> int:
     ap.add_argument("--row-stride", type=int, default=0, metavar="BYTES",
                     help="hit stage, --reattach full: row stride of both pools in bytes, a multiple of 16 "
                          "(0 = packed rows; 768 puts every fp8 row on its own 128-byte lines)")
-    ap.add_argument("--layer-pad", type=int, default=0, metavar="ROWS",
-                    help="--reattach kr / kr-dense: rows of padding behind every layer of the k_r pools, so that the "
-                         "layer stride is not a power of two")
     ap.add_argument("--heads", type=int, default=16, help="attend stage: query rows per request, a multiple of 16 "
                                                               "(heads, or new tokens x heads over a cached prefix)")
     ap.add_argument("--linear-rows", action="store_true",
@@ -257,13 +254,12 @@ def run(args) -> dict:
         hit_index = torch.full((w0.dst_rows,), -1, dtype=torch.int32, device=dev)
         bytes_per_token_layer = 12.0 / L                            # 4 B slot read, 8 B written, per token
     else:
-        dst = torch.zeros((L, w0.dst_rows + args.layer_pad, 64), dtype=torch.bfloat16, device=dev)[:, :w0.dst_rows]
+        dst = torch.zeros((L, w0.dst_rows, 64), dtype=torch.bfloat16, device=dev)
         dst_ptrs = B.kr_layer_pointers(dst)
         if args.reattach == "kr":
             kr_src_ptrs, kr_src_stride = B.kr_slice_pointers(src), ROW_BYTES
         else:
-            kr_base = torch.empty((L, w0.src_rows + args.layer_pad, 64), dtype=torch.bfloat16,
-                                  device=dev)[:, :w0.src_rows]
+            kr_base = torch.empty((L, w0.src_rows, 64), dtype=torch.bfloat16, device=dev)
             for l in range(L):
                 kr_base[l].copy_(src[l, :, 512:])
             kr_src_ptrs, kr_src_stride = B.kr_layer_pointers(kr_base), 128

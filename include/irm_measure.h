@@ -28,8 +28,7 @@ extern "C" {
  * knob 7: layers a workgroup of the k_r-only kernel keeps its tile for (0 = chosen by batch size)
  * knob 8: polls one in-kernel wait of irm_attend_ref may take before the wave gives up and raises
  *         IRM_FLAG_WAIT_TIMEOUT (default 2^18; 0 makes every wait that is not met at once give up:
- *         for tests of that path, the results of such a call are not to be used)
- * knob 9: layers of rows a wave of the k_r-only kernel has on their way (2 or 4) */
+ *         for tests of that path, the results of such a call are not to be used) */
 irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value);
 
 /* Kernel timing for measurements.  irm_ctx_profile_begin creates max_samples

@@ -43,7 +43,6 @@ extern "C" irm_status irm_ctx_create(const irm_config *cfg, irm_ctx **out)
     c->xcd_ranges = 1;
     c->kr_rows_per_lane = 2;
     c->att_spin_limit = 1u << 18;
-    c->kr_depth = 2;
 
     hipDeviceProp_t prop;
     if (hipGetDevice(&c->device) != hipSuccess || hipGetDeviceProperties(&prop, c->device) != hipSuccess) {
@@ -151,11 +150,6 @@ extern "C" irm_status irm_ctx_tune(irm_ctx *ctx, uint32_t knob, uint32_t value)
     if (knob == 5) {
         if (value > 1) return IRM_ERR_INVALID_ARG;
         ctx->cdc_serial = value;
-        return IRM_OK;
-    }
-    if (knob == 9) {
-        if (value != 2 && value != 4) return IRM_ERR_INVALID_ARG;
-        ctx->kr_depth = value;
         return IRM_OK;
     }
     if (knob == 8) {

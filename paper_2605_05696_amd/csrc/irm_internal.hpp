@@ -40,7 +40,6 @@ struct irm_ctx {
     uint32_t cdc_serial;    // knob 5: 1 = always use the serial cut selection
     uint32_t kr_rows_per_lane; // knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; tile = 32x that)
     uint32_t kr_layers_per_wg; // knob 7: layers a workgroup of the k_r-only kernel keeps its tile for (0 = by batch size)
-    uint32_t kr_depth;      // knob 9: layers of rows a wave of the k_r-only kernel has on their way (2 or 4)
     uint32_t att_spin_limit; // knob 8: polls a wave of the attention kernel spends in one wait before it gives up
     uint32_t xcd_ranges;    // knob 3: 1 = each XCD serves a contiguous range of a layer's tiles
     uint32_t n_cu;

@@ -443,8 +443,8 @@ static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode, ui
 // few KB, too little for a workgroup of its own (the dispatcher, not the memory, then sets
 // the pace: 0.63 of peak).  A workgroup therefore keeps its tile for `lpw` layers: the tile
 // record, the slots and the (cos, sin) values are fetched once, the rows of the next layer
-// are requested before the current ones are rotated and stored (D layers on their way).
-template <int Q, int D>
+// are requested before the current ones are rotated and stored.
+template <int Q>
 __global__ __launch_bounds__(256) void reattach_kr_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
     uint64_t kr_stride, uint64_t kr_rows, const int32_t *__restrict__ dst_slots,
@@ -489,7 +489,8 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
                 }
             }
         }
-        // D layers' rows are on their way at any time
+        // two layers' rows are on their way at any time (four were no faster)
+        constexpr int D = 2;
         u32x4 buf[D][Q];
         auto fetch = [&](u32x4 (&into)[Q], uint32_t layer) {
             const char *base = (const char *)src_ptrs[layer];
@@ -566,10 +567,8 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     void (*kr_kernel)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t, const int32_t *,
                       const irm_tile *, const uint32_t *, const float2 *, int32_t *, uint32_t, uint32_t, uint32_t,
                       uint32_t, uint32_t *) =
-        ctx->kr_depth == 4 ? (ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2, 4>
-                              : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4, 4> : reattach_kr_rows<8, 4>)
-                           : (ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2, 2>
-                              : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4, 2> : reattach_kr_rows<8, 2>);
+        ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2>
+        : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4> : reattach_kr_rows<8>;
     hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)((tile_slots + 7) / 8 * 8), (L + lpw - 1) / lpw), dim3(256), 0, s,
                        d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
                        kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index, L, lpw,

@@ -367,23 +367,22 @@ def test_reattach_kr_small_configs(name, slots, dense):
     assert np.all(got_kr[:, untouched] == wl.SENTINEL_BF16)
 
 
-@pytest.mark.parametrize("rows_per_lane,layers_per_wg,depth", [(2, 1, 2), (2, 2, 4), (4, 3, 2), (8, 1, 4), (2, 0, 4),
-                                                               (4, 5, 4)])
+@pytest.mark.parametrize("rows_per_lane,layers_per_wg", [(2, 1), (2, 2), (4, 3), (8, 1), (2, 0), (4, 5)])
 @pytest.mark.parametrize("name,slots,pair_mode", [("c4", "permuted", 0), ("c1", "contiguous", 1)])
-def test_reattach_kr_launch_shapes(name, slots, pair_mode, rows_per_lane, layers_per_wg, depth):
-    """Rows per lane, layers a workgroup keeps its tile for (c1 and c4 have three layers: one, two
-    with a remainder, all, more than there are) and the number of layers on their way: same rows."""
+def test_reattach_kr_launch_shapes(name, slots, pair_mode, rows_per_lane, layers_per_wg):
+    """Rows per lane and layers a workgroup keeps its tile for (c1 and c4 have three layers: one, two
+    with a remainder, all, more than there are): same rows."""
     w = small(name, slots=slots)
     hits = oracle_front(w)["hits"]
     src = wl.kv_pool_torch(w.n_layers, w.src_rows, wl.kv_seed(name), DEV)
     got_kr, got_idx = run_kr_variant(w, hits, src, pair_mode=pair_mode,
-                                     knobs=((6, rows_per_lane), (7, layers_per_wg), (9, depth)))
+                                     knobs=((6, rows_per_lane), (7, layers_per_wg)))
     want_kr = np.full((w.n_layers, w.dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
     want_idx = np.full(w.dst_rows, -1, np.int32)
     orc.reattach_kr(bits(src), want_kr, want_idx, w.dst_slots, hits, w.inv_freq, pair_mode)
     assert np.array_equal(got_idx, want_idx)
     pad = lambda k: np.concatenate([np.zeros(k.shape[:2] + (512,), np.uint16), k], axis=2)
-    compare_rows(pad(got_kr), pad(want_kr), what=f"{w.name} k_r only, shape {rows_per_lane}/{layers_per_wg}/{depth}")
+    compare_rows(pad(got_kr), pad(want_kr), what=f"{w.name} k_r only, shape {rows_per_lane}/{layers_per_wg}")
     assert np.all(got_kr[:, want_idx < 0] == wl.SENTINEL_BF16)
 
 
