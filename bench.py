@@ -30,7 +30,7 @@ ROW_BYTES = 1152                                     # bf16 rows; main() takes t
 HBM_PEAK_GBS = 8000.0
 
 
-def main() -> int:
+def build_parser() -> argparse.ArgumentParser:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default: per workload, see DEFAULTS)")
@@ -100,7 +100,11 @@ def main() -> int:
                     help="'all' or '': after the headline and the secondary workloads, also run the path's other "
                          "variants (split pool, fp8 rows, miss path, S1 fallback, rotate-on-load attention) and "
                          "report them in the 'other_paths' block (default with the c4 headline: all)")
-    args = ap.parse_args()
+    return ap
+
+
+def main() -> int:
+    args = build_parser().parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path is built and measured on ONE GPU; --gpus above 1 is not supported "
