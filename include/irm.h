@@ -239,8 +239,9 @@ irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
  * supply comes as arguments (inv_freq: HOST array of the 32 fp32 inverse frequencies;
  * n_layers, pair_mode, row_format as in irm_config), and the call's scratch (tile list,
  * per-hit rotation table) lives in a fixed array inside the library's device image, about
- * 1.5 MB on every GPU the library runs on, held until the process ends.  The call
- * allocates nothing, frees nothing and does not synchronise.
+ * 1.25 MB on every GPU the library runs on, held until the process ends.  The call
+ * allocates nothing, frees nothing and does not synchronise.  The first call on a device
+ * looks the array's address up (once per device); make that call outside a graph capture.
  *   n_slot_tokens  <= IRM_REATTACH_STATIC_MAX_TOKENS, hit_capacity <= IRM_REATTACH_STATIC_MAX_HITS
  *                  (else IRM_ERR_CAPACITY, nothing is launched)
  *   d_error_flags  optional device word the kernels OR the IRM_FLAG_* bits into (the

@@ -278,10 +278,12 @@ __device__ __forceinline__ bool select_jump(const uint64_t *__restrict__ bitmap,
     __syncthreads();
     // 3. orbit of node 0 by pointer doubling
     constexpr int NODE_ITERS = (CDC_NODE_CAP + 2 + 255) / 256;   // nodes per thread at 256 threads
+    const uint32_t node_iters = (n_nodes + 255u) >> 8;           // ... of which this request needs so many (uniform)
     for (uint32_t span = 1; span < n_nodes; span <<= 1) {
         uint32_t j1[NODE_ITERS], j2[NODE_ITERS];
 #pragma unroll
         for (int k = 0; k < NODE_ITERS; ++k) {
+            if ((uint32_t)k >= node_iters) break;                // a typical request has a few hundred nodes: one pass
             const uint32_t i = tid + (uint32_t)k * 256u;
             if (i < n_nodes) {
                 j1[k] = g->jump[i];
@@ -291,6 +293,7 @@ __device__ __forceinline__ bool select_jump(const uint64_t *__restrict__ bitmap,
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < NODE_ITERS; ++k) {
+            if ((uint32_t)k >= node_iters) break;
             const uint32_t i = tid + (uint32_t)k * 256u;
             if (i < n_nodes) {
                 if (g->mark[i]) g->mark[j1[k]] = 1;
