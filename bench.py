@@ -154,6 +154,8 @@ EXTRAS = [
     dict(what="no-materialise variant: references and rotation table only", workload="c2", reattach="ref", steps=40, warmup=5),
     dict(what="fp8 pool rows (656 B)", workload="c2", rows="fp8"),
     dict(what="fp8 pool rows (656 B), 32 K-token request", workload="c1", rows="fp8"),
+    dict(what="two batches in flight on two streams (the front end of one hides behind the other's row kernel; "
+              "the kernel columns then span both streams and say nothing)", workload="c1", streams=2),
     dict(what="miss path, irm_admit alone", workload="c2", stage="admit", steps=8, warmup=2),
     dict(what="hit path + S1 window fallback on unaligned batches", workload="c1", stage="s1"),
     dict(what="rotate-on-load decode attention over the references, 16 heads", workload="c2", stage="attend",
