@@ -124,7 +124,11 @@ def main() -> int:
         out["secondary"] = []
         for item in filter(None, args.secondary.split(",")):
             name, _, cdc = item.partition(":")
-            sub = run(with_defaults(args, name, cdc or "config", None, None, None, cpu=False))
+            try:
+                sub = run(with_defaults(args, name, cdc or "config", None, None, None, cpu=False))
+            except Exception as exc:                             # the headline is printed whatever happens here
+                out["secondary"].append({"workload": item, "error": f"{type(exc).__name__}: {exc}"})
+                continue
             out["secondary"].append({"workload": sub["config"]["workload"], "steps": sub["steps"],
                                      "ms_per_step": sub["ms_per_step"], "value": sub["value"], "unit": sub["unit"],
                                      "hit_tokens_per_step": sub["config"]["hit_tokens_per_step"],
@@ -139,7 +143,11 @@ def main() -> int:
                               flags.get("variants"), cpu=False)
             for k, v in flags.items():
                 setattr(a, k, v)
-            sub = run(a)
+            try:
+                sub = run(a)
+            except Exception as exc:
+                out["other_paths"].append({"what": flags["what"], "error": f"{type(exc).__name__}: {exc}"})
+                continue
             out["other_paths"].append({"what": flags["what"], "metric": sub["metric"], "workload": sub["config"]["workload"],
                                        "steps": sub["steps"], "ms_per_step": sub["ms_per_step"], "value": sub["value"],
                                        "unit": sub["unit"], "roofline": sub["roofline"]})

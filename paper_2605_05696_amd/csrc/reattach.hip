@@ -5,8 +5,8 @@
 //   reattach_plan  per hit: the 32 (cos, sin) of delta * inv_freq[i], angle as an
 //                  fp64 product with fp64 range reduction (|delta| reaches 1e5, an
 //                  fp32 angle would already cost half a bf16 ulp); the hits are cut
-//                  into tiles of up to 16 rows, the tile list is written by all
-//                  workgroups at once.
+//                  into tiles (16 rows of 1152 bytes, 32 rows of 656 bytes), the tile
+//                  list is written by all workgroups at once.
 //   reattach_rows  grid (tile slots, layers), one workgroup per tile and layer: a
 //                  tile's source rows are one contiguous span; each of the 8 waves
 //                  moves 2 rows of c_KV with one 16-byte load and store per lane and
@@ -18,7 +18,11 @@
 //                  non-temporal: every byte is touched once.
 //   reattach_kr_rows  the split-pool variant (App. C): only the k_r slice is
 //                  materialised, c_KV is handed on as a row index; eight lanes per
-//                  row, whole 128-byte lines per access, partners four lanes apart.
+//                  row, whole 128-byte lines per access, partners four lanes apart; a
+//                  workgroup keeps its tile for several layers.
+//   reattach_ref_rows  the no-materialise variant: row references only.
+// irm_reattach_static runs the same kernels for a caller without a context, with the
+// plan in a static device array.
 #include "irm_internal.hpp"
 
 // ---- plan --------------------------------------------------------------------
