@@ -445,9 +445,10 @@ static rows_kernel_t pick_kernel(uint32_t waves, uint32_t rpw, uint32_t mode, ui
 // worth of data, so a tile is 32 * Q rows.
 // Grid (tile slots, layer groups): a row's k_r is only 128 bytes, so one tile and layer is a
 // few KB, too little for a workgroup of its own (the dispatcher, not the memory, then sets
-// the pace: 0.63 of peak).  A workgroup therefore keeps its tile for `lpw` layers: the tile
+// the pace: 0.57 of peak).  A workgroup therefore keeps its tile for `lpw` layers: the tile
 // record, the slots and the (cos, sin) values are fetched once, the rows of the next layer
-// are requested before the current ones are rotated and stored.
+// are requested before the current ones are rotated and stored.  The walk is kept short
+// (three layers unless the caller sets it): every layer is another page.
 template <int Q>
 __global__ __launch_bounds__(256) void reattach_kr_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ kr_ptrs,
@@ -555,13 +556,17 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
     // as for the row kernel: slots for the tiles n_slot_tokens rows can fill, the overflow in a second pass
     uint64_t tile_slots = (n_slot_tokens + kr_tile_rows - 1) / kr_tile_rows;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
-    // layers per workgroup: all of them for a large batch, fewer while that leaves too few workgroups to fill
-    // the chip (about 16 per compute unit)
+    // layers per workgroup: three, fewer while that leaves too few workgroups to fill the chip (about 16
+    // per compute unit).  Every layer is a new page for the wave's source and destination, and a wave
+    // that walks all layers misses the first-level translation cache once per layer and stream (the
+    // second level is then busy 87 % of the time against 5 % for short walks) and runs at anything from
+    // 0.62 to 0.76 of peak from one process to the next; walks of three layers give a steady 0.71-0.75,
+    // one layer per workgroup 0.56-0.58 (too little work per workgroup).
     const uint32_t L = ctx->cfg.n_layers;
     uint32_t lpw = ctx->kr_layers_per_wg;
     if (!lpw) {
         const uint64_t want = 16ull * ctx->n_cu;
-        lpw = tile_slots >= want ? L : (uint32_t)((tile_slots * L + want - 1) / want);
+        lpw = tile_slots * L >= 3 * want ? 3u : (uint32_t)((tile_slots * L + want - 1) / want);
     }
     if (lpw < 1) lpw = 1;
     if (lpw > L) lpw = L;
