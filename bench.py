@@ -545,22 +545,27 @@ def bench_yardstick(args):
     reps = max(1, args.steps or 5)
     with torch.cuda.stream(stream):
         for mode, mname in ((B.YARDSTICK_READ, "read"), (B.YARDSTICK_WRITE, "write"), (B.YARDSTICK_COPY, "copy")):
-            for grid in (2048, 4096, 8192, 16384, 65536):
-                for lanes, vec in ((256, 2), (256, 4), (256, 9), (256, 18), (256, 36), (512, 4), (512, 9), (1024, 2),
-                                   (1024, 4)):
+            # the large grids give every workgroup one or two steps only: no loop, workgroups dispatched in
+            # address order like the row kernel's, instead of a few thousand private ranges walked side by side
+            for grid in (2048, 4096, 8192, 16384, 65536, 131072, 147456, 262144, 294912, 589824):
+                for lanes, vec in ((256, 2), (256, 4), (256, 9), (256, 18), (256, 36), (512, 2), (512, 4), (512, 9),
+                                   (1024, 2), (1024, 4)):
                     if n % (grid * lanes * vec * 16):
                         continue                                 # ranges must be whole steps
-                    B.irm_yardstick(dst, src, mode, grid, lanes, vec, stream)          # warm-up
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record(stream)
-                    for _ in range(reps):
-                        B.irm_yardstick(dst, src, mode, grid, lanes, vec, stream)
-                    b.record(stream)
-                    b.synchronize()
-                    ms = a.elapsed_time(b) / reps
-                    moved = n * (2 if mode == B.YARDSTICK_COPY else 1)
-                    rows.append({"mode": mname, "grid": grid, "lanes": lanes, "vectors_per_lane": vec,
-                                 "ms": ms, "gbs": moved / (ms * 1e-3) / 1e9})
+                    # the address-ordered shapes also with the row kernels' mapping: one contiguous eighth per XCD
+                    for xcd in ((0, B.YARDSTICK_XCD_RANGES) if grid >= 131072 else (0,)):
+                        B.irm_yardstick(dst, src, mode | xcd, grid, lanes, vec, stream)      # warm-up
+                        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        a.record(stream)
+                        for _ in range(reps):
+                            B.irm_yardstick(dst, src, mode | xcd, grid, lanes, vec, stream)
+                        b.record(stream)
+                        b.synchronize()
+                        ms = a.elapsed_time(b) / reps
+                        moved = n * (2 if mode == B.YARDSTICK_COPY else 1)
+                        rows.append({"mode": mname, "grid": grid, "lanes": lanes, "vectors_per_lane": vec,
+                                     "xcd_ranges": bool(xcd), "steps_per_workgroup": n // (grid * lanes * vec * 16),
+                                     "ms": ms, "gbs": moved / (ms * 1e-3) / 1e9})
     best = {m: max((r for r in rows if r["mode"] == m), key=lambda r: r["gbs"]) for m in ("read", "write", "copy")}
     median = {m: float(np.median([r["gbs"] for r in rows if r["mode"] == m])) for m in ("read", "write", "copy")}
     # a copy whose reads and writes take turns on the memory bus at their own best rates

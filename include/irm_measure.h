@@ -53,11 +53,17 @@ irm_status irm_calibrate_copy(void *d_dst, const void *d_src, uint64_t bytes, ui
  * of a step are issued before its stores.  IRM_YARDSTICK_COPY reads d_src and writes d_dst
  * (traffic 2 x bytes), IRM_YARDSTICK_READ only reads d_src (the data must not be the one
  * pattern that would make it store; any random fill is fine), IRM_YARDSTICK_WRITE only
- * writes d_dst.  bytes must be a multiple of grid x lanes x vectors_per_lane x 16.  What these
- * reach bounds what a kernel that moves rows can reach. */
+ * writes d_dst.  bytes must be a multiple of grid x lanes x vectors_per_lane x 16.  With
+ * IRM_YARDSTICK_XCD_RANGES or-ed into the mode (grid a multiple of 8) workgroup x takes range
+ * (x % 8) * grid / 8 + x / 8, so that every XCD streams one contiguous eighth, the mapping of
+ * the row kernels; without it workgroup x takes range x.  With one step per workgroup (grid =
+ * bytes / (lanes x vectors_per_lane x 16)) the stream is dispatched in address order with no
+ * loop, the launch shape of the row kernels.  What these reach bounds what a kernel that moves
+ * rows can reach. */
 #define IRM_YARDSTICK_COPY 0u
 #define IRM_YARDSTICK_READ 1u
 #define IRM_YARDSTICK_WRITE 2u
+#define IRM_YARDSTICK_XCD_RANGES 4u
 irm_status irm_yardstick(void *d_dst, const void *d_src, uint64_t bytes, uint32_t mode, uint32_t grid,
                          uint32_t lanes, uint32_t vectors_per_lane, void *stream);
 

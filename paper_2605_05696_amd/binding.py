@@ -172,6 +172,7 @@ def irm_calibrate_copy(d_dst, d_src, grid: int = 0, stream=None) -> None:
 
 
 YARDSTICK_COPY, YARDSTICK_READ, YARDSTICK_WRITE = 0, 1, 2
+YARDSTICK_XCD_RANGES = 4                             # or-ed into the mode: one contiguous eighth per XCD
 
 
 def irm_yardstick(d_dst, d_src, mode: int, grid: int, lanes: int, vectors_per_lane: int, stream=None) -> None:
