@@ -48,6 +48,9 @@ def build_parser() -> argparse.ArgumentParser:
                          "the 'secondary' block of the JSON line, each as name or name:paper (default with the c4 "
                          "headline: c1,c2,c3,c1:paper; '' = none)")
     ap.add_argument("--slots", default="contiguous", choices=["contiguous", "permuted"])
+    ap.add_argument("--layers", type=int, default=0,
+                    help="layer count of the pools instead of the configuration's own (0 = its own): the same "
+                         "batches over fewer or more layers, to separate a launch's fixed cost from its per-layer cost")
     ap.add_argument("--grid", type=int, default=0, help="workgroups of the row kernel (0 = library default)")
     ap.add_argument("--reattach", default="full", choices=["full", "kr", "kr-dense", "ref"],
                     help="full = c_KV copied + k_r rotated (the headline); kr = split-pool variant, "
@@ -222,6 +225,9 @@ def run(args) -> dict:
     works = [wl.make_workload(name, gpu_chunker, size=args.size, variant=v, slots=args.slots,
                               assembly="unaligned" if s1 else "aligned", s1_window=128 if s1 else 0, cdc=args.cdc)
              for v in range(n_var)]
+    if args.layers:
+        for w in works:
+            w.n_layers = args.layers
     w0 = works[0]
     _, _, _, pool_hash = front.chunk_host(w0.pool_tokens, np.array([0, len(w0.pool_tokens)], np.uint32))
     pool_windows = None
@@ -393,7 +399,7 @@ def run(args) -> dict:
     tfile = os.path.join(ROOT, "profiles", f"reattach_rows_{'fp8_' if fp8 else ''}{name}"
                                            f"{'_paper' if args.cdc == 'paper' else ''}_traffic.json")
     if (args.size == "full" and args.reattach == "full" and args.stage == "hit" and args.slots == "contiguous"
-            and not args.row_stride and os.path.exists(tfile)):
+            and not args.row_stride and not args.layers and os.path.exists(tfile)):
         stored = json.load(open(tfile))
         traffic = stored.get("hbm_bytes_per_launch")
         traffic_source = f"stored: profiles/{os.path.basename(tfile)} ({stored.get('kernel', 'reattach_rows')})"
