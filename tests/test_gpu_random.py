@@ -1,6 +1,8 @@
 """Randomised end-to-end parity: random CDC parameters, gear tables, vocabularies, request
 mixes (empty and tiny requests included), registries with repeated content, both pair
 layouts; every stage and the miss path against the oracle on each case."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -54,7 +56,8 @@ def random_case(seed):
                 pos_base=pos_base, carve=carve, inv=inv, pair_mode=int(rng.integers(0, 2)), L=int(rng.integers(1, 3)))
 
 
-@pytest.mark.parametrize("seed", range(40))
+# IRM_TEST_SEEDS=N widens the sweep for a longer soak (default 40 cases)
+@pytest.mark.parametrize("seed", range(int(os.environ.get("IRM_TEST_SEEDS", "40"))))
 def test_random_case_every_stage(seed):
     c = random_case(seed)
     rng, tokens, off = c["rng"], c["tokens"], c["off"]
