@@ -1,6 +1,7 @@
 """Randomised end-to-end parity: random CDC parameters, gear tables, vocabularies, request
 mixes (empty and tiny requests included), registries with repeated content, both pair
-layouts; every stage and the miss path against the oracle on each case."""
+layouts; every stage, every re-attachment variant (full rows with and without a context,
+k_r alone, references) and the miss path against the oracle on each case."""
 import os
 
 import numpy as np
@@ -109,6 +110,37 @@ def test_random_case_every_stage(seed):
             assert np.array_equal(getattr(got, f), getattr(hits, f)), f
         assert int(buf["hit_tokens"].item()) == hit_tokens
         compare_rows(bits(req), want_rows, what=f"seed {seed}")
+        # the same hit list through the other re-attachment variants
+        n_hits_max = buf["hits"].shape[0]
+        if len(hits) and n_tok <= B.REATTACH_STATIC_MAX_TOKENS and n_hits_max <= B.REATTACH_STATIC_MAX_HITS:
+            again = wl.kv_pool_torch(L, n_tok, 900 + seed, DEV)            # without a context: bit-equal to the above
+            flags = torch.zeros(1, dtype=torch.int32, device=DEV)
+            B.irm_reattach_static(c["inv"], L, c["pair_mode"], B.IRM_ROW_BF16, pool_ptrs, ROW * 2, pool_rows,
+                                  B.layer_pointers(again), ROW * 2, n_tok, d_slots, buf["hits"], buf["n_hits"], flags)
+            torch.cuda.synchronize()
+            assert int(flags.item()) == 0 and torch.equal(again.view(torch.int16), req.view(torch.int16))
+        kr = torch.empty((L, n_tok, 64), dtype=torch.bfloat16, device=DEV)  # split pool: k_r alone
+        kr.view(torch.int16).fill_(wl.SENTINEL_BF16 - 0x10000 if wl.SENTINEL_BF16 >= 0x8000 else wl.SENTINEL_BF16)
+        idx = torch.full((n_tok,), -1, dtype=torch.int32, device=DEV)
+        B.irm_reattach_kr(s.ctx, B.kr_slice_pointers(pool), ROW * 2, pool_rows, B.kr_layer_pointers(kr), 128, n_tok,
+                          idx, d_slots, buf["hits"], buf["n_hits"])
+        row = torch.full((n_tok,), -1, dtype=torch.int32, device=DEV)       # no-materialise: references
+        hit = torch.full((n_tok,), -1, dtype=torch.int32, device=DEV)
+        trig = torch.zeros((n_hits_max, 32, 2), dtype=torch.float32, device=DEV)
+        B.irm_reattach_ref(s.ctx, pool_rows, row, hit, trig, d_slots, buf["hits"], buf["n_hits"])
+        torch.cuda.synchronize()
+        assert s.error_flags() == 0
+        want_kr = np.full((L, n_tok, 64), wl.SENTINEL_BF16, np.uint16)
+        want_idx = np.full(n_tok, -1, np.int32)
+        want_row, want_hit = np.full(n_tok, -1, np.int32), np.full(n_tok, -1, np.int32)
+        if len(hits):
+            orc.reattach_kr(bits(pool), want_kr, want_idx, slots, hits, c["inv"], c["pair_mode"])
+            want_trig = orc.reattach_ref(pool_rows, want_row, want_hit, slots, hits, c["inv"])
+            assert np.abs(trig.cpu().numpy()[:len(hits)].astype(np.float64) - want_trig).max() <= 2.0 ** -23
+        assert np.array_equal(idx.cpu().numpy(), want_idx)
+        assert np.array_equal(row.cpu().numpy(), want_row) and np.array_equal(hit.cpu().numpy(), want_hit)
+        pad = lambda k: np.concatenate([np.zeros(k.shape[:2] + (512,), np.uint16), k], axis=2)
+        compare_rows(pad(bits(kr)), pad(want_kr), what=f"seed {seed} k_r only")
         # miss path
         d_cursor = torch.tensor([len(lib)], dtype=torch.int32, device=DEV)
         d_adm = torch.full((buf["cap"],), -7, dtype=torch.int32, device=DEV)
