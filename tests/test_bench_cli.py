@@ -31,3 +31,16 @@ def test_variant_runs_only_set_known_flags():
 def test_more_than_one_gpu_is_refused():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""
+
+
+def test_stored_traffic_profiles_have_what_the_bench_line_reads():
+    import glob
+    import json
+    files = sorted(glob.glob(os.path.join(ROOT, "profiles", "*_traffic.json")))
+    assert files, "the bench line's roofline.traffic comes from these"
+    for f in files:
+        t = json.load(open(f))
+        assert t["kernel"].startswith("reattach_rows"), f
+        ratio = t["hbm_bytes_per_launch"] / t["algorithmic_bytes_per_launch"]
+        assert 0.99 < ratio < 1.03 and abs(ratio - t["traffic_over_algorithmic"]) < 1e-9, (f, ratio)
+        assert 1.9 < t["fetch_scale"] < 2.1 and 0.99 < t["write_scale"] < 1.01, f     # the plain copy's yardstick
