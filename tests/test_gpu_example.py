@@ -1,0 +1,17 @@
+"""The package's example (an empty pool, one request admitted, a second one that finds the first
+one's chunks at shifted positions) runs and reports what it should."""
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+def test_example_serves_from_what_it_admitted():
+    assert torch.cuda.is_available(), "GPU tests need an MI355X; deselect with -m 'not gpu'"
+    from paper_2605_05696_amd import example
+    r = example.main()
+    chunks, hits, admitted = r["first"]
+    assert hits == 0 and admitted == chunks - 1            # the first chunk sits inside the carve-out
+    chunks2, hits2, hit_tokens = r["second"]
+    assert hits2 >= chunks2 - 3 and hit_tokens > 3000      # all but the chunks around the fresh head
+    assert r["delta"] < 0 and r["ckv_identical"]
