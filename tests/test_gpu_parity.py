@@ -321,6 +321,67 @@ def test_reattach_no_hits_and_bad_indices_are_skipped_and_flagged():
         s.close()
 
 
+def test_more_hits_than_the_list_holds_are_dropped_and_flagged():
+    """A hit count above the list's capacity (a caller's mistake, or a count another call left there):
+    the hits the list holds are re-attached, the flag says that some were dropped."""
+    L, rows = 2, 512
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, L, wl.inv_freq_plain(), 1024, 1, DEV)
+    try:
+        src = wl.kv_pool_torch(L, rows, 3, DEV)
+        dst = wl.sentinel_pool_torch(L, rows, DEV)
+        d_slots = torch.arange(rows, dtype=torch.int32, device=DEV)
+        hits = orc.Hits(np.array([0, 100, 200], np.uint32), np.array([300, 0, 100], np.uint32),
+                        np.array([40, 70, 17], np.uint32), np.array([5, -9, 0], np.int32))
+        d_hits, d_n = hits_to_dev(hits, 3)
+        d_n.fill_(7)                                                  # the list has room for three
+        B.irm_reattach(s.ctx, B.layer_pointers(src), ROW * 2, rows, B.layer_pointers(dst), ROW * 2, rows, d_slots,
+                       d_hits, d_n)
+        assert s.error_flags() == B.IRM_FLAG_CHUNK_OVERFLOW
+        want = np.full((L, rows, ROW), wl.SENTINEL_BF16, np.uint16)
+        orc.reattach(bits(src), want, np.arange(rows, dtype=np.int32), hits, wl.inv_freq_plain())
+        compare_rows(bits(dst), want, what="three of seven")
+    finally:
+        s.close()
+
+
+def test_chunk_records_outside_the_tokens_are_skipped_and_flagged():
+    """irm_chunk_hash: a record that runs past the token array gets fingerprint 0 and raises the flag, the
+    others are fingerprinted as usual.  irm_cdc_chunk: a request whose offsets run backwards or past the
+    token array yields no chunks and raises the flag, the request in front of it is chunked as usual."""
+    rng = np.random.default_rng(11)
+    tokens = rng.integers(0, 102400, 3000).astype(np.int32)
+    s = Session(wl.gear_table(), 0xFF, 64, 1024, 32, 1, wl.inv_freq_plain(), 4096, 2, DEV)
+    try:
+        d_tok = torch.from_numpy(tokens).to(DEV)
+        start = np.array([0, 500, 2900, 1000], np.uint32)
+        length = np.array([500, 300, 101, 64], np.uint32)             # record 2 ends one token past the array
+        d_hash = torch.full((4,), -1, dtype=torch.int64, device=DEV)
+        B.irm_chunk_hash(s.ctx, d_tok, s.to_dev_u32(start), s.to_dev_u32(length),
+                         torch.tensor([4], dtype=torch.int32, device=DEV), d_hash)
+        assert s.error_flags() == B.IRM_FLAG_BAD_CHUNK
+        got = d_hash.cpu().numpy().view(np.uint64)
+        ok = [0, 1, 3]
+        assert np.array_equal(got[ok], orc.chunk_hash(tokens, start[ok], length[ok])) and got[2] == 0
+        # chunking: the second request claims tokens the array does not have
+        for off in ([0, 1700, 3001], [2000, 1000]):
+            off = np.array(off, np.uint32)
+            buf = s.alloc_front(len(tokens), len(off) - 1)
+            B.irm_cdc_chunk(s.ctx, d_tok, s.to_dev_u32(off), buf["chunk_start"], buf["chunk_len"],
+                            buf["req_chunk_offsets"], buf["n_chunks"])
+            assert s.error_flags() == B.IRM_FLAG_BAD_CHUNK
+            n = int(buf["n_chunks"].item())
+            rco = buf["req_chunk_offsets"].cpu().numpy().view(np.uint32)
+            if len(off) == 3:
+                st, ln, _ = orc.cdc_chunk(tokens[:1700], [0, 1700], wl.gear_table(), 0xFF, 64, 1024)
+                assert n == len(st) and list(rco) == [0, n, n]
+                assert np.array_equal(buf["chunk_start"].cpu().numpy().view(np.uint32)[:n], st)
+                assert np.array_equal(buf["chunk_len"].cpu().numpy().view(np.uint32)[:n], ln)
+            else:
+                assert n == 0 and list(rco) == [0, 0]
+    finally:
+        s.close()
+
+
 # ------------------------------------------------- split pool (k_r only) --
 
 def run_kr_variant(w, hits, src, dense=False, pair_mode=0, knobs=()):
