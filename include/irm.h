@@ -178,7 +178,10 @@ irm_status irm_table_insert(irm_table *table, const uint64_t *d_hash, const irm_
  *   d_n_chunks         uint32[1] out
  * Needs n_tokens <= cfg.max_tokens, n_req <= cfg.max_requests and
  * chunk_capacity >= irm_chunk_capacity_bound(n_tokens, n_req, min_chunk)
- * (else IRM_ERR_CAPACITY). */
+ * (else IRM_ERR_CAPACITY).  The offsets are only seen on the device: a request whose
+ * offsets run backwards or past n_tokens yields no chunks and raises IRM_FLAG_BAD_CHUNK;
+ * the chunks of requests that overlap such a one are then unspecified (every access
+ * stays inside the arrays). */
 irm_status irm_cdc_chunk(irm_ctx *ctx, const int32_t *d_tokens, uint64_t n_tokens,
                          const uint32_t *d_req_offsets, uint32_t n_req, uint32_t *d_chunk_start,
                          uint32_t *d_chunk_len, uint32_t *d_req_chunk_offsets,
