@@ -16,6 +16,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libirm.so")
+CLIENT = os.path.join(HERE, "abi_client")                 # plain C99 caller of the library (csrc/abi_client.c)
+ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -65,7 +67,20 @@ def build(verbose: bool = False, incremental: bool = False) -> str:
     if verbose:
         print(" ".join(link), flush=True)
     subprocess.run(link, check=True, cwd=ROOT)
+    build_client(verbose)
     return LIB
+
+
+def build_client(verbose: bool = False) -> str:
+    """The C99 client: gcc, the public header, the HIP runtime's C API; finds libirm.so beside itself."""
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROCM, "include"),
+           "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "abi_client.c"), "-o", CLIENT,
+           "-L", HERE, "-lirm", "-L", os.path.join(ROCM, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(ROCM, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, cwd=ROOT)
+    return CLIENT
 
 
 if __name__ == "__main__":

@@ -15,3 +15,19 @@ def test_example_serves_from_what_it_admitted():
     chunks2, hits2, hit_tokens = r["second"]
     assert hits2 >= chunks2 - 3 and hit_tokens > 3000      # all but the chunks around the fresh head
     assert r["delta"] < 0 and r["ckv_identical"]
+
+
+def test_plain_c_client_of_the_library():
+    """csrc/abi_client.c, built by gcc as C99 against the public header, drives the four calls from C
+    and checks their results itself (a child process: no Python object crosses the boundary)."""
+    import os
+    import subprocess
+    from paper_2605_05696_amd import build
+    if not os.path.exists(build.CLIENT):                   # built with the library; a second of gcc if it is not there
+        try:
+            build.build_client()
+        except (OSError, subprocess.CalledProcessError) as e:
+            pytest.skip(f"no C client and no way to build it here: {e}")
+    r = subprocess.run([build.CLIENT], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert r.stdout.startswith("abi_client ok:"), r.stdout
