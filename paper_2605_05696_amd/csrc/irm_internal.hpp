@@ -41,7 +41,8 @@ struct irm_ctx {
     uint32_t kr_rows_per_lane; // knob 6: rows per lane of the k_r-only kernel (2, 4 or 8; tile = 32x that)
     uint32_t kr_layers_per_wg; // knob 7: layers a workgroup of the k_r-only kernel keeps its tile for (0 = by batch size)
     uint32_t att_spin_limit; // knob 8: polls a wave of the attention kernel spends in one wait before it gives up
-    uint32_t xcd_ranges;    // knob 3: 1 = each XCD serves a contiguous range of a layer's tiles
+    uint32_t xcd_ranges;    // knob 3: 2 = each XCD serves a contiguous eighth of the launch's (layer, tile) list,
+                            // 1 = of every layer's tiles, 0 = workgroup x serves tile x, 3 = 2 from 32 layers on, else 1
     uint32_t n_cu;
     // one device slab, carved up below
     void *slab;

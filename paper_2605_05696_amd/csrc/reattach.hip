@@ -7,7 +7,8 @@
 //                  fp32 angle would already cost half a bf16 ulp); the hits are cut
 //                  into tiles (16 rows of 1152 bytes, 32 rows of 656 bytes), the tile
 //                  list is written by all workgroups at once.
-//   reattach_rows  grid (tile slots, layers), one workgroup per tile and layer: a
+//   reattach_rows  one workgroup per tile and layer, every XCD on a contiguous eighth
+//                  of the launch's layer-major list of them: a
 //                  tile's source rows are one contiguous span; each of the 8 waves
 //                  moves 2 rows of c_KV with one 16-byte load and store per lane and
 //                  row (a row's 1024 c_KV bytes are exactly one wave-wide access),
@@ -315,46 +316,63 @@ __device__ __forceinline__ void reattach_tile(const char *__restrict__ sbase, ui
     }
 }
 
-// Grid (x, y) = (tile slots, layers): all tiles of layer 0 are dispatched first, then
-// layer 1, ...; a tile's address needs no division.  grid.x is a multiple of 8 and the
-// dispatcher deals workgroups round-robin to the 8 XCDs, so with `xcd_ranges` workgroup
-// x serves tile (x % 8) * ceil(n_tiles / 8) + x / 8: each XCD streams one contiguous
-// eighth of the layer's tile list.  Workgroups past the last tile leave at once.
+// Which tile and layer a workgroup serves.  The dispatcher deals workgroups round-robin to the 8
+// XCDs and every grid here is a multiple of 8 wide, so workgroup x runs on XCD x % 8.
+//   xcd_ranges 2  1-D grid over the launch's whole list of (layer, tile) items, layer-major: workgroup
+//                 x serves item (x % 8) * ceil(items / 8) + x / 8, so every XCD streams one contiguous
+//                 eighth of the launch, each in layers of its own (the host's choice for deep models:
+//                 3 to 5 % faster at 61 layers than an eighth of every layer each);
+//   xcd_ranges 1  grid (tile slots, layers): tile (x % 8) * ceil(tiles / 8) + x / 8 of layer blockIdx.y;
+//   xcd_ranges 0  grid (tile slots, layers): tile x of layer blockIdx.y.
+// Workgroups past the last item leave at once.  With fewer workgroups than items (a grid set by
+// the caller, or more ragged tiles than the grid has slots) a workgroup walks several items; the
+// record of the next one is requested before the current tile's rows, so that its latency hides
+// behind them.
 template <int WAVES, int RPW, bool NT_LD, bool NT_ST, bool F8>
 __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
     const void *const *__restrict__ src_ptrs, uint64_t src_stride, void *const *__restrict__ dst_ptrs,
     uint64_t dst_stride, uint64_t dst_rows, const int32_t *__restrict__ dst_slots,
     const irm_tile *__restrict__ tiles, const uint32_t *__restrict__ plan, const float2 *__restrict__ trig,
-    uint32_t xcd_ranges, uint32_t pair_mode, uint32_t *err)
+    uint32_t xcd_ranges, uint32_t n_layers, uint32_t pair_mode, uint32_t *err)
 {
     constexpr uint32_t TILE = WAVES * RPW, NQ = (TILE + 63) / 64;
     const bool il = pair_mode != 0;
     const uint32_t n_tiles = plan[0];
-    const uint32_t layer = blockIdx.y;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = irm_wave_id();
-    const uint32_t per_xcd = (n_tiles + 7) >> 3;
-    const char *const src_layer = (const char *)src_ptrs[layer];
-    char *const dbase = (char *)dst_ptrs[layer];
-    // With fewer workgroups than tiles (a grid set by the caller) a workgroup walks several
-    // tiles; the record of the next one is requested before the current tile's rows, so
-    // that its latency hides behind them.
+    const bool flat = xcd_ranges == 2;
+    const uint32_t n_items = flat ? n_tiles * n_layers : n_tiles;     // flat: the host keeps the product below 2^31
+    const uint32_t per_xcd = (n_items + 7) >> 3;
     const uint32_t limit = per_xcd * 8;
-    auto tile_of = [&](uint32_t x) { return xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x; };
-    uint32_t x = blockIdx.x;
+    auto locate = [&](uint32_t x, uint32_t &layer, uint32_t &ti) {
+        const uint32_t item = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
+        if (item >= n_items) return false;
+        layer = flat ? item / n_tiles : blockIdx.y;
+        ti = flat ? item - layer * n_tiles : item;
+        return true;
+    };
+    uint32_t x = blockIdx.x, layer = 0, ti = 0, cur_layer = 0;
     irm_tile cur = {0u, 0u, 0u, 0u};
-    if (x < limit && tile_of(x) < n_tiles) cur = tiles[tile_of(x)];
+    if (x < limit && locate(x, layer, ti)) {
+        cur = tiles[ti];
+        cur_layer = layer;
+    }
 #pragma nounroll
     while (x < limit) {
         const uint32_t xn = x + gridDim.x;
         irm_tile nxt = {0u, 0u, 0u, 0u};
-        if (xn < limit && tile_of(xn) < n_tiles) nxt = tiles[tile_of(xn)];
+        uint32_t nxt_layer = 0;
+        if (xn < limit && locate(xn, layer, ti)) {
+            nxt = tiles[ti];
+            nxt_layer = layer;
+        }
         const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(cur.src_row0);
         const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(cur.dst_tok0);
         const uint32_t n_rows = __builtin_amdgcn_readfirstlane(cur.n_rows);
         const uint32_t hit = __builtin_amdgcn_readfirstlane(cur.hit);
         if (n_rows != 0) {                              // 0: no tile behind this slot
-            const char *sbase = src_layer + (uint64_t)src_row0 * src_stride;
+            const char *sbase = (const char *)src_ptrs[cur_layer] + (uint64_t)src_row0 * src_stride;
+            char *const dbase = (char *)dst_ptrs[cur_layer];
             int32_t slot[NQ];                           // -1: row absent or its slot unusable
 #pragma unroll
             for (uint32_t q = 0; q < NQ; ++q) {
@@ -375,13 +393,14 @@ __global__ __launch_bounds__(WAVES * 64) void reattach_rows(
                                                                    n_rows, trig_hit, wave, lane, il);
         }
         cur = nxt;
+        cur_layer = nxt_layer;
         x = xn;
     }
 }
 
 typedef void (*rows_kernel_t)(const void *const *, uint64_t, void *const *, uint64_t, uint64_t,
                               const int32_t *, const irm_tile *, const uint32_t *, const float2 *, uint32_t,
-                              uint32_t, uint32_t *);
+                              uint32_t, uint32_t, uint32_t *);
 
 template <int WAVES, int RPW, bool F8>
 static rows_kernel_t pick_mode(uint32_t mode)
@@ -680,7 +699,7 @@ static irm_status reattach_check(uint32_t row_format, const void *const *d_src_l
 // n_slot_tokens rows can fill; workgroups without a tile leave on their first compare (their
 // number does not show in the launch time: 1,536 to 3,072 slots for 1,660 tiles per layer all
 // take 276-278 us on the 32 K-token configuration); the ragged last tiles of the hits, if they
-// overflow the grid, are taken by the first workgroups of the layer in a second pass.
+// overflow the grid, are taken by the first workgroups in a second pass.
 static void rows_enqueue(const rows_launch &k, const void *const *d_src_layer_ptrs, uint64_t src_row_stride_bytes,
                          void *const *d_dst_layer_ptrs, uint64_t dst_row_stride_bytes, uint64_t dst_rows,
                          const int32_t *d_dst_slots, uint64_t n_slot_tokens, hipStream_t s)
@@ -690,10 +709,18 @@ static void rows_enqueue(const rows_launch &k, const void *const *d_src_layer_pt
     if (k.grid) tile_slots = k.grid;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
     const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8);
-    hipLaunchKernelGGL(pick_kernel(k.waves, k.rows_per_wave, k.mem_mode, k.row_format), dim3(grid_x, k.n_layers),
-                       dim3(k.waves * 64), 0, s, d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs,
-                       dst_row_stride_bytes, dst_rows, d_dst_slots, k.d_tiles, k.d_plan, k.d_trig, k.xcd_ranges,
-                       k.pair_mode, k.d_err);
+    // One list over all layers pays with many layers (61 layers: 3 to 5 % faster in every run, 54: 2 %;
+    // 27 and fewer: from 4 % slower to 4 % faster between processes, 1 % slower on short requests), so
+    // the library takes it from 32 layers on, if every index into the list fits 31 bits; else an
+    // eighth of every layer per XCD.
+    const bool want_flat = k.xcd_ranges == 2 || (k.xcd_ranges == 3 && k.n_layers >= 32);
+    const bool flat = want_flat && ((uint64_t)k.tile_cap + 8) * k.n_layers < (1ull << 31) &&
+                      (uint64_t)grid_x * k.n_layers < (1ull << 31);
+    const uint32_t ranges = flat ? 2u : (k.xcd_ranges ? 1u : 0u);
+    hipLaunchKernelGGL(pick_kernel(k.waves, k.rows_per_wave, k.mem_mode, k.row_format),
+                       flat ? dim3(grid_x * k.n_layers) : dim3(grid_x, k.n_layers), dim3(k.waves * 64), 0, s,
+                       d_src_layer_ptrs, src_row_stride_bytes, d_dst_layer_ptrs, dst_row_stride_bytes, dst_rows,
+                       d_dst_slots, k.d_tiles, k.d_plan, k.d_trig, ranges, k.n_layers, k.pair_mode, k.d_err);
 }
 
 extern "C" irm_status irm_reattach(irm_ctx *ctx, const void *const *d_src_layer_ptrs,
@@ -795,7 +822,7 @@ extern "C" irm_status irm_reattach_static(const float *inv_freq, uint32_t n_laye
     uint32_t *plan = (uint32_t *)base;
     uint32_t *err = d_error_flags ? d_error_flags : (uint32_t *)base + 16;
     // fp8 rows share 128-byte lines with their neighbours: cached accesses (as in a context)
-    const rows_launch k = {8u, 2u, row_format == IRM_ROW_FP8 ? 0u : 3u, 1u, 0u, pair_mode, row_format, n_layers,
+    const rows_launch k = {8u, 2u, row_format == IRM_ROW_FP8 ? 0u : 3u, 3u, 0u, pair_mode, row_format, n_layers,
                            (float2 *)(base + IRM_STATIC_HEAD_BYTES + IRM_STATIC_TILES_BYTES),
                            (irm_tile *)(base + IRM_STATIC_HEAD_BYTES), IRM_STATIC_TILE_CAP, plan, err};
     hipLaunchKernelGGL(reattach_plan_byval, dim3((hit_capacity + 7) / 8), dim3(256), 0, s, d_hits, d_n_hits,

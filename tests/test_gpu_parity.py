@@ -263,17 +263,19 @@ def test_reattach_special_deltas_and_tile_tails():
         s.close()
 
 
-@pytest.mark.parametrize("waves,rpw,grid", [(8, 2, 0), (8, 2, 8), (8, 2, 64), (8, 4, 0), (4, 4, 16), (16, 2, 0),
-                                            (4, 8, 24), (16, 4, 8)])
+@pytest.mark.parametrize("waves,rpw,grid,ranges", [(8, 2, 0, 2), (8, 2, 8, 2), (8, 2, 64, 2), (8, 4, 0, 2), (4, 4, 16, 2),
+                                                   (16, 2, 0, 2), (4, 8, 24, 2), (16, 4, 8, 2), (8, 2, 0, 0), (8, 2, 0, 1),
+                                                   (8, 2, 8, 1), (8, 2, 64, 1), (16, 4, 8, 0)])
 @pytest.mark.parametrize("name,slots", [("c2", "permuted"), ("c4", "contiguous")])
-def test_reattach_launch_shapes(name, slots, waves, rpw, grid):
-    """Every launch shape of the row kernel writes the same rows: tile shapes, and grids smaller
-    than the tile count, where a workgroup walks several tiles.  All rows against the oracle; rows
-    no hit covers keep the sentinel."""
+def test_reattach_launch_shapes(name, slots, waves, rpw, grid, ranges):
+    """Every launch shape of the row kernel writes the same rows: tile shapes, grids smaller than
+    the tile count, where a workgroup walks several tiles, and every mapping of workgroups to tiles
+    (2: an eighth of the whole launch per XCD, the default; 1: an eighth of every layer; 0: tile x).
+    All rows against the oracle; rows no hit covers keep the sentinel."""
     w = small(name, slots=slots)
     rig = Rig(w)
     try:
-        for knob, value in ((4, 16), (1, rpw), (4, waves), (0, grid)):
+        for knob, value in ((4, 16), (1, rpw), (4, waves), (0, grid), (3, ranges)):
             B.irm_ctx_tune(rig.s.ctx, knob, value)
         hits = rig.o["hits"]
         d_hits, d_n = hits_to_dev(hits, rig.buf["cap"])
