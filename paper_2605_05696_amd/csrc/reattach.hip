@@ -480,15 +480,22 @@ __global__ __launch_bounds__(256) void reattach_kr_rows(
     // a wave-wide access covers eight whole 128-byte rows, contiguous when the rows are.
     // Vectors 0..3 are the first halves of the pairs, 4..7 their partners, four lanes on.
     const uint32_t n_tiles = plan[0];
-    const uint32_t l0 = blockIdx.y * lpw, l1 = l0 + lpw < n_layers ? l0 + lpw : n_layers;
     const uint32_t lane = threadIdx.x & 63, wave = irm_wave_id();
     const uint32_t v = lane & 7, jq = v & 3;
     const float sgn = v < 4 ? -1.0f : 1.0f;            // first half: a c - b s; partner: b c + a s
-    const uint32_t per_xcd = (n_tiles + 7) >> 3;       // as in reattach_rows
+    // which (tile, layer group) a workgroup serves: as in reattach_rows (xcd_ranges 2: a 1-D grid over the
+    // launch's whole list of them, group-major, one contiguous eighth per XCD)
+    const bool flat = xcd_ranges == 2;
+    const uint32_t n_groups = (n_layers + lpw - 1) / lpw;
+    const uint32_t n_items = flat ? n_tiles * n_groups : n_tiles;
+    const uint32_t per_xcd = (n_items + 7) >> 3;
 #pragma nounroll
     for (uint32_t x = blockIdx.x; x < per_xcd * 8; x += gridDim.x) {
-        const uint32_t ti = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
-        if (ti >= n_tiles) continue;
+        const uint32_t item = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
+        if (item >= n_items) continue;
+        const uint32_t group = flat ? item / n_tiles : blockIdx.y;
+        const uint32_t ti = flat ? item - group * n_tiles : item;
+        const uint32_t l0 = group * lpw, l1 = l0 + lpw < n_layers ? l0 + lpw : n_layers;
         const irm_tile *tp = tiles + ti;
         const uint32_t src_row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
         const uint32_t dst_tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
@@ -597,10 +604,15 @@ extern "C" irm_status irm_reattach_kr(irm_ctx *ctx, const void *const *d_src_kr_
                       uint32_t, uint32_t *) =
         ctx->kr_rows_per_lane == 2 ? reattach_kr_rows<2>
         : ctx->kr_rows_per_lane == 4 ? reattach_kr_rows<4> : reattach_kr_rows<8>;
-    hipLaunchKernelGGL(kr_kernel, dim3((uint32_t)((tile_slots + 7) / 8 * 8), (L + lpw - 1) / lpw), dim3(256), 0, s,
+    // as for the row kernel: from 32 layers on one list over all layer groups, an eighth of it per XCD
+    const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8), n_groups = (L + lpw - 1) / lpw;
+    const bool want_flat = ctx->xcd_ranges == 2 || (ctx->xcd_ranges == 3 && L >= 32);
+    const bool flat = want_flat && ((uint64_t)ctx->tile_cap + 8) * n_groups < (1ull << 31) &&
+                      (uint64_t)grid_x * n_groups < (1ull << 31);
+    hipLaunchKernelGGL(kr_kernel, flat ? dim3(grid_x * n_groups) : dim3(grid_x, n_groups), dim3(256), 0, s,
                        d_src_kr_layer_ptrs, src_kr_row_stride_bytes, d_kr_layer_ptrs, kr_row_stride_bytes,
                        kr_rows, d_dst_slots, ctx->d_tiles, ctx->d_plan, ctx->d_trig, d_ckv_index, L, lpw,
-                       ctx->cfg.pair_mode, ctx->xcd_ranges, ctx->d_err);
+                       ctx->cfg.pair_mode, flat ? 2u : (ctx->xcd_ranges ? 1u : 0u), ctx->d_err);
     if (sample) {
         IRM_HIP_TRY(hipEventRecord(ctx->prof_events[2 * ctx->prof_n + 1], s));
         ++ctx->prof_n;

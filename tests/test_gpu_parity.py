@@ -430,16 +430,18 @@ def test_reattach_kr_small_configs(name, slots, dense):
     assert np.all(got_kr[:, untouched] == wl.SENTINEL_BF16)
 
 
-@pytest.mark.parametrize("rows_per_lane,layers_per_wg", [(2, 1), (2, 2), (4, 3), (8, 1), (2, 0), (4, 5)])
+@pytest.mark.parametrize("rows_per_lane,layers_per_wg,ranges", [(2, 1, 3), (2, 2, 3), (4, 3, 3), (8, 1, 3), (2, 0, 3),
+                                                                (4, 5, 3), (2, 1, 2), (2, 2, 2), (4, 0, 2), (2, 2, 0)])
 @pytest.mark.parametrize("name,slots,pair_mode", [("c4", "permuted", 0), ("c1", "contiguous", 1)])
-def test_reattach_kr_launch_shapes(name, slots, pair_mode, rows_per_lane, layers_per_wg):
-    """Rows per lane and layers a workgroup keeps its tile for (c1 and c4 have three layers: one, two
-    with a remainder, all, more than there are): same rows."""
+def test_reattach_kr_launch_shapes(name, slots, pair_mode, rows_per_lane, layers_per_wg, ranges):
+    """Rows per lane, layers a workgroup keeps its tile for (c1 and c4 have three layers: one, two
+    with a remainder, all, more than there are) and which XCD serves which (tile, layer group)
+    (3: the library's choice, 2: an eighth of the whole launch, 0: round-robin): same rows."""
     w = small(name, slots=slots)
     hits = oracle_front(w)["hits"]
     src = wl.kv_pool_torch(w.n_layers, w.src_rows, wl.kv_seed(name), DEV)
     got_kr, got_idx = run_kr_variant(w, hits, src, pair_mode=pair_mode,
-                                     knobs=((6, rows_per_lane), (7, layers_per_wg)))
+                                     knobs=((6, rows_per_lane), (7, layers_per_wg), (3, ranges)))
     want_kr = np.full((w.n_layers, w.dst_rows, 64), wl.SENTINEL_BF16, np.uint16)
     want_idx = np.full(w.dst_rows, -1, np.int32)
     orc.reattach_kr(bits(src), want_kr, want_idx, w.dst_slots, hits, w.inv_freq, pair_mode)
