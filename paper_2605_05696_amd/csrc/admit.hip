@@ -136,18 +136,23 @@ __global__ __launch_bounds__(256) void admit_rows(const void *const *__restrict_
                                                   uint64_t pool_stride, const int32_t *__restrict__ slots,
                                                   const irm_tile *__restrict__ tiles,
                                                   const uint32_t *__restrict__ plan, uint32_t xcd_ranges,
-                                                  uint32_t *err)
+                                                  uint32_t n_layers, uint32_t *err)
 {
     __shared__ int32_t slot_s[ADMIT_TILE_ROWS];
     const uint32_t n_tiles = plan[0];
-    const uint32_t layer = blockIdx.y;
-    // grid.x is a multiple of 8 and workgroups go round-robin to the 8 XCDs: workgroup x serves tile
-    // (x % 8) * ceil(n_tiles / 8) + x / 8, so each XCD streams one contiguous eighth of the tile list
-    const uint32_t per_xcd = (n_tiles + 7) >> 3;
+    // The grid is a multiple of 8 wide and workgroups go round-robin to the 8 XCDs.  xcd_ranges 1: grid
+    // (tile slots, layers), workgroup x serves tile (x % 8) * ceil(n_tiles / 8) + x / 8 of layer
+    // blockIdx.y, so each XCD streams one contiguous eighth of the layer's tile list; 2: a 1-D grid
+    // over the layer-major list of all (layer, tile) items, an eighth of it per XCD; 0: tile x.
+    const bool flat = xcd_ranges == 2;
+    const uint32_t n_items = flat ? n_tiles * n_layers : n_tiles;      // flat: below 2^31 (the host checks)
+    const uint32_t per_xcd = (n_items + 7) >> 3;
 #pragma nounroll
     for (uint32_t x = blockIdx.x; x < per_xcd * 8; x += gridDim.x) {
-        const uint32_t ti = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
-        if (ti >= n_tiles) continue;                    // uniform
+        const uint32_t item = xcd_ranges ? (x & 7u) * per_xcd + (x >> 3) : x;
+        if (item >= n_items) continue;                  // uniform
+        const uint32_t layer = flat ? item / n_tiles : blockIdx.y;
+        const uint32_t ti = flat ? item - layer * n_tiles : item;
         const irm_tile *tp = tiles + ti;
         const uint32_t row0 = __builtin_amdgcn_readfirstlane(tp->src_row0);
         const uint32_t tok0 = __builtin_amdgcn_readfirstlane(tp->dst_tok0);
@@ -207,12 +212,18 @@ extern "C" irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *
                        d_admitted_row, ctx->d_slot_of, ctx->d_tiles, ctx->tile_cap, ctx->d_plan, ctx->d_plan + 3,
                        ctx->d_err);
     // measured: contiguous tile ranges per XCD gain 10 % on a batch of a million tokens, cost 5 % on one of 32 K
-    const uint32_t xcd_ranges = ctx->xcd_ranges && n_slot_tokens >= (1u << 18) ? 1u : 0u;
+    // from 32 layers on an eighth of the whole launch's list per XCD, as in the re-attach row kernel
+    const uint32_t L = ctx->cfg.n_layers;
     uint64_t tile_slots = n_slot_tokens / ADMIT_TILE_ROWS + chunk_capacity;
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
+    const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8);
+    const bool big = ctx->xcd_ranges && n_slot_tokens >= (1u << 18);
+    const bool flat = big && (ctx->xcd_ranges == 2 || (ctx->xcd_ranges == 3 && L >= 32)) &&
+                      ((uint64_t)ctx->tile_cap + 8) * L < (1ull << 31) && (uint64_t)grid_x * L < (1ull << 31);
     hipLaunchKernelGGL(ctx->cfg.row_format == IRM_ROW_FP8 ? admit_rows<IRM_F8_ROW_BYTES / 16> : admit_rows<IRM_ROW_BYTES / 16>,
-                       dim3((uint32_t)((tile_slots + 7) / 8 * 8), ctx->cfg.n_layers), dim3(256), 0, s,
+                       flat ? dim3(grid_x * L) : dim3(grid_x, L), dim3(256), 0, s,
                        d_req_layer_ptrs, req_row_stride_bytes, req_rows, d_pool_layer_ptrs,
-                       pool_row_stride_bytes, d_slots, ctx->d_tiles, ctx->d_plan, xcd_ranges, ctx->d_err);
+                       pool_row_stride_bytes, d_slots, ctx->d_tiles, ctx->d_plan, flat ? 2u : (big ? 1u : 0u), L,
+                       ctx->d_err);
     return irm_launch_status();
 }

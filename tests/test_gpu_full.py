@@ -203,16 +203,20 @@ def test_full_size_split_pool_variant_c1():
         rig.close()
 
 
-@pytest.mark.parametrize("name", ["c1", "c2"])
-def test_full_size_admit(name):
+@pytest.mark.parametrize("name,ranges", [("c1", 3), ("c2", 3), ("c2", 2)])
+def test_full_size_admit(name, ranges):
     """irm_admit on the misses of a full-size batch.  The oracle decides who is admitted and
     where (it sees layer 0 only, and the free tail of the pool as rows 0.. of its own array);
     layer 0 of the free tail is compared with it byte for byte, every other layer on the
-    device: admitted pool rows equal the request rows their tokens were prefilled into."""
+    device: admitted pool rows equal the request rows their tokens were prefilled into.
+    ``ranges`` 2: the copy (and the serve before it) with an eighth of the whole launch's tile
+    list per XCD, the mapping the library itself takes from 32 layers on."""
+    from paper_2605_05696_amd import binding as B
     from tests.gpu_util import ROW
     w = wl.make_workload(name, orc.cdc_chunk, size="full")
     rig = Rig(w)
     try:
+        B.irm_ctx_tune(rig.s.ctx, 3, ranges)
         o, L = rig.o, w.n_layers
         n_chunks = len(o["start"])
         miss_tokens = int(o["len"][o["entry"] < 0].sum())
