@@ -79,6 +79,7 @@ def test_random_case_every_stage(seed):
     s = Session(c["gear"], c["mask"], c["lo"], c["hi"], c["carve"], L, c["inv"], max(n_tok, len(lib)), n_req, DEV,
                 pair_mode=c["pair_mode"])
     try:
+        B.irm_ctx_tune(s.ctx, 3, seed % 4)                                 # every mapping of workgroups to tiles
         g_pst, g_pln, _, g_ph = s.chunk_host(lib, np.array([0, len(lib)], np.uint32))
         assert np.array_equal(g_pst, pst) and np.array_equal(g_pln, pln) and np.array_equal(g_ph, reg["hash"])
         s.build_table(int((len(pst) + len(st)) / 0.6) + 4, reg)            # room for what the miss path adds
