@@ -21,8 +21,8 @@ extern "C" {
  * knob 2: bit 0 = non-temporal loads, bit 1 = non-temporal stores
  * knob 3: which tiles an XCD serves in the row kernel: 2 = one contiguous eighth of the launch's whole
  *         (layer, tile) list, 1 = an eighth of every layer's tiles, 0 = tile x to workgroup x
- *         (round-robin), 3 = the library's choice (default: 2 from 32 layers on, else 1); the k_r-only
- *         kernel and the miss path's copy take 1 for any value above 0
+ *         (round-robin), 3 = the library's choice (default: 2 from 32 layers on over bf16 rows, else 1);
+ *         the k_r-only kernel and the miss path's copy follow the same values over their own lists
  * knob 4: waves per workgroup (1, 2, 4, 8 or 16; fp8 rows: 4 or more); a tile is
  *         waves x rows-per-wave rows, at least 4
  * knob 5: 1 = irm_cdc_chunk always selects cuts with the serial walk (else only for

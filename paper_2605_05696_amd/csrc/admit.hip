@@ -218,7 +218,7 @@ extern "C" irm_status irm_admit(irm_ctx *ctx, irm_table *table, const uint64_t *
     if (tile_slots > (1u << 24)) tile_slots = 1u << 24;
     const uint32_t grid_x = (uint32_t)((tile_slots + 7) / 8 * 8);
     const bool big = ctx->xcd_ranges && n_slot_tokens >= (1u << 18);
-    const bool flat = big && (ctx->xcd_ranges == 2 || (ctx->xcd_ranges == 3 && L >= 32)) &&
+    const bool flat = big && (ctx->xcd_ranges == 2 || (ctx->xcd_ranges == 3 && L >= 32 && ctx->cfg.row_format == IRM_ROW_BF16)) &&
                       ((uint64_t)ctx->tile_cap + 8) * L < (1ull << 31) && (uint64_t)grid_x * L < (1ull << 31);
     hipLaunchKernelGGL(ctx->cfg.row_format == IRM_ROW_FP8 ? admit_rows<IRM_F8_ROW_BYTES / 16> : admit_rows<IRM_ROW_BYTES / 16>,
                        flat ? dim3(grid_x * L) : dim3(grid_x, L), dim3(256), 0, s,
