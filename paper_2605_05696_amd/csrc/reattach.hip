@@ -725,7 +725,7 @@ static void rows_enqueue(const rows_launch &k, const void *const *d_src_layer_pt
     // 27 and fewer: from 4 % slower to 4 % faster between processes, 1 % slower on short requests), so
     // the library takes it from 32 layers on, if every index into the list fits 31 bits; else an
     // eighth of every layer per XCD.
-    // (bf16 rows; over fp8 rows the per-layer eighths stay ahead at 61 layers too, 0.74 against 0.72)
+    // (bf16 rows; over fp8 rows the per-layer eighths stay ahead at 61 layers too, 0.74-0.75 against 0.68-0.74)
     const bool want_flat = k.xcd_ranges == 2 || (k.xcd_ranges == 3 && k.n_layers >= 32 && k.row_format == IRM_ROW_BF16);
     const bool flat = want_flat && ((uint64_t)k.tile_cap + 8) * k.n_layers < (1ull << 31) &&
                       (uint64_t)grid_x * k.n_layers < (1ull << 31);
